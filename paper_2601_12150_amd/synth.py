@@ -1,0 +1,160 @@
+"""Seeded synthetic inputs shaped like the paper's high-resolution tiles.
+
+This module serves both the CPU oracle's tests and the HIP path's tests and
+benchmark.  It contains input generation only -- none of the method's
+arithmetic (no attention, no scores, no selection) -- and imports neither side.
+
+The paper evaluates on pathology tiles (PANDA, SegPath) run through a trained
+backbone; neither is available here, so these generators stand in for them with
+the same shapes (patch grids 28^2 ... 256^2 plus one CLS token, 16 heads of 64
+channels) and the same structure: smooth spatial correlation and large
+"background" regions whose tokens pruning should remove (paper, "Time-Efficiency
+Optimization" and the qualitative pruning figure).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import numpy as np
+
+
+@dataclass(frozen=True)
+class Config:
+    name: str
+    batch: int
+    heads: int
+    head_dim: int
+    grid: int
+    block: int
+    dtype: str          # "f32" | "bf16"
+    keep_pct: int       # percentage of patch tokens kept by the filter
+    kind: str           # "iid" | "grf" | "background"
+    background: float = 0.0
+    seed: int = 0
+
+    @property
+    def n_patches(self) -> int:
+        return self.grid * self.grid
+
+    @property
+    def tokens(self) -> int:
+        return 1 + self.n_patches
+
+    @property
+    def k(self) -> int:
+        # ceil(keep * N) in integer arithmetic
+        return (self.n_patches * self.keep_pct + 99) // 100
+
+    @property
+    def scale(self) -> float:
+        return 1.0 / float(np.sqrt(self.head_dim))
+
+
+CONFIGS = {
+    1: Config("cfg1_g28_b7_f32", 1, 16, 64, 28, 7, "f32", 50, "iid", seed=0),
+    2: Config("cfg2_g64_b8_bf16", 4, 16, 64, 64, 8, "bf16", 60, "grf", seed=2),
+    3: Config("cfg3_g128_b8_bf16", 2, 16, 64, 128, 8, "bf16", 60, "background", 0.40, seed=3),
+    4: Config("cfg4_g256_b16_bf16", 1, 16, 64, 256, 16, "bf16", 40, "background", 0.55, seed=4),
+}
+
+
+def round_to_bf16(x: np.ndarray) -> np.ndarray:
+    """Round float32 values to the nearest bfloat16 (ties to even); result stays float32."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    r = (u + np.uint32(0x7FFF) + lsb) & np.uint32(0xFFFF0000)
+    return r.view(np.float32)
+
+
+def bf16_bits(x: np.ndarray) -> np.ndarray:
+    """uint16 bit patterns of float32 values that are already bfloat16-representable."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    assert not np.any(u & np.uint32(0xFFFF)), "values are not bf16-representable"
+    return (u >> np.uint32(16)).astype(np.uint16)
+
+
+def _rng(seed: int, stream: int) -> np.random.Generator:
+    # counter-based generator: (seed, stream) -> independent reproducible stream
+    return np.random.Generator(np.random.Philox(key=[np.uint64(seed), np.uint64(stream)]))
+
+
+def _finish(x: np.ndarray, dtype: str) -> np.ndarray:
+    x = x.astype(np.float32)
+    return round_to_bf16(x) if dtype == "bf16" else x
+
+
+def background_mask(grid: int, fraction: float, seed: int, batch: int,
+                    side_lo: int = 8, side_hi: int = 48) -> np.ndarray:
+    """[batch, grid, grid] bool: union of seeded axis-aligned rectangles, coverage >= fraction."""
+    g = _rng(seed, 1000)
+    out = np.zeros((batch, grid, grid), dtype=bool)
+    for b in range(batch):
+        m = out[b]
+        while m.mean() < fraction:
+            h = int(g.integers(side_lo, side_hi + 1))
+            w = int(g.integers(side_lo, side_hi + 1))
+            h, w = min(h, grid), min(w, grid)
+            r0 = int(g.integers(0, grid - h + 1))
+            c0 = int(g.integers(0, grid - w + 1))
+            m[r0:r0 + h, c0:c0 + w] = True
+    return out
+
+
+def _gaussian_field(rng: np.random.Generator, lead_shape, grid: int, sigma: float) -> np.ndarray:
+    """Unit-variance smooth random fields on the grid: white noise * Gaussian kernel (wrap)."""
+    from scipy.ndimage import gaussian_filter
+    w = rng.standard_normal(lead_shape + (grid, grid), dtype=np.float32)
+    sig = (0,) * len(lead_shape) + (sigma, sigma)
+    f = gaussian_filter(w, sigma=sig, mode="wrap")
+    f /= f.std(axis=(-2, -1), keepdims=True)
+    return f
+
+
+def make_qkv(cfg: Config):
+    """q, k, v float32 arrays [B,H,T,D] whose values are exactly representable in cfg.dtype.
+
+    Also returns `info` (background mask etc.) for diagnostics."""
+    B, H, D, g, T = cfg.batch, cfg.heads, cfg.head_dim, cfg.grid, cfg.tokens
+    info = {}
+    tensors = []
+    bg = None
+    if cfg.kind == "background":
+        bg = background_mask(g, cfg.background, cfg.seed, B)
+        info["background"] = bg
+        info["background_fraction"] = float(bg.mean())
+    for ti, name in enumerate("qkv"):
+        rng = _rng(cfg.seed, ti)
+        x = rng.standard_normal((B, H, T, D), dtype=np.float32)
+        if cfg.kind == "grf":
+            # one smooth field per (tensor, batch, head, channel), length scale 4 patches;
+            # the CLS row stays plain N(0,1)
+            f = _gaussian_field(_rng(cfg.seed, 10 + ti), (B, H, D), g, 4.0)
+            x[:, :, 1:, :] += 0.5 * f.reshape(B, H, D, g * g).transpose(0, 1, 3, 2)
+        elif cfg.kind == "background" and name in "kv":
+            shared = _rng(cfg.seed, 20 + ti).standard_normal((B, H, 1, D), dtype=np.float32)
+            noise = _rng(cfg.seed, 30 + ti).standard_normal((B, H, g * g, D), dtype=np.float32)
+            flat = bg.reshape(B, 1, g * g, 1)
+            patch = x[:, :, 1:, :]
+            x[:, :, 1:, :] = np.where(flat, shared + np.float32(0.01) * noise, patch)
+        tensors.append(_finish(x, cfg.dtype))
+    return tensors[0], tensors[1], tensors[2], info
+
+
+def make_tokens(cfg: Config, channels: int = 1024) -> np.ndarray:
+    """Token-major activations x [B,T,channels] for the compaction step (values in cfg.dtype)."""
+    x = _rng(cfg.seed, 50).standard_normal((cfg.batch, cfg.tokens, channels), dtype=np.float32)
+    return _finish(x, cfg.dtype)
+
+
+def small_case(seed: int, B: int, H: int, D: int, grid_h: int, grid_w: int, dtype: str = "f32",
+               n_global: int = 1):
+    """iid N(0,1) q, k, v [B,H,G+grid_h*grid_w,D] for unit tests."""
+    T = n_global + grid_h * grid_w
+    return tuple(_finish(_rng(seed, i).standard_normal((B, H, T, D), dtype=np.float32), dtype)
+                 for i in range(3))
+
+
+def raster_coords(grid_h: int, grid_w: int) -> np.ndarray:
+    """Packed (r << 16 | c) of every patch of the full grid, raster order: [grid_h*grid_w] int32."""
+    r, c = np.divmod(np.arange(grid_h * grid_w, dtype=np.int64), grid_w)
+    return ((r << 16) | c).astype(np.int32)
