@@ -1,0 +1,202 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X: one "step" = ns_attn_forward (with the CLS
+by-products) -> cls_scores_from_logits -> topk_filter (select + gather) on one batch of the
+128x128-grid workload (B=2, 16 heads x 64, 8x8 blocks, bf16, keep 60 %).
+
+Prints ONE JSON line.  `value` is tokens/s of the whole step with inputs resident in HBM;
+`roofline` prices the dominant kernel (patch-query attention) against the bf16 MFMA peak,
+counting only the FLOPs of the sparse pattern (4*D per allowed query-key pair);
+`cpu_baseline` is the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_MFMA = 2.5e15     # MI355X published dense bf16 MFMA peak, FLOP/s
+PEAK_HBM = 8.0e12           # MI355X published HBM3E bandwidth, B/s
+
+
+def sparse_pairs(grid: int, block: int):
+    """Allowed (query, key) pairs per head-image: patch rows (a2) and the CLS row (a3)."""
+    nb = grid // block
+    n = grid * grid
+    span = 3 * nb - 2 if nb > 1 else 1
+    patch_rows = span * span * block ** 4 + n      # neighbourhood pairs + patch->CLS
+    cls_row = n + 1
+    return patch_rows, cls_row
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=3, help="workload: 2, 3 (headline) or 4")
+    ap.add_argument("--sets", type=int, default=3,
+                    help="input sets rotated between steps so that no step finds its inputs in the 256 MB "
+                         "Infinity Cache (1 = warm-cache run)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target duration of the oracle sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2601_12150_amd import binding as nb
+    from paper_2601_12150_amd import synth
+
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.config]
+    B, H, T, D, g, blk, k = cfg.batch, cfg.heads, cfg.tokens, cfg.head_dim, cfg.grid, cfg.block, cfg.k
+    C = H * D
+    q, kk, v, info = synth.make_qkv(cfg)
+    x_host = synth.make_tokens(cfg, C)
+
+    def dev(a):
+        return torch.from_numpy(a).to(torch.bfloat16 if cfg.dtype == "bf16" else torch.float32).cuda()
+
+    # input sets: set 0 holds the workload itself, the others the same tensors again so every
+    # step does identical work on memory that has been evicted from the last-level cache
+    sets = []
+    for i in range(max(1, args.sets)):
+        s = {"q": dev(q), "k": dev(kk), "v": dev(v), "x": dev(x_host)}
+        s["out"] = torch.empty_like(s["q"])
+        s["logits"] = torch.empty((B, H, T), dtype=torch.float32, device="cuda")
+        s["lse"] = torch.empty((B, H), dtype=torch.float32, device="cuda")
+        s["scores"] = torch.empty((B, T - 1), dtype=torch.float32, device="cuda")
+        s["kept"] = torch.empty((B, k), dtype=torch.int32, device="cuda")
+        s["y"] = torch.empty((B, 1 + k, C), dtype=s["x"].dtype, device="cuda")
+        sets.append(s)
+    import ctypes
+    desc0 = nb.make_desc(sets[0]["q"], g, g, blk, cfg.scale, sets[0]["out"])
+    ws = torch.empty(max(1, nb.lib.ns_attn_workspace_bytes(ctypes.byref(desc0))), dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step(s):
+        # every stage runs in the HIP library; the binding only marshals pointers
+        lib, by, vp = nb.lib, ctypes.byref, ctypes.c_void_p
+        d = nb.make_desc(s["q"], g, g, blk, cfg.scale, s["out"])
+        st = vp(stream.cuda_stream)
+        nb._check(lib.ns_attn_forward(by(d), vp(s["q"].data_ptr()), vp(s["k"].data_ptr()), vp(s["v"].data_ptr()),
+                                      vp(s["out"].data_ptr()), vp(s["logits"].data_ptr()), vp(s["lse"].data_ptr()),
+                                      vp(ws.data_ptr()), ws.numel(), st))
+        nb._check(lib.cls_scores_from_logits(B, H, T, 1, vp(s["logits"].data_ptr()), vp(s["lse"].data_ptr()),
+                                             vp(s["scores"].data_ptr()), st))
+        nb._check(lib.topk_filter(B, T - 1, k, vp(s["scores"].data_ptr()), vp(s["x"].data_ptr()), C,
+                                  nb.NS_BF16 if cfg.dtype == "bf16" else nb.NS_F32, None,
+                                  vp(s["kept"].data_ptr()), vp(s["y"].data_ptr()), None, None, 0, st))
+
+    for i in range(args.warmup):
+        step(sets[i % len(sets)])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(sets[i % len(sets)])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    tokens_per_s = B * T * args.steps / dt
+
+    # ---- dominant kernel, timed alone with HIP events on its launch stream -------------
+    reps = 30
+    kern_ms = []
+    for i in range(len(sets)):
+        s = sets[i]
+        kern_ms.append(nb.ns_attn_patch_kernel_time(s["q"], s["k"], s["v"], g, g, blk, cfg.scale, out=s["out"],
+                                                    reps=1, workspace=ws))
+    # cold-ish: one launch per set in rotation; warm: back-to-back launches on one set
+    cold = []
+    for r in range(reps):
+        s = sets[r % len(sets)]
+        cold.append(nb.ns_attn_patch_kernel_time(s["q"], s["k"], s["v"], g, g, blk, cfg.scale, out=s["out"],
+                                                 reps=1, workspace=ws))
+    warm_ms = nb.ns_attn_patch_kernel_time(sets[0]["q"], sets[0]["k"], sets[0]["v"], g, g, blk, cfg.scale,
+                                           out=sets[0]["out"], reps=reps, workspace=ws)
+    kernel_ms = float(np.mean(cold))
+    patch_pairs, cls_pairs = sparse_pairs(g, blk)
+    flops_kernel = 4.0 * D * patch_pairs * H * B          # QK^T + PV of the patch rows
+    flops_layer = 4.0 * D * (patch_pairs + cls_pairs) * H * B
+    achieved = flops_kernel / (kernel_ms * 1e-3)
+    roofline = {"bound": "mfma", "kernel": "attn_mfma_kernel", "achieved": achieved / 1e12,
+                "peak": PEAK_BF16_MFMA / 1e12, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_MFMA,
+                "traffic": None, "kernel_ms": kernel_ms, "kernel_ms_warm_cache": warm_ms,
+                "flops_per_launch": flops_kernel,
+                "min_hbm_bytes_per_launch": 4.0 * B * H * T * D * (2 if cfg.dtype == "bf16" else 4)}
+
+    # ---- the bandwidth-bound stages, each timed alone (extra information) ---------------
+    def time_call(fn, n=20):
+        fn(sets[0]); torch.cuda.synchronize()
+        t = time.perf_counter()
+        for i in range(n):
+            fn(sets[i % len(sets)])
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / n
+
+    ws2 = torch.empty(nb.lib.cls_scores_workspace_bytes(ctypes.byref(desc0)), dtype=torch.uint8, device="cuda")
+    elt = 2 if cfg.dtype == "bf16" else 4
+    t_scores = time_call(lambda s: nb.cls_scores(s["q"], s["k"], cfg.scale, scores=s["scores"], workspace=ws2))
+    t_filter = time_call(lambda s: nb.topk_filter(s["scores"], k, x=s["x"], kept_idx=s["kept"], y=s["y"]))
+    t_select = time_call(lambda s: nb.topk_filter(s["scores"], k, kept_idx=s["kept"]))
+    t_attn = time_call(lambda s: nb.ns_attn_forward(s["q"], s["k"], s["v"], g, g, blk, cfg.scale, out=s["out"],
+                                                    workspace=ws))
+    bytes_scores = B * H * T * D * elt + B * H * T * 4 * 2 + B * (T - 1) * 4
+    bytes_gather = 2 * B * (1 + k) * C * elt + B * k * 4
+    stages = {
+        "ns_attn_forward_ms": t_attn * 1e3,
+        "ns_attn_forward_tflops_sparse": flops_layer / t_attn / 1e12,
+        "cls_scores_standalone_ms": t_scores * 1e3,
+        "cls_scores_standalone_GBps": bytes_scores / t_scores / 1e9,
+        "topk_select_ms": t_select * 1e3,
+        "gather_ms": max(t_filter - t_select, 0.0) * 1e3,
+        "gather_GBps": bytes_gather / max(t_filter - t_select, 1e-9) / 1e9,
+        "hbm_peak_GBps": PEAK_HBM / 1e9,
+    }
+
+    # ---- CPU oracle on a bounded sample of the same workload --------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        rng = np.random.default_rng(0)
+        probe = np.sort(rng.choice(np.arange(1, T), size=64, replace=False)).astype(np.int32)
+        t = time.perf_counter()
+        oracle.ns_attn(q, kk, v, g, g, blk, cfg.scale, rows=probe)
+        per_row = (time.perf_counter() - t) / len(probe)
+        n_rows = int(min(T - 1, max(64, args.cpu_seconds / per_row)))
+        rows = np.sort(rng.choice(np.arange(1, T), size=n_rows, replace=False)).astype(np.int32)
+        t = time.perf_counter()
+        oracle.ns_attn(q, kk, v, g, g, blk, cfg.scale, rows=rows)
+        sc = oracle.cls_scores(q, kk, cfg.scale)
+        oracle.topk(sc.astype(np.float32), k)
+        t_cpu = time.perf_counter() - t
+        cpu = {"value": B * n_rows / t_cpu, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": "%d of %d query tokens per image (all %d heads, %d images) through the attention oracle, "
+                         "plus full scoring and top-k; %.1f s" % (n_rows, T, H, B, t_cpu)}
+
+    out = {"metric": "sparse_attn_layer_tokens_per_s", "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+           "config": {"workload": "%s: B=%d, %dx%d patch grid + CLS (T=%d), %d heads x %d, %dx%d blocks, 3x3 "
+                                  "neighbourhood, keep %d%% (k=%d)" % (cfg.name, B, g, g, T, H, D, blk, blk,
+                                                                        cfg.keep_pct, k),
+                      "step": "ns_attn_forward + cls_scores_from_logits + topk_filter(select+gather)",
+                      "input_sets_rotated": len(sets),
+                      "background_fraction": info.get("background_fraction")},
+           "roofline": roofline, "cpu_baseline": cpu, "stages": stages}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,246 @@
+"""ctypes binding of libnsattn.so: argument marshalling only.
+
+Every function here has the name of the C entry point it calls (include/nsattn.h) and does
+nothing but turn torch tensors into device pointers, strides and sizes; all computation runs
+in the HIP kernels.  PyTorch supplies device memory and the current stream.  There is no
+fallback: if the library has not been built, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libnsattn.so")
+
+NS_OK, NS_ERR_INVALID_ARG, NS_ERR_UNSUPPORTED, NS_ERR_WORKSPACE, NS_ERR_HIP = range(5)
+NS_F32, NS_BF16 = 0, 1
+
+EXPORTS = ["ns_attn_workspace_bytes", "ns_attn_forward", "cls_scores_workspace_bytes", "cls_scores",
+           "cls_scores_from_logits", "topk_filter_workspace_bytes", "topk_filter",
+           "vit_block_workspace_bytes", "vit_block_forward", "ns_attn_patch_kernel_time", "ns_last_error",
+           "ns_version"]
+
+
+class NsError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__("libnsattn error %d: %s" % (code, message))
+        self.code = code
+
+
+class ns_attn_desc(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("grid_h", ctypes.c_int32), ("grid_w", ctypes.c_int32), ("block", ctypes.c_int32),
+                ("radius", ctypes.c_int32), ("n_global", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("tokens", ctypes.c_int32), ("scale", ctypes.c_float),
+                ("q_stride_b", ctypes.c_int64), ("q_stride_h", ctypes.c_int64),
+                ("q_stride_t", ctypes.c_int64), ("out_stride_b", ctypes.c_int64),
+                ("out_stride_h", ctypes.c_int64), ("out_stride_t", ctypes.c_int64),
+                ("coords", ctypes.c_void_p)]
+
+
+class ns_vit_block_desc(ctypes.Structure):
+    _fields_ = [("attn", ns_attn_desc), ("dim", ctypes.c_int32), ("mlp_dim", ctypes.c_int32),
+                ("ln_eps", ctypes.c_float)]
+
+
+class ns_vit_block_weights(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in
+                ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_proj", "b_proj", "ln2_g", "ln2_b",
+                 "w_fc1", "b_fc1", "w_fc2", "b_fc2")]
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            "%s is missing: build it with `python -m paper_2601_12150_amd.build` "
+            "(there is no CPU or PyTorch fallback)" % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, sz, i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32
+    dp = ctypes.POINTER(ns_attn_desc)
+    lib.ns_attn_workspace_bytes.restype = sz
+    lib.ns_attn_workspace_bytes.argtypes = [dp]
+    lib.ns_attn_forward.restype = ctypes.c_int
+    lib.ns_attn_forward.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.ns_attn_patch_kernel_time.restype = ctypes.c_int
+    lib.ns_attn_patch_kernel_time.argtypes = [dp, vp, vp, vp, vp, vp, sz, i32,
+                                              ctypes.POINTER(ctypes.c_float), vp]
+    lib.cls_scores_workspace_bytes.restype = sz
+    lib.cls_scores_workspace_bytes.argtypes = [dp]
+    lib.cls_scores.restype = ctypes.c_int
+    lib.cls_scores.argtypes = [dp, vp, vp, vp, vp, sz, vp]
+    lib.cls_scores_from_logits.restype = ctypes.c_int
+    lib.cls_scores_from_logits.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp]
+    lib.topk_filter_workspace_bytes.restype = sz
+    lib.topk_filter_workspace_bytes.argtypes = [i32, i32, i32]
+    lib.topk_filter.restype = ctypes.c_int
+    lib.topk_filter.argtypes = [i32, i32, i32, vp, vp, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.vit_block_workspace_bytes.restype = sz
+    lib.vit_block_workspace_bytes.argtypes = [ctypes.POINTER(ns_vit_block_desc)]
+    lib.vit_block_forward.restype = ctypes.c_int
+    lib.vit_block_forward.argtypes = [ctypes.POINTER(ns_vit_block_desc),
+                                      ctypes.POINTER(ns_vit_block_weights), vp, vp, vp, vp, sz, vp]
+    lib.ns_last_error.restype = ctypes.c_char_p
+    lib.ns_version.restype = ctypes.c_char_p
+    return lib
+
+
+lib = _load()
+
+
+def _check(code: int) -> None:
+    if code != NS_OK:
+        raise NsError(code, lib.ns_last_error().decode())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return NS_F32
+    if t.dtype == torch.bfloat16:
+        return NS_BF16
+    raise TypeError("only float32 and bfloat16 tensors are supported, got %s" % t.dtype)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _workspace(nbytes: int, device, workspace: Optional[torch.Tensor]) -> Optional[torch.Tensor]:
+    if nbytes == 0:
+        return workspace
+    if workspace is None:
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    return workspace
+
+
+def make_desc(q: torch.Tensor, grid_h: int, grid_w: int, block: int, scale: Optional[float] = None,
+              out: Optional[torch.Tensor] = None, coords: Optional[torch.Tensor] = None,
+              radius: int = 1, n_global: int = 1) -> ns_attn_desc:
+    """Descriptor for q (and k, v with the same strides) of shape [B,H,T,D]."""
+    B, H, T, D = q.shape
+    if q.stride(3) != 1:
+        raise ValueError("head_dim must be contiguous")
+    d = ns_attn_desc()
+    d.batch, d.heads, d.head_dim = B, H, D
+    d.grid_h, d.grid_w, d.block, d.radius, d.n_global = grid_h, grid_w, block, radius, n_global
+    d.dtype = _dtype_code(q)
+    d.tokens = T
+    d.scale = float(D) ** -0.5 if scale is None else float(scale)
+    d.q_stride_b, d.q_stride_h, d.q_stride_t = q.stride(0), q.stride(1), q.stride(2)
+    if out is not None:
+        d.out_stride_b, d.out_stride_h, d.out_stride_t = out.stride(0), out.stride(1), out.stride(2)
+    d.coords = None if coords is None else coords.data_ptr()
+    return d
+
+
+def ns_attn_forward(q, k, v, grid_h, grid_w, block, scale=None, coords=None, out=None,
+                    want_cls=False, workspace=None, stream=None, radius=1, n_global=1):
+    """Neighbourhood-sparse attention.  q, k, v: [B,H,T,D] device tensors with equal strides.
+
+    Returns out [B,H,T,D] (allocated contiguous unless given) and, with want_cls, also the
+    global query's logits [B,H,T] and log-sum-exp [B,H] (both fp32)."""
+    if not (q.shape == k.shape == v.shape and q.stride() == k.stride() == v.stride()):
+        raise ValueError("q, k, v must have the same shape and strides")
+    if not (q.dtype == k.dtype == v.dtype):
+        raise ValueError("q, k, v must have the same dtype")
+    B, H, T, D = q.shape
+    if out is None:
+        out = torch.empty((B, H, T, D), dtype=q.dtype, device=q.device)
+    if coords is not None and (coords.dtype != torch.int32 or not coords.is_contiguous()):
+        raise ValueError("coords must be a contiguous int32 tensor [B, T - n_global]")
+    desc = make_desc(q, grid_h, grid_w, block, scale, out, coords, radius, n_global)
+    logits = lse = None
+    if want_cls:
+        logits = torch.empty((B, H, T), dtype=torch.float32, device=q.device)
+        lse = torch.empty((B, H), dtype=torch.float32, device=q.device)
+    nbytes = lib.ns_attn_workspace_bytes(ctypes.byref(desc))
+    ws = _workspace(nbytes, q.device, workspace)
+    _check(lib.ns_attn_forward(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(logits),
+                               _ptr(lse), _ptr(ws), 0 if ws is None else ws.numel(), _stream(stream)))
+    return (out, logits, lse) if want_cls else out
+
+
+def ns_attn_patch_kernel_time(q, k, v, grid_h, grid_w, block, scale=None, coords=None, out=None,
+                              reps=10, workspace=None, stream=None) -> float:
+    """Average duration in ms of one launch of the patch-query attention kernel (HIP events
+    on the launch stream; this call waits for the GPU)."""
+    B, H, T, D = q.shape
+    if out is None:
+        out = torch.empty((B, H, T, D), dtype=q.dtype, device=q.device)
+    desc = make_desc(q, grid_h, grid_w, block, scale, out, coords)
+    nbytes = lib.ns_attn_workspace_bytes(ctypes.byref(desc))
+    ws = _workspace(nbytes, q.device, workspace)
+    ms = ctypes.c_float(0.0)
+    _check(lib.ns_attn_patch_kernel_time(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(ws),
+                                         0 if ws is None else ws.numel(), int(reps), ctypes.byref(ms),
+                                         _stream(stream)))
+    return float(ms.value)
+
+
+def cls_scores(q, k, scale=None, n_global=1, scores=None, workspace=None, stream=None):
+    """Head-averaged softmax weight of the global query on every patch key: [B, T-G] fp32."""
+    if not (q.shape == k.shape and q.stride() == k.stride() and q.dtype == k.dtype):
+        raise ValueError("q and k must have the same shape, strides and dtype")
+    B, H, T, D = q.shape
+    # the grid fields are not used by scoring; a 1 x (T-G) grid keeps the descriptor valid
+    desc = make_desc(q, 1, T - n_global, 1, scale, None, None, 1, n_global)
+    if scores is None:
+        scores = torch.empty((B, T - n_global), dtype=torch.float32, device=q.device)
+    nbytes = lib.cls_scores_workspace_bytes(ctypes.byref(desc))
+    ws = _workspace(nbytes, q.device, workspace)
+    _check(lib.cls_scores(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(scores), _ptr(ws),
+                          0 if ws is None else ws.numel(), _stream(stream)))
+    return scores
+
+
+def cls_scores_from_logits(cls_logits, cls_lse, n_global=1, scores=None, stream=None):
+    """The same scores from ns_attn_forward's by-products (no second pass over K)."""
+    B, H, T = cls_logits.shape
+    if not (cls_logits.is_contiguous() and cls_lse.is_contiguous()):
+        raise ValueError("cls_logits and cls_lse must be contiguous")
+    if scores is None:
+        scores = torch.empty((B, T - n_global), dtype=torch.float32, device=cls_logits.device)
+    _check(lib.cls_scores_from_logits(B, H, T, n_global, _ptr(cls_logits), _ptr(cls_lse),
+                                      _ptr(scores), _stream(stream)))
+    return scores
+
+
+def topk_filter(scores, k, x=None, coords=None, kept_idx=None, y=None, coords_out=None,
+                workspace=None, stream=None):
+    """Keep the k best-scoring patches per image.
+
+    scores [B,N] fp32; x optional [B,1+N,C]; coords optional [B,N] int32.
+    Returns (kept_idx [B,k] int32 ascending, y [B,1+k,C] or None, coords_out [B,k] or None)."""
+    if scores.dtype != torch.float32 or not scores.is_contiguous():
+        raise ValueError("scores must be a contiguous float32 tensor")
+    B, N = scores.shape
+    dev = scores.device
+    kk = max(int(k), 0)
+    if kept_idx is None:
+        kept_idx = torch.empty((B, kk), dtype=torch.int32, device=dev)
+    C, xdt = 0, NS_BF16
+    if x is not None:
+        if not x.is_contiguous() or x.shape[0] != B or x.shape[1] != 1 + N:
+            raise ValueError("x must be contiguous [B, 1+N, C]")
+        C, xdt = x.shape[2], _dtype_code(x)
+        if y is None:
+            y = torch.empty((B, 1 + kk, C), dtype=x.dtype, device=dev)
+    if coords is not None:
+        if coords.dtype != torch.int32 or not coords.is_contiguous():
+            raise ValueError("coords must be contiguous int32 [B,N]")
+        if coords_out is None:
+            coords_out = torch.empty((B, kk), dtype=torch.int32, device=dev)
+    nbytes = lib.topk_filter_workspace_bytes(B, N, int(k))
+    ws = _workspace(nbytes, dev, workspace)
+    _check(lib.topk_filter(B, N, int(k), _ptr(scores), _ptr(x), C, xdt, _ptr(coords), _ptr(kept_idx),
+                           _ptr(y), _ptr(coords_out), _ptr(ws), 0 if ws is None else ws.numel(),
+                           _stream(stream)))
+    return kept_idx, y, coords_out

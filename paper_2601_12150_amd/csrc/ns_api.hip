@@ -1,0 +1,277 @@
+// C ABI of libnsattn.so: host-side validation and kernel dispatch.  No kernel lives here.
+#include <stdarg.h>
+#include <stdio.h>
+
+#include "ns_common.h"
+
+namespace ns {
+
+static thread_local char g_err[512] = "";
+
+ns_status fail(ns_status code, const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+ns_status check_launch(const char *what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(NS_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+  return NS_OK;
+}
+
+namespace {
+
+inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+inline size_t elt_size(int dtype) { return dtype == NS_F32 ? 4 : 2; }
+
+// Checks everything about a descriptor that does not involve the data pointers.
+// need_grid = false (scoring): the grid fields and coords are not looked at.
+ns_status validate_desc(const ns_attn_desc *d, bool need_out_strides, bool need_grid = true) {
+  if (!d) return fail(NS_ERR_INVALID_ARG, "descriptor is NULL");
+  if (d->batch < 1 || d->heads < 1 || d->head_dim < 1)
+    return fail(NS_ERR_INVALID_ARG, "batch, heads and head_dim must be positive");
+  if (d->n_global < 1) return fail(NS_ERR_INVALID_ARG, "n_global must be >= 1");
+  if (need_grid && (d->grid_h < 1 || d->grid_w < 1 || d->block < 1 || d->radius < 0))
+    return fail(NS_ERR_INVALID_ARG, "grid and block must be positive, radius >= 0");
+  if (d->dtype != NS_F32 && d->dtype != NS_BF16)
+    return fail(NS_ERR_INVALID_ARG, "dtype must be NS_F32 or NS_BF16");
+  if (!(d->scale == d->scale) || d->scale - d->scale != 0.f)
+    return fail(NS_ERR_INVALID_ARG, "scale must be finite");
+  if (!need_grid) {
+    if (d->tokens <= d->n_global) return fail(NS_ERR_INVALID_ARG, "tokens must exceed n_global");
+  } else if (d->grid_h > 65535 || d->grid_w > 65535) {
+    return fail(NS_ERR_INVALID_ARG, "grid sides must fit 16 bits");
+  }
+  const long long full = (long long)d->grid_h * d->grid_w + d->n_global;
+  if (!need_grid) {
+    // nothing more to check about the geometry
+  } else if (full > 0x7fffffffLL) {
+    return fail(NS_ERR_INVALID_ARG, "grid too large");
+  } else if (d->coords == nullptr) {
+    if (d->tokens != (int32_t)full)
+      return fail(NS_ERR_INVALID_ARG, "tokens (%d) must equal n_global + grid_h*grid_w (%lld)",
+                  d->tokens, full);
+  } else {
+    if (d->tokens <= d->n_global || d->tokens > (int32_t)full)
+      return fail(NS_ERR_INVALID_ARG, "tokens (%d) out of range for a pruned sequence", d->tokens);
+    if (!aligned(d->coords, 4)) return fail(NS_ERR_INVALID_ARG, "coords misaligned");
+  }
+  if (d->head_dim != 64) return fail(NS_ERR_UNSUPPORTED, "head_dim %d: only 64 is implemented", d->head_dim);
+  if (need_grid && d->radius != 1)
+    return fail(NS_ERR_UNSUPPORTED, "radius %d: only 1 (3x3 blocks) is implemented", d->radius);
+  if (d->n_global != 1) return fail(NS_ERR_UNSUPPORTED, "n_global %d: only 1 is implemented", d->n_global);
+  if (d->heads > 1024) return fail(NS_ERR_UNSUPPORTED, "more than 1024 heads");
+  if (need_grid && d->block > 256) return fail(NS_ERR_UNSUPPORTED, "block side above 256");
+  const size_t es = elt_size(d->dtype);
+  if (d->q_stride_t < d->head_dim || (d->q_stride_b * es) % 16 || (d->q_stride_h * es) % 16 ||
+      (d->q_stride_t * es) % 16 || d->q_stride_b < 0 || d->q_stride_h < 0)
+    return fail(NS_ERR_INVALID_ARG, "q/k/v strides must be non-negative, rows 16-byte aligned, stride_t >= head_dim");
+  if (need_out_strides &&
+      (d->out_stride_t < d->head_dim || (d->out_stride_b * es) % 16 || (d->out_stride_h * es) % 16 ||
+       (d->out_stride_t * es) % 16 || d->out_stride_b < 0 || d->out_stride_h < 0))
+    return fail(NS_ERR_INVALID_ARG, "out strides must be non-negative, rows 16-byte aligned, stride_t >= head_dim");
+  return NS_OK;
+}
+
+struct AttnWorkspace {
+  size_t partials_off, lists_off, counts_off, total;
+};
+
+AttnWorkspace attn_workspace_layout(const ns_attn_desc &d) {
+  AttnWorkspace w;
+  size_t off = 0;
+  w.partials_off = off;
+  off += align_up((size_t)d.batch * d.heads * cls_num_chunks(d.tokens) * kClsPartialFloats * 4, 256);
+  w.lists_off = w.counts_off = off;
+  if (d.coords) {
+    const size_t nbh = (d.grid_h + d.block - 1) / d.block, nbw = (d.grid_w + d.block - 1) / d.block;
+    off += align_up((size_t)d.batch * nbh * nbw * d.block * d.block * 4, 256);
+    w.counts_off = off;
+    off += align_up((size_t)d.batch * nbh * nbw * 4, 256);
+  }
+  w.total = off;
+  return w;
+}
+
+ns_status check_workspace(void *ws, size_t have, size_t need) {
+  if (need == 0) return NS_OK;
+  if (!ws) return fail(NS_ERR_WORKSPACE, "workspace is NULL, %zu bytes needed", need);
+  if (!aligned(ws, 256)) return fail(NS_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+  if (have < need) return fail(NS_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", have, need);
+  return NS_OK;
+}
+
+}  // namespace
+}  // namespace ns
+
+using namespace ns;
+
+extern "C" {
+
+const char *ns_last_error(void) { return g_err; }
+const char *ns_version(void) { return "0.1"; }
+
+size_t ns_attn_workspace_bytes(const ns_attn_desc *desc) {
+  if (validate_desc(desc, true) != NS_OK) return 0;
+  return attn_workspace_layout(*desc).total;
+}
+
+// Shared by ns_attn_forward and the timing aid: validation, workspace carving, block lists.
+static ns_status prepare_attn(const ns_attn_desc *desc, const void *q, const void *k, const void *v,
+                              void *out, void *workspace, size_t workspace_bytes, void *stream,
+                              AttnArgs &a, float *&partials) {
+  ns_status st = validate_desc(desc, true);
+  if (st != NS_OK) return st;
+  if (!q || !k || !v || !out) return fail(NS_ERR_INVALID_ARG, "q, k, v and out must not be NULL");
+  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(out, 16))
+    return fail(NS_ERR_INVALID_ARG, "q, k, v and out must be 16-byte aligned");
+  if (out == q || out == k || out == v) return fail(NS_ERR_INVALID_ARG, "out must not alias an input");
+  const ns_attn_desc &d = *desc;
+  const AttnWorkspace w = attn_workspace_layout(d);
+  st = check_workspace(workspace, workspace_bytes, w.total);
+  if (st != NS_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  unsigned char *ws = static_cast<unsigned char *>(workspace);
+  partials = reinterpret_cast<float *>(ws + w.partials_off);
+  a.d = d; a.q = q; a.k = k; a.v = v; a.out = out; a.stream = s;
+  BlockGeom &g = a.geom;
+  g.grid_h = d.grid_h; g.grid_w = d.grid_w; g.block = d.block;
+  g.nbh = (d.grid_h + d.block - 1) / d.block;
+  g.nbw = (d.grid_w + d.block - 1) / d.block;
+  g.n_global = d.n_global; g.tokens = d.tokens; g.cap = d.block * d.block;
+  g.lists = nullptr; g.counts = nullptr;
+  if (d.coords) {
+    int32_t *lists = reinterpret_cast<int32_t *>(ws + w.lists_off);
+    int32_t *counts = reinterpret_cast<int32_t *>(ws + w.counts_off);
+    st = launch_block_lists(d, lists, counts, s);
+    if (st != NS_OK) return st;
+    g.lists = lists; g.counts = counts;
+  }
+  return NS_OK;
+}
+
+ns_status ns_attn_forward(const ns_attn_desc *desc, const void *q, const void *k, const void *v,
+                          void *out, float *cls_logits, float *cls_lse, void *workspace,
+                          size_t workspace_bytes, void *stream) {
+  if ((cls_logits && !aligned(cls_logits, 4)) || (cls_lse && !aligned(cls_lse, 4)))
+    return fail(NS_ERR_INVALID_ARG, "cls_logits / cls_lse misaligned");
+  AttnArgs a;
+  float *partials = nullptr;
+  ns_status st = prepare_attn(desc, q, k, v, out, workspace, workspace_bytes, stream, a, partials);
+  if (st != NS_OK) return st;
+  const ns_attn_desc &d = a.d;
+  st = mfma_attn_supported(d) ? launch_attn_mfma(a) : launch_attn_generic(a);
+  if (st != NS_OK) return st;
+  // the global query's row: chunk partials, then the merge that also writes out[:, :, 0, :]
+  st = launch_cls_row(d, q, k, v, cls_logits, partials, true, a.stream);
+  if (st != NS_OK) return st;
+  return launch_cls_combine(d, partials, out, cls_lse, true, a.stream);
+}
+
+ns_status ns_attn_patch_kernel_time(const ns_attn_desc *desc, const void *q, const void *k,
+                                    const void *v, void *out, void *workspace,
+                                    size_t workspace_bytes, int32_t reps, float *avg_ms,
+                                    void *stream) {
+  if (reps < 1 || !avg_ms) return fail(NS_ERR_INVALID_ARG, "reps must be positive and avg_ms not NULL");
+  AttnArgs a;
+  float *partials = nullptr;
+  ns_status st = prepare_attn(desc, q, k, v, out, workspace, workspace_bytes, stream, a, partials);
+  if (st != NS_OK) return st;
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
+    return fail(NS_ERR_HIP, "hipEventCreate failed");
+  const bool mfma = mfma_attn_supported(a.d);
+  hipEventRecord(e0, a.stream);
+  for (int i = 0; i < reps && st == NS_OK; i++) st = mfma ? launch_attn_mfma(a) : launch_attn_generic(a);
+  hipEventRecord(e1, a.stream);
+  hipError_t e = hipEventSynchronize(e1);
+  float ms = 0.f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+  hipEventDestroy(e0);
+  hipEventDestroy(e1);
+  if (st != NS_OK) return st;
+  if (e != hipSuccess) return fail(NS_ERR_HIP, "event timing: %s", hipGetErrorString(e));
+  *avg_ms = ms / (float)reps;
+  return NS_OK;
+}
+
+size_t cls_scores_workspace_bytes(const ns_attn_desc *desc) {
+  if (validate_desc(desc, false, false) != NS_OK) return 0;
+  const ns_attn_desc &d = *desc;
+  return align_up((size_t)d.batch * d.heads * d.tokens * 4, 256) +
+         align_up((size_t)d.batch * d.heads * cls_num_chunks(d.tokens) * kClsPartialFloats * 4, 256);
+}
+
+ns_status cls_scores(const ns_attn_desc *desc, const void *q, const void *k, float *scores,
+                     void *workspace, size_t workspace_bytes, void *stream) {
+  ns_status st = validate_desc(desc, false, false);
+  if (st != NS_OK) return st;
+  if (!q || !k || !scores) return fail(NS_ERR_INVALID_ARG, "q, k and scores must not be NULL");
+  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(scores, 4))
+    return fail(NS_ERR_INVALID_ARG, "q and k must be 16-byte aligned, scores 4-byte aligned");
+  const ns_attn_desc &d = *desc;
+  st = check_workspace(workspace, workspace_bytes, cls_scores_workspace_bytes(desc));
+  if (st != NS_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  float *logits = static_cast<float *>(workspace);
+  float *partials = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) +
+                                              align_up((size_t)d.batch * d.heads * d.tokens * 4, 256));
+  st = launch_cls_row(d, q, k, nullptr, logits, partials, false, s);
+  if (st != NS_OK) return st;
+  return launch_cls_scores(d.batch, d.heads, d.tokens, d.n_global, logits, nullptr, partials,
+                           cls_num_chunks(d.tokens), scores, s);
+}
+
+ns_status cls_scores_from_logits(int32_t batch, int32_t heads, int32_t tokens, int32_t n_global,
+                                 const float *cls_logits, const float *cls_lse, float *scores,
+                                 void *stream) {
+  if (batch < 1 || heads < 1 || n_global < 1 || tokens <= n_global)
+    return fail(NS_ERR_INVALID_ARG, "batch, heads, n_global must be positive and tokens > n_global");
+  if (heads > 1024) return fail(NS_ERR_UNSUPPORTED, "more than 1024 heads");
+  if (batch > 65535) return fail(NS_ERR_UNSUPPORTED, "batch above 65535");
+  if (!cls_logits || !cls_lse || !scores) return fail(NS_ERR_INVALID_ARG, "NULL pointer");
+  if (!aligned(cls_logits, 4) || !aligned(cls_lse, 4) || !aligned(scores, 4))
+    return fail(NS_ERR_INVALID_ARG, "misaligned pointer");
+  return launch_cls_scores(batch, heads, tokens, n_global, cls_logits, cls_lse, nullptr, 0, scores,
+                           static_cast<hipStream_t>(stream));
+}
+
+size_t topk_filter_workspace_bytes(int32_t batch, int32_t n, int32_t k) {
+  (void)batch; (void)n; (void)k;
+  return 0;   // the selection keeps its state in LDS
+}
+
+ns_status topk_filter(int32_t batch, int32_t n, int32_t k, const float *scores, const void *x,
+                      int32_t channels, int32_t x_dtype, const int32_t *coords_in,
+                      int32_t *kept_idx, void *y, int32_t *coords_out, void *workspace,
+                      size_t workspace_bytes, void *stream) {
+  (void)workspace; (void)workspace_bytes;
+  if (batch < 1 || n < 1) return fail(NS_ERR_INVALID_ARG, "batch and n must be positive");
+  if (k < 1 || k > n) return fail(NS_ERR_INVALID_ARG, "k = %d must be in [1, n = %d]", k, n);
+  if (batch > 65535) return fail(NS_ERR_UNSUPPORTED, "batch above 65535");
+  if (!scores || !kept_idx) return fail(NS_ERR_INVALID_ARG, "scores and kept_idx must not be NULL");
+  if (!aligned(scores, 4) || !aligned(kept_idx, 4)) return fail(NS_ERR_INVALID_ARG, "misaligned pointer");
+  if ((x == nullptr) != (y == nullptr)) return fail(NS_ERR_INVALID_ARG, "x and y must be given together");
+  if ((coords_in == nullptr) != (coords_out == nullptr))
+    return fail(NS_ERR_INVALID_ARG, "coords_in and coords_out must be given together");
+  size_t row_bytes = 0;
+  if (x) {
+    if (x_dtype != NS_F32 && x_dtype != NS_BF16) return fail(NS_ERR_INVALID_ARG, "bad x_dtype");
+    if (channels < 1) return fail(NS_ERR_INVALID_ARG, "channels must be positive");
+    row_bytes = (size_t)channels * elt_size(x_dtype);
+    if (row_bytes % 16) return fail(NS_ERR_UNSUPPORTED, "row size %zu bytes is not a multiple of 16", row_bytes);
+    if (row_bytes / 16 > 0x7fffffffULL) return fail(NS_ERR_UNSUPPORTED, "row too long");
+    if (!aligned(x, 16) || !aligned(y, 16)) return fail(NS_ERR_INVALID_ARG, "x and y must be 16-byte aligned");
+    if (x == y) return fail(NS_ERR_INVALID_ARG, "y must not alias x");
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  ns_status st = launch_topk_select(batch, n, k, scores, coords_in, kept_idx, coords_out, s);
+  if (st != NS_OK) return st;
+  if (x) return launch_gather_rows(batch, n, k, row_bytes, x, kept_idx, y, s);
+  return NS_OK;
+}
+
+}  // extern "C"

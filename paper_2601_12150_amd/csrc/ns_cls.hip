@@ -1,0 +1,227 @@
+// The global (CLS) query's attention row and the importance scores derived from it.
+//
+// Paper, "Memory-Efficiency Optimization": the global token attends to every token.
+// Paper, "Time-Efficiency Optimization": a per-token importance score is read off the
+// global token's attention weights; here: softmax weight of CLS on each patch key, averaged
+// over heads.
+//
+// One query against T keys is a bandwidth problem, so the row is cut into chunks of 512
+// keys: cls_row_kernel streams K (and V) once, writes the raw logits and one softmax
+// partial (max, sum, weighted V sum) per chunk; cls_combine_kernel merges the partials in
+// chunk order; cls_scores_kernel turns logits + log-sum-exp into head-averaged weights.
+#include "ns_common.h"
+
+namespace ns {
+
+namespace {
+
+template <typename T> struct Row8;   // 8 consecutive elements of a row as floats
+template <> struct Row8<float> {
+  __device__ static void load(const float *p, float (&x)[8]) {
+    f32x4 a = *reinterpret_cast<const f32x4 *>(p), b = *reinterpret_cast<const f32x4 *>(p + 4);
+#pragma unroll
+    for (int e = 0; e < 4; e++) { x[e] = a[e]; x[4 + e] = b[e]; }
+  }
+};
+template <> struct Row8<uint16_t> {
+  __device__ static void load(const uint16_t *p, float (&x)[8]) {
+    uint4 u = *reinterpret_cast<const uint4 *>(p);
+    x[0] = bf16_lo(u.x); x[1] = bf16_hi(u.x); x[2] = bf16_lo(u.y); x[3] = bf16_hi(u.y);
+    x[4] = bf16_lo(u.z); x[5] = bf16_hi(u.z); x[6] = bf16_lo(u.w); x[7] = bf16_hi(u.w);
+  }
+};
+
+constexpr int kSteps = kClsChunk / (4 * 8);   // 4 waves x 8 keys per wave-step
+
+// grid (chunks, H, B), 256 threads.  Lane = (key slot, 8-channel slice): 8 lanes per key row.
+template <typename T, bool WITH_V>
+__global__ __launch_bounds__(256) void cls_row_kernel(const T *q, const T *k, const T *v,
+                                                      int64_t sb, int64_t sh, int64_t st, int T_,
+                                                      int H, float scale, float *logits,
+                                                      float *partials, int nchunks) {
+  const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int slot = lane >> 3, sub = lane & 7;
+  const T *qb = q + b * sb + h * sh;          // token 0
+  const T *kb = k + b * sb + h * sh;
+  const T *vb = WITH_V ? v + b * sb + h * sh : nullptr;
+  __shared__ float red[4];
+  __shared__ float osum[4][64];
+
+  float q8[8];
+  Row8<T>::load(qb + sub * 8, q8);
+#pragma unroll
+  for (int e = 0; e < 8; e++) q8[e] *= scale;
+
+  const int key0 = chunk * kClsChunk + wave * (kSteps * 8) + slot;
+  float s[kSteps];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < kSteps; i++) {
+    const int key = key0 + i * 8;
+    float acc = -INFINITY;
+    if (key < T_) {
+      float k8[8];
+      Row8<T>::load(kb + (int64_t)key * st + sub * 8, k8);
+      acc = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; e++) acc = __builtin_fmaf(q8[e], k8[e], acc);
+    }
+    // sum the 8 channel slices of the row (all lanes of the slot end up with the logit)
+    acc += __shfl_xor(acc, 1);
+    acc += __shfl_xor(acc, 2);
+    acc += __shfl_xor(acc, 4);
+    s[i] = acc;
+    mx = fmaxf(mx, acc);
+    if (sub == 0 && key < T_ && logits) logits[((size_t)b * H + h) * T_ + key] = acc;
+  }
+  mx = fmaxf(mx, __shfl_xor(mx, 8));
+  mx = fmaxf(mx, __shfl_xor(mx, 16));
+  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  if (lane == 0) red[wave] = mx;
+  __syncthreads();
+  const float M = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));   // finite: chunk non-empty
+  __syncthreads();
+
+  float l = 0.f;
+  float o8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int i = 0; i < kSteps; i++) {
+    const int key = key0 + i * 8;
+    if (key < T_) {
+      const float pr = __builtin_amdgcn_exp2f((s[i] - M) * kLog2e);
+      l += pr;
+      if (WITH_V) {
+        float v8[8];
+        Row8<T>::load(vb + (int64_t)key * st + sub * 8, v8);
+#pragma unroll
+        for (int e = 0; e < 8; e++) o8[e] = __builtin_fmaf(pr, v8[e], o8[e]);
+      }
+    }
+  }
+  // across the 8 key slots of the wave (not across channel slices)
+#pragma unroll
+  for (int sft = 8; sft < 64; sft <<= 1) {
+    l += __shfl_xor(l, sft);
+    if (WITH_V) {
+#pragma unroll
+      for (int e = 0; e < 8; e++) o8[e] += __shfl_xor(o8[e], sft);
+    }
+  }
+  if (lane == 0) red[wave] = l;
+  if (WITH_V && slot == 0) {
+#pragma unroll
+    for (int e = 0; e < 8; e++) osum[wave][sub * 8 + e] = o8[e];
+  }
+  __syncthreads();
+  float *rec = partials + (((size_t)b * H + h) * nchunks + chunk) * kClsPartialFloats;
+  if (tid == 0) {
+    rec[0] = M;
+    rec[1] = (red[0] + red[1]) + (red[2] + red[3]);
+  }
+  if (WITH_V && tid < 64) rec[2 + tid] = (osum[0][tid] + osum[1][tid]) + (osum[2][tid] + osum[3][tid]);
+}
+
+__device__ __forceinline__ void store_out(float *p, float x) { *p = x; }
+__device__ __forceinline__ void store_out(uint16_t *p, float x) { *p = (uint16_t)(pack_bf16(x, 0.f) & 0xffffu); }
+
+// grid (H, B), 64 threads (thread = channel).  Merges the chunk partials in chunk order.
+template <typename T, bool WITH_V>
+__global__ __launch_bounds__(64) void cls_combine_kernel(const float *partials, int nchunks, int H,
+                                                         T *out, int64_t osb, int64_t osh,
+                                                         float *lse) {
+  const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
+  const float *rec = partials + ((size_t)b * H + h) * nchunks * kClsPartialFloats;
+  float M = -INFINITY;
+  for (int c = 0; c < nchunks; c++) M = fmaxf(M, rec[c * kClsPartialFloats]);
+  float L = 0.f, O = 0.f;
+  for (int c = 0; c < nchunks; c++) {
+    const float w = __builtin_amdgcn_exp2f((rec[c * kClsPartialFloats] - M) * kLog2e);
+    L = __builtin_fmaf(rec[c * kClsPartialFloats + 1], w, L);
+    if (WITH_V) O = __builtin_fmaf(rec[c * kClsPartialFloats + 2 + d], w, O);
+  }
+  if (WITH_V) store_out(out + b * osb + h * osh + d, O / L);
+  if (lse && d == 0) lse[(size_t)b * H + h] = M + __builtin_amdgcn_logf(L) * kLn2;
+}
+
+// grid (ceil(N/256), B), 256 threads (thread = patch).  lse given directly, or recomputed per
+// head from the row kernel's (max, sum) partials.
+__global__ __launch_bounds__(256) void cls_scores_kernel(const float *logits, const float *lse,
+                                                         const float *partials, int nchunks, int H,
+                                                         int T_, int G, float *scores) {
+  __shared__ float s_lse[1024];
+  const int b = blockIdx.y, tid = threadIdx.x;
+  for (int h = tid; h < H; h += 256) {
+    if (lse) {
+      s_lse[h] = lse[(size_t)b * H + h];
+    } else {
+      const float *rec = partials + ((size_t)b * H + h) * nchunks * kClsPartialFloats;
+      float M = -INFINITY;
+      for (int c = 0; c < nchunks; c++) M = fmaxf(M, rec[c * kClsPartialFloats]);
+      float L = 0.f;
+      for (int c = 0; c < nchunks; c++)
+        L = __builtin_fmaf(rec[c * kClsPartialFloats + 1],
+                           __builtin_amdgcn_exp2f((rec[c * kClsPartialFloats] - M) * kLog2e), L);
+      s_lse[h] = M + __builtin_amdgcn_logf(L) * kLn2;
+    }
+  }
+  __syncthreads();
+  const int N = T_ - G;
+  const int j = blockIdx.x * 256 + tid;
+  if (j >= N) return;
+  float acc = 0.f;
+  for (int h = 0; h < H; h++) {
+    const float x = logits[((size_t)b * H + h) * T_ + G + j];
+    acc += __builtin_amdgcn_exp2f((x - s_lse[h]) * kLog2e);
+  }
+  scores[(size_t)b * N + j] = acc / (float)H;
+}
+
+}  // namespace
+
+ns_status launch_cls_row(const ns_attn_desc &d, const void *q, const void *k, const void *v,
+                         float *logits, float *partials, bool with_v, hipStream_t s) {
+  const int nch = cls_num_chunks(d.tokens);
+  dim3 grid(nch, d.heads, d.batch), blk(256);
+#define NS_ROW(T, WV)                                                                          \
+  hipLaunchKernelGGL((cls_row_kernel<T, WV>), grid, blk, 0, s, static_cast<const T *>(q),      \
+                     static_cast<const T *>(k), static_cast<const T *>(v), d.q_stride_b,       \
+                     d.q_stride_h, d.q_stride_t, d.tokens, d.heads, d.scale, logits, partials, nch)
+  if (d.dtype == NS_F32) { if (with_v) NS_ROW(float, true); else NS_ROW(float, false); }
+  else { if (with_v) NS_ROW(uint16_t, true); else NS_ROW(uint16_t, false); }
+#undef NS_ROW
+  return check_launch("cls_row_kernel");
+}
+
+ns_status launch_cls_combine(const ns_attn_desc &d, const float *partials, void *out, float *lse,
+                             bool with_v, hipStream_t s) {
+  const int nch = cls_num_chunks(d.tokens);
+  dim3 grid(d.heads, d.batch), blk(64);
+  if (d.dtype == NS_F32) {
+    if (with_v)
+      hipLaunchKernelGGL((cls_combine_kernel<float, true>), grid, blk, 0, s, partials, nch, d.heads,
+                         static_cast<float *>(out), d.out_stride_b, d.out_stride_h, lse);
+    else
+      hipLaunchKernelGGL((cls_combine_kernel<float, false>), grid, blk, 0, s, partials, nch, d.heads,
+                         static_cast<float *>(out), d.out_stride_b, d.out_stride_h, lse);
+  } else {
+    if (with_v)
+      hipLaunchKernelGGL((cls_combine_kernel<uint16_t, true>), grid, blk, 0, s, partials, nch,
+                         d.heads, static_cast<uint16_t *>(out), d.out_stride_b, d.out_stride_h, lse);
+    else
+      hipLaunchKernelGGL((cls_combine_kernel<uint16_t, false>), grid, blk, 0, s, partials, nch,
+                         d.heads, static_cast<uint16_t *>(out), d.out_stride_b, d.out_stride_h, lse);
+  }
+  return check_launch("cls_combine_kernel");
+}
+
+ns_status launch_cls_scores(int B, int H, int T, int G, const float *logits, const float *lse,
+                            const float *partials, int nchunks, float *scores, hipStream_t s) {
+  const int N = T - G;
+  dim3 grid((N + 255) / 256, B), blk(256);
+  hipLaunchKernelGGL(cls_scores_kernel, grid, blk, 0, s, logits, lse, partials, nchunks, H, T, G,
+                     scores);
+  return check_launch("cls_scores_kernel");
+}
+
+}  // namespace ns

@@ -1,0 +1,97 @@
+// Internal helpers shared by the HIP translation units of libnsattn.so.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "../../include/nsattn.h"
+
+namespace ns {
+
+// ---- error reporting -------------------------------------------------------
+ns_status fail(ns_status code, const char *fmt, ...);
+ns_status check_launch(const char *what);   // hipGetLastError -> NS_ERR_HIP
+
+// ---- bf16 <-> fp32 on the device ------------------------------------------
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
+
+// round-to-nearest-even pack of two floats into two bf16 (v_cvt_pk_bf16_f32 on gfx950)
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  f32x2 v = {lo, hi};
+  bf16x2 r = __builtin_convertvector(v, bf16x2);
+  return __builtin_bit_cast(uint32_t, r);
+}
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// ---- geometry of the block neighbourhood ----------------------------------
+// Everything a kernel needs to turn (block, slot) into a token index.  With lists == nullptr
+// the sequence is the full raster grid and the mapping is analytic; otherwise (pruned
+// sequence) lists[b][blk][slot] holds the token index and counts[b][blk] the fill.
+struct BlockGeom {
+  int grid_h, grid_w, block, nbh, nbw, n_global, tokens;
+  int cap;                 // block*block: slots per block in `lists`
+  const int32_t *lists;    // [B, nbh*nbw, cap] or nullptr
+  const int32_t *counts;   // [B, nbh*nbw]      or nullptr
+};
+
+__device__ __forceinline__ int block_count(const BlockGeom &g, int b, int R, int C) {
+  if (g.counts) return g.counts[(size_t)b * g.nbh * g.nbw + R * g.nbw + C];
+  int bh = min(g.block, g.grid_h - R * g.block);
+  int bw = min(g.block, g.grid_w - C * g.block);
+  return bh * bw;
+}
+
+__device__ __forceinline__ int block_token(const BlockGeom &g, int b, int R, int C, int slot) {
+  if (g.lists) return g.lists[((size_t)b * g.nbh * g.nbw + R * g.nbw + C) * g.cap + slot];
+  int bw = min(g.block, g.grid_w - C * g.block);
+  int r = R * g.block + slot / bw;
+  int c = C * g.block + slot % bw;
+  return g.n_global + r * g.grid_w + c;
+}
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---- launchers implemented in the individual .hip files --------------------
+struct AttnArgs {
+  ns_attn_desc d;
+  const void *q, *k, *v;
+  void *out;
+  BlockGeom geom;
+  hipStream_t stream;
+};
+
+ns_status launch_block_lists(const ns_attn_desc &d, int32_t *lists, int32_t *counts, hipStream_t s);
+ns_status launch_attn_generic(const AttnArgs &a);
+bool mfma_attn_supported(const ns_attn_desc &d);
+ns_status launch_attn_mfma(const AttnArgs &a);
+
+// global-query (CLS) row: per-chunk partials, then a combine.
+constexpr int kClsChunk = 512;                      // keys per workgroup of the row kernel
+inline int cls_num_chunks(int tokens) { return (tokens + kClsChunk - 1) / kClsChunk; }
+// partial record per (b, h, chunk): m, l, o[64]
+constexpr int kClsPartialFloats = 2 + 64;
+ns_status launch_cls_row(const ns_attn_desc &d, const void *q, const void *k, const void *v,
+                         float *logits /* [B,H,T] */, float *partials, bool with_v, hipStream_t s);
+ns_status launch_cls_combine(const ns_attn_desc &d, const float *partials, void *out, float *lse,
+                             bool with_v, hipStream_t s);
+// lse given directly, or (lse == nullptr) recomputed from the row kernel's partials
+ns_status launch_cls_scores(int B, int H, int T, int G, const float *logits, const float *lse,
+                            const float *partials, int nchunks, float *scores, hipStream_t s);
+
+ns_status launch_topk_select(int B, int N, int k, const float *scores, const int32_t *coords_in,
+                             int32_t *kept, int32_t *coords_out, hipStream_t s);
+ns_status launch_gather_rows(int B, int N, int k, size_t row_bytes, const void *x,
+                             const int32_t *kept, void *y, hipStream_t s);
+
+}  // namespace ns

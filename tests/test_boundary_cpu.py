@@ -1,0 +1,103 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every function
+the header declares, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "nsattn.h")
+
+
+@pytest.fixture(scope="module")
+def nb():
+    from paper_2601_12150_amd import binding
+    return binding
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b([a-z_][a-z0-9_]*)\s*\([^;{]*\)\s*;", text)
+    return sorted(set(names))
+
+
+def test_library_exports_every_declared_function(nb):
+    names = declared_functions()
+    assert {"ns_attn_forward", "cls_scores", "topk_filter", "vit_block_forward"} <= set(names)
+    raw = ctypes.CDLL(nb.LIB_PATH)
+    for n in names:
+        assert hasattr(raw, n), "libnsattn.so does not export %s" % n
+    assert set(nb.EXPORTS) == set(names)
+
+
+def good_desc(nb):
+    d = nb.ns_attn_desc()
+    d.batch, d.heads, d.head_dim = 1, 2, 64
+    d.grid_h = d.grid_w = 8
+    d.block, d.radius, d.n_global, d.dtype, d.tokens = 4, 1, 1, nb.NS_BF16, 65
+    d.scale = 0.125
+    d.q_stride_b, d.q_stride_h, d.q_stride_t = 2 * 65 * 64, 65 * 64, 64
+    d.out_stride_b, d.out_stride_h, d.out_stride_t = 2 * 65 * 64, 65 * 64, 64
+    return d
+
+
+FAKE = ctypes.c_void_p(0x10000)   # never dereferenced: every call below fails validation first
+
+
+def attn_call(nb, d, q=FAKE, out=ctypes.c_void_p(0x20000), ws=ctypes.c_void_p(0x30000), ws_bytes=1 << 30):
+    return nb.lib.ns_attn_forward(ctypes.byref(d), q, FAKE, FAKE, out, None, None, ws, ws_bytes, None)
+
+
+def test_descriptor_validation(nb):
+    d = good_desc(nb)
+    assert nb.lib.ns_attn_workspace_bytes(ctypes.byref(d)) > 0
+    cases = [("batch", 0, nb.NS_ERR_INVALID_ARG), ("heads", -1, nb.NS_ERR_INVALID_ARG),
+             ("block", 0, nb.NS_ERR_INVALID_ARG), ("dtype", 7, nb.NS_ERR_INVALID_ARG),
+             ("tokens", 64, nb.NS_ERR_INVALID_ARG), ("scale", float("nan"), nb.NS_ERR_INVALID_ARG),
+             ("q_stride_t", 63, nb.NS_ERR_INVALID_ARG), ("q_stride_h", 65 * 64 + 1, nb.NS_ERR_INVALID_ARG),
+             ("out_stride_t", 8, nb.NS_ERR_INVALID_ARG),
+             ("head_dim", 128, nb.NS_ERR_UNSUPPORTED), ("radius", 2, nb.NS_ERR_UNSUPPORTED),
+             ("n_global", 2, nb.NS_ERR_UNSUPPORTED)]
+    for field, value, code in cases:
+        d = good_desc(nb)
+        setattr(d, field, value)
+        if field == "n_global":
+            d.tokens = 66
+        assert attn_call(nb, d) == code, field
+        assert nb.lib.ns_last_error()
+        assert nb.lib.ns_attn_workspace_bytes(ctypes.byref(d)) == 0
+    assert nb.lib.ns_attn_forward(None, FAKE, FAKE, FAKE, FAKE, None, None, None, 0, None) == nb.NS_ERR_INVALID_ARG
+
+
+def test_pointer_and_workspace_validation(nb):
+    d = good_desc(nb)
+    assert attn_call(nb, d, q=None) == nb.NS_ERR_INVALID_ARG
+    assert attn_call(nb, d, q=ctypes.c_void_p(0x10008)) == nb.NS_ERR_INVALID_ARG       # misaligned
+    assert attn_call(nb, d, out=FAKE) == nb.NS_ERR_INVALID_ARG                         # aliasing
+    assert attn_call(nb, d, ws=None) == nb.NS_ERR_WORKSPACE
+    assert attn_call(nb, d, ws=ctypes.c_void_p(0x30010)) == nb.NS_ERR_WORKSPACE        # misaligned
+    assert attn_call(nb, d, ws_bytes=16) == nb.NS_ERR_WORKSPACE
+    assert b"needed" in nb.lib.ns_last_error()
+
+
+def test_topk_and_scores_validation(nb):
+    L = nb.lib
+    args = dict(x=None, C=0, dt=nb.NS_BF16, cin=None, kept=FAKE, y=None, cout=None)
+    def call(B, N, k, scores=FAKE, **kw):
+        a = dict(args); a.update(kw)
+        return L.topk_filter(B, N, k, scores, a["x"], a["C"], a["dt"], a["cin"], a["kept"], a["y"],
+                             a["cout"], None, 0, None)
+    assert call(1, 100, 0) == nb.NS_ERR_INVALID_ARG
+    assert call(1, 100, 101) == nb.NS_ERR_INVALID_ARG
+    assert call(0, 100, 10) == nb.NS_ERR_INVALID_ARG
+    assert call(1, 100, 10, scores=None) == nb.NS_ERR_INVALID_ARG
+    assert call(1, 100, 10, x=FAKE, C=64) == nb.NS_ERR_INVALID_ARG                   # y missing
+    assert call(1, 100, 10, x=FAKE, y=ctypes.c_void_p(0x20000), C=3) == nb.NS_ERR_UNSUPPORTED
+    assert call(1, 100, 10, cin=FAKE) == nb.NS_ERR_INVALID_ARG                       # coords_out missing
+    assert L.cls_scores_from_logits(1, 2, 1, 1, FAKE, FAKE, FAKE, None) == nb.NS_ERR_INVALID_ARG
+    assert L.cls_scores_from_logits(1, 2, 10, 1, None, FAKE, FAKE, None) == nb.NS_ERR_INVALID_ARG
+    d = good_desc(nb)
+    assert L.cls_scores(ctypes.byref(d), FAKE, FAKE, None, FAKE, 1 << 30, None) == nb.NS_ERR_INVALID_ARG
+    assert L.cls_scores_workspace_bytes(ctypes.byref(d)) > 0
