@@ -44,6 +44,10 @@ def main() -> int:
                     help="input sets rotated between steps so that no step finds its inputs in the 256 MB "
                          "Infinity Cache (1 = warm-cache run)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-stages", action="store_true", help="skip the per-stage timings (profiling runs)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain copy of known size (the row-gather kernel with every row kept) "
+                         "so that byte counters of a profiler can be scaled")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target duration of the oracle sample")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -98,6 +102,16 @@ def main() -> int:
                                   nb.NS_BF16 if cfg.dtype == "bf16" else nb.NS_F32, None,
                                   vp(s["kept"].data_ptr()), vp(s["y"].data_ptr()), None, None, 0, st))
 
+    if args.calibration_copy:
+        # plain copy of B*T*C elements: every patch kept, so gather_rows_kernel reads and writes each row once
+        s0 = sets[0]
+        ident = torch.arange(T - 1, dtype=torch.float32, device="cuda").flip(0).repeat(B, 1).contiguous()
+        ycal = torch.empty_like(s0["x"])
+        kcal = torch.empty((B, T - 1), dtype=torch.int32, device="cuda")
+        nb.topk_filter(ident, T - 1, x=s0["x"], kept_idx=kcal, y=ycal)
+        torch.cuda.synchronize()
+        del ycal, kcal, ident
+
     for i in range(args.warmup):
         step(sets[i % len(sets)])
     torch.cuda.synchronize()
@@ -135,54 +149,19 @@ def main() -> int:
                 "flops_per_launch": flops_kernel,
                 "min_hbm_bytes_per_launch": 4.0 * B * H * T * D * (2 if cfg.dtype == "bf16" else 4)}
 
-    # ---- the bandwidth-bound stages, each timed alone (extra information) ---------------
-    def time_call(fn, n=20):
-        fn(sets[0]); torch.cuda.synchronize()
-        t = time.perf_counter()
-        for i in range(n):
-            fn(sets[i % len(sets)])
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t) / n
+    # traffic measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by the calibration copy) is
+    # recorded in profiles/; it is reported here when the record is for this workload
+    traffic_file = os.path.join(ROOT, "profiles", "attn_mfma_kernel_%s_traffic.json" % cfg.name)
+    if os.path.exists(traffic_file):
+        with open(traffic_file) as f:
+            roofline["traffic"] = json.load(f).get("hbm_bytes_per_launch")
 
-    ws2 = torch.empty(nb.lib.cls_scores_workspace_bytes(ctypes.byref(desc0)), dtype=torch.uint8, device="cuda")
-    elt = 2 if cfg.dtype == "bf16" else 4
-    t_scores = time_call(lambda s: nb.cls_scores(s["q"], s["k"], cfg.scale, scores=s["scores"], workspace=ws2))
-    t_filter = time_call(lambda s: nb.topk_filter(s["scores"], k, x=s["x"], kept_idx=s["kept"], y=s["y"]))
-    t_select = time_call(lambda s: nb.topk_filter(s["scores"], k, kept_idx=s["kept"]))
-    t_attn = time_call(lambda s: nb.ns_attn_forward(s["q"], s["k"], s["v"], g, g, blk, cfg.scale, out=s["out"],
-                                                    workspace=ws))
-    bytes_scores = B * H * T * D * elt + B * H * T * 4 * 2 + B * (T - 1) * 4
-    bytes_gather = 2 * B * (1 + k) * C * elt + B * k * 4
-    stages = {
-        "ns_attn_forward_ms": t_attn * 1e3,
-        "ns_attn_forward_tflops_sparse": flops_layer / t_attn / 1e12,
-        "cls_scores_standalone_ms": t_scores * 1e3,
-        "cls_scores_standalone_GBps": bytes_scores / t_scores / 1e9,
-        "topk_select_ms": t_select * 1e3,
-        "gather_ms": max(t_filter - t_select, 0.0) * 1e3,
-        "gather_GBps": bytes_gather / max(t_filter - t_select, 1e-9) / 1e9,
-        "hbm_peak_GBps": PEAK_HBM / 1e9,
-    }
-
-    # ---- CPU oracle on a bounded sample of the same workload --------------------------------
+    stages = None
     cpu = None
+    if not args.no_stages:
+        stages = measure_stages(nb, torch, sets, cfg, g, blk, k, C, B, H, T, D, ws, desc0, flops_layer)
     if not args.no_cpu_baseline:
-        import oracle
-        rng = np.random.default_rng(0)
-        probe = np.sort(rng.choice(np.arange(1, T), size=64, replace=False)).astype(np.int32)
-        t = time.perf_counter()
-        oracle.ns_attn(q, kk, v, g, g, blk, cfg.scale, rows=probe)
-        per_row = (time.perf_counter() - t) / len(probe)
-        n_rows = int(min(T - 1, max(64, args.cpu_seconds / per_row)))
-        rows = np.sort(rng.choice(np.arange(1, T), size=n_rows, replace=False)).astype(np.int32)
-        t = time.perf_counter()
-        oracle.ns_attn(q, kk, v, g, g, blk, cfg.scale, rows=rows)
-        sc = oracle.cls_scores(q, kk, cfg.scale)
-        oracle.topk(sc.astype(np.float32), k)
-        t_cpu = time.perf_counter() - t
-        cpu = {"value": B * n_rows / t_cpu, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
-               "sample": "%d of %d query tokens per image (all %d heads, %d images) through the attention oracle, "
-                         "plus full scoring and top-k; %.1f s" % (n_rows, T, H, B, t_cpu)}
+        cpu = cpu_baseline(np, cfg, q, kk, v, g, blk, k, B, H, T, args.cpu_seconds)
 
     out = {"metric": "sparse_attn_layer_tokens_per_s", "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1,
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
@@ -196,6 +175,61 @@ def main() -> int:
            "roofline": roofline, "cpu_baseline": cpu, "stages": stages}
     print(json.dumps(out))
     return 0
+
+
+def measure_stages(nb, torch, sets, cfg, g, blk, k, C, B, H, T, D, ws, desc0, flops_layer):
+    """The bandwidth-bound stages and the whole attention call, each timed alone (extra information)."""
+    import ctypes
+
+    def time_call(fn, n=20):
+        fn(sets[0]); torch.cuda.synchronize()
+        t = time.perf_counter()
+        for i in range(n):
+            fn(sets[i % len(sets)])
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / n
+
+    ws2 = torch.empty(nb.lib.cls_scores_workspace_bytes(ctypes.byref(desc0)), dtype=torch.uint8, device="cuda")
+    elt = 2 if cfg.dtype == "bf16" else 4
+    t_scores = time_call(lambda s: nb.cls_scores(s["q"], s["k"], cfg.scale, scores=s["scores"], workspace=ws2))
+    t_fused = time_call(lambda s: nb.cls_scores_from_logits(s["logits"], s["lse"], scores=s["scores"]))
+    t_filter = time_call(lambda s: nb.topk_filter(s["scores"], k, x=s["x"], kept_idx=s["kept"], y=s["y"]))
+    t_select = time_call(lambda s: nb.topk_filter(s["scores"], k, kept_idx=s["kept"]))
+    t_attn = time_call(lambda s: nb.ns_attn_forward(s["q"], s["k"], s["v"], g, g, blk, cfg.scale, out=s["out"],
+                                                    workspace=ws))
+    bytes_scores = B * H * T * D * elt + B * H * T * 4 * 2 + B * (T - 1) * 4
+    bytes_gather = 2 * B * (1 + k) * C * elt + B * k * 4
+    return {
+        "ns_attn_forward_ms": t_attn * 1e3,
+        "ns_attn_forward_tflops_sparse": flops_layer / t_attn / 1e12,
+        "cls_scores_standalone_ms": t_scores * 1e3,
+        "cls_scores_standalone_GBps": bytes_scores / t_scores / 1e9,
+        "cls_scores_from_logits_ms": t_fused * 1e3,
+        "topk_select_ms": t_select * 1e3,
+        "gather_ms": max(t_filter - t_select, 0.0) * 1e3,
+        "gather_GBps": bytes_gather / max(t_filter - t_select, 1e-9) / 1e9,
+        "hbm_peak_GBps": PEAK_HBM / 1e9,
+    }
+
+
+def cpu_baseline(np, cfg, q, kk, v, g, blk, k, B, H, T, seconds):
+    """The CPU oracle as it stands, timed on a bounded sample of the same workload."""
+    import oracle
+    rng = np.random.default_rng(0)
+    probe = np.sort(rng.choice(np.arange(1, T), size=64, replace=False)).astype(np.int32)
+    t = time.perf_counter()
+    oracle.ns_attn(q, kk, v, g, g, blk, cfg.scale, rows=probe)
+    per_row = (time.perf_counter() - t) / len(probe)
+    n_rows = int(min(T - 1, max(64, seconds / per_row)))
+    rows = np.sort(rng.choice(np.arange(1, T), size=n_rows, replace=False)).astype(np.int32)
+    t = time.perf_counter()
+    oracle.ns_attn(q, kk, v, g, g, blk, cfg.scale, rows=rows)
+    sc = oracle.cls_scores(q, kk, cfg.scale)
+    oracle.topk(sc.astype(np.float32), k)
+    t_cpu = time.perf_counter() - t
+    return {"value": B * n_rows / t_cpu, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "%d of %d query tokens per image (all %d heads, %d images) through the attention oracle, "
+                      "plus full scoring and top-k; %.1f s" % (n_rows, T, H, B, t_cpu)}
 
 
 if __name__ == "__main__":

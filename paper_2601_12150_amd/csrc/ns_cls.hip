@@ -125,23 +125,41 @@ __global__ __launch_bounds__(256) void cls_row_kernel(const T *q, const T *k, co
 __device__ __forceinline__ void store_out(float *p, float x) { *p = x; }
 __device__ __forceinline__ void store_out(uint16_t *p, float x) { *p = (uint16_t)(pack_bf16(x, 0.f) & 0xffffu); }
 
-// grid (H, B), 64 threads (thread = channel).  Merges the chunk partials in chunk order.
+// grid (H, B), 256 threads: thread (group g = tid/64, channel d = tid%64).  Group g merges the
+// chunk partials g, g+4, g+8, ... with a running maximum; the four groups are then merged in
+// group order.  The order of operations is fixed, so the result is deterministic.
 template <typename T, bool WITH_V>
-__global__ __launch_bounds__(64) void cls_combine_kernel(const float *partials, int nchunks, int H,
-                                                         T *out, int64_t osb, int64_t osh,
-                                                         float *lse) {
-  const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
+__global__ __launch_bounds__(256) void cls_combine_kernel(const float *partials, int nchunks, int H,
+                                                          T *out, int64_t osb, int64_t osh,
+                                                          float *lse) {
+  const int h = blockIdx.x, b = blockIdx.y, g = threadIdx.x >> 6, d = threadIdx.x & 63;
   const float *rec = partials + ((size_t)b * H + h) * nchunks * kClsPartialFloats;
-  float M = -INFINITY;
-  for (int c = 0; c < nchunks; c++) M = fmaxf(M, rec[c * kClsPartialFloats]);
-  float L = 0.f, O = 0.f;
-  for (int c = 0; c < nchunks; c++) {
-    const float w = __builtin_amdgcn_exp2f((rec[c * kClsPartialFloats] - M) * kLog2e);
-    L = __builtin_fmaf(rec[c * kClsPartialFloats + 1], w, L);
-    if (WITH_V) O = __builtin_fmaf(rec[c * kClsPartialFloats + 2 + d], w, O);
+  __shared__ float sm[4], sl[4], so[4][64];
+  float M = -INFINITY, L = 0.f, O = 0.f;
+#pragma unroll 4
+  for (int c = g; c < nchunks; c += 4) {
+    const float mc = rec[c * kClsPartialFloats], lc = rec[c * kClsPartialFloats + 1];
+    const float oc = WITH_V ? rec[c * kClsPartialFloats + 2 + d] : 0.f;
+    const float Mn = fmaxf(M, mc);
+    const float wo = __builtin_amdgcn_exp2f((M - Mn) * kLog2e), wn = __builtin_amdgcn_exp2f((mc - Mn) * kLog2e);
+    L = __builtin_fmaf(L, wo, lc * wn);
+    O = __builtin_fmaf(O, wo, oc * wn);
+    M = Mn;
   }
-  if (WITH_V) store_out(out + b * osb + h * osh + d, O / L);
-  if (lse && d == 0) lse[(size_t)b * H + h] = M + __builtin_amdgcn_logf(L) * kLn2;
+  if (d == 0) { sm[g] = M; sl[g] = L; }
+  so[g][d] = O;
+  __syncthreads();
+  if (g != 0) return;
+  float Mt = fmaxf(fmaxf(sm[0], sm[1]), fmaxf(sm[2], sm[3]));   // finite: group 0 always has a chunk
+  float Lt = 0.f, Ot = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    const float w = __builtin_amdgcn_exp2f((sm[i] - Mt) * kLog2e);   // 0 for an empty group
+    Lt = __builtin_fmaf(sl[i], w, Lt);
+    Ot = __builtin_fmaf(so[i][d], w, Ot);
+  }
+  if (WITH_V) store_out(out + b * osb + h * osh + d, Ot / Lt);
+  if (lse && d == 0) lse[(size_t)b * H + h] = Mt + __builtin_amdgcn_logf(Lt) * kLn2;
 }
 
 // grid (ceil(N/256), B), 256 threads (thread = patch).  lse given directly, or recomputed per
@@ -196,7 +214,7 @@ ns_status launch_cls_row(const ns_attn_desc &d, const void *q, const void *k, co
 ns_status launch_cls_combine(const ns_attn_desc &d, const float *partials, void *out, float *lse,
                              bool with_v, hipStream_t s) {
   const int nch = cls_num_chunks(d.tokens);
-  dim3 grid(d.heads, d.batch), blk(64);
+  dim3 grid(d.heads, d.batch), blk(256);
   if (d.dtype == NS_F32) {
     if (with_v)
       hipLaunchKernelGGL((cls_combine_kernel<float, true>), grid, blk, 0, s, partials, nch, d.heads,

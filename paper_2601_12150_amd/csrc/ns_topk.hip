@@ -22,6 +22,23 @@ __device__ __forceinline__ uint32_t order_key(float x) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// Adds the digits of the wave's candidate lanes to the wave's histogram.  Clustered scores put
+// most lanes of a wave into the same few bins, where one LDS atomic per lane would serialise;
+// so the first bins are peeled off with one add of a lane count each, and only what is left
+// (digits that are spread out, hence rarely colliding) goes through per-lane atomics.
+__device__ __forceinline__ void wave_histogram_add(uint32_t *h, bool cand, uint32_t digit, int lane) {
+  unsigned long long rem = __ballot(cand);
+#pragma unroll 1
+  for (int it = 0; it < 2 && rem; it++) {
+    const int leader = __ffsll((long long)rem) - 1;
+    const uint32_t d0 = (uint32_t)__builtin_amdgcn_readlane((int)digit, leader);
+    const unsigned long long same = __ballot(cand && digit == d0) & rem;
+    if (lane == leader) atomicAdd(&h[d0], (uint32_t)__popcll(same));
+    rem &= ~same;
+  }
+  if ((rem >> lane) & 1ull) atomicAdd(&h[digit], 1u);
+}
+
 __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(const float *scores, int N, int k,
                                                                   const int32_t *coords_in,
                                                                   int32_t *kept,
@@ -47,18 +64,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(const float *s
         cand = (key & mask) == prefix;
         digit = (key >> shift) & 255u;
       }
-      const unsigned long long act = __ballot(cand);
-      if (act) {
-        // clustered scores put whole waves into one bin: count those with a single add
-        const int leader = __ffsll((long long)act) - 1;
-        const uint32_t d0 = __shfl(digit, leader);
-        const unsigned long long same = __ballot(cand && digit == d0);
-        if (same == act) {
-          if (lane == leader) atomicAdd(&hist[wave][d0], (uint32_t)__popcll(act));
-        } else if (cand) {
-          atomicAdd(&hist[wave][digit], 1u);
-        }
-      }
+      wave_histogram_add(hist[wave], cand, digit, lane);
     }
     __syncthreads();
     // threads 0..255: bin totals, suffix sums (count of candidates with a larger digit)
@@ -125,6 +131,104 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(const float *s
   }
 }
 
+// Register-resident variant for N <= 1024 * KPT: every thread keeps its KPT keys in registers
+// (thread t holds indices i*1024 + t), so the selection and the compaction read global memory
+// exactly once and the step is a few microseconds of ALU work.
+template <int KPT>
+__global__ __launch_bounds__(kSelThreads) void topk_select_reg_kernel(const float *scores, int N, int k,
+                                                                      const int32_t *coords_in,
+                                                                      int32_t *kept,
+                                                                      int32_t *coords_out) {
+  const int b = blockIdx.x;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const float *sc = scores + (size_t)b * N;
+  __shared__ uint32_t wtot[2][kSelWaves];
+  __shared__ uint32_t pgt[KPT * kSelWaves], peq[KPT * kSelWaves];   // per (i, wave) counts -> prefixes
+  __shared__ uint32_t sgt[kSelWaves], seq[kSelWaves];
+
+  // Padding slots hold key 0.  A real key is never 0 (that would be a NaN bit pattern), and
+  // tau, the k-th largest real key, is therefore > 0: padding never passes "> tau" or "== tau".
+  uint32_t key[KPT];
+#pragma unroll
+  for (int i = 0; i < KPT; i++) {
+    const int j = i * kSelThreads + tid;
+    key[i] = j < N ? order_key(sc[j]) : 0u;
+  }
+  // k-th largest key by bisection on its bits, most significant first: tau keeps a bit iff at
+  // least k keys are >= the candidate.  A wave counts with one compare + one scalar popcount per
+  // key slot (no LDS atomics, cost independent of how the scores cluster); the 16 wave counts
+  // are exchanged through LDS, double-buffered so that one barrier per bit suffices.  (Measured:
+  // the step time is set by the compares of all N keys on this one CU; two bits per step, with
+  // three candidates, was slower.)
+  auto block_total = [&](uint32_t wave_count, int slot) -> uint32_t {
+    if (lane == 0) wtot[slot][wave] = wave_count;
+    __syncthreads();
+    uint32_t t = lane < kSelWaves ? wtot[slot][lane] : 0u;
+    // sum over lanes 0..15 (one DPP row): row_shr 1, 2, 4, 8 leaves the total in lane 15
+    t += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)t, 0x111, 0xf, 0xf, true);
+    t += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)t, 0x112, 0xf, 0xf, true);
+    t += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)t, 0x114, 0xf, 0xf, true);
+    t += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)t, 0x118, 0xf, 0xf, true);
+    return (uint32_t)__builtin_amdgcn_readlane((int)t, 15);
+  };
+  uint32_t tau = 0;
+  for (int bit = 31; bit >= 0; bit--) {
+    const uint32_t cand = tau | (1u << bit);
+    uint32_t c = 0;   // wave-uniform: lives in a scalar register
+#pragma unroll
+    for (int i = 0; i < KPT; i++) c += (uint32_t)__popcll(__ballot(key[i] >= cand));   // padding keys are 0 < cand
+    if (block_total(c, bit & 1) >= (uint32_t)k) tau = cand;
+  }
+  uint32_t cg = 0;
+#pragma unroll
+  for (int i = 0; i < KPT; i++) cg += (uint32_t)__popcll(__ballot(key[i] > tau));
+  // every score above tau is kept; of those equal to it, the first `need` in index order
+  const uint32_t need = (uint32_t)k - block_total(cg, 1);   // slot 1: slot 0 may still be read (bit 0)
+  // index order = (i, wave, lane); count per (i, wave), scan, then place
+#pragma unroll
+  for (int i = 0; i < KPT; i++) {
+    const unsigned long long bgt = __ballot(key[i] > tau);
+    const unsigned long long beq = __ballot(key[i] == tau);
+    if (lane == 0) {
+      pgt[i * kSelWaves + wave] = (uint32_t)__popcll(bgt);
+      peq[i * kSelWaves + wave] = (uint32_t)__popcll(beq);
+    }
+  }
+  __syncthreads();
+  {
+    // block-wide exclusive scan of the KPT*16 (<= 1024) counts: thread t owns entry t
+    const bool own = tid < KPT * kSelWaves;
+    const uint32_t g = own ? pgt[tid] : 0u, e = own ? peq[tid] : 0u;
+    uint32_t ig = g, ie = e;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const uint32_t tg = __shfl_up(ig, off), te = __shfl_up(ie, off);
+      if (lane >= off) { ig += tg; ie += te; }
+    }
+    if (lane == 63) { sgt[wave] = ig; seq[wave] = ie; }
+    __syncthreads();
+    uint32_t bg = 0, be = 0;
+    for (int w = 0; w < wave; w++) { bg += sgt[w]; be += seq[w]; }
+    if (own) { pgt[tid] = bg + ig - g; peq[tid] = be + ie - e; }
+    __syncthreads();
+  }
+  int32_t *kb = kept + (size_t)b * k;
+  const unsigned long long lt = (1ull << lane) - 1ull;
+#pragma unroll
+  for (int i = 0; i < KPT; i++) {
+    const int j = i * kSelThreads + tid;
+    const bool gt = key[i] > tau, eq = key[i] == tau;
+    const unsigned long long bgt = __ballot(gt), beq = __ballot(eq);
+    const uint32_t my_gt = pgt[i * kSelWaves + wave] + (uint32_t)__popcll(bgt & lt);
+    const uint32_t my_eq = peq[i * kSelWaves + wave] + (uint32_t)__popcll(beq & lt);
+    if (gt || (eq && my_eq < need)) {
+      const uint32_t pos = my_gt + min(my_eq, need);
+      kb[pos] = j;
+      if (coords_in) coords_out[(size_t)b * k + pos] = coords_in[(size_t)b * N + j];
+    }
+  }
+}
+
 // grid (ceil((1+k)/4), B), 256 threads: one wave per output row.
 __global__ __launch_bounds__(256) void gather_rows_kernel(const uint4 *x, const int32_t *kept,
                                                           uint4 *y, int N, int k, int vec_per_row) {
@@ -141,8 +245,15 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const uint4 *x, const 
 
 ns_status launch_topk_select(int B, int N, int k, const float *scores, const int32_t *coords_in,
                              int32_t *kept, int32_t *coords_out, hipStream_t s) {
-  hipLaunchKernelGGL(topk_select_kernel, dim3(B), dim3(kSelThreads), 0, s, scores, N, k, coords_in,
-                     kept, coords_out);
+  if (N <= 16 * kSelThreads)
+    hipLaunchKernelGGL(topk_select_reg_kernel<16>, dim3(B), dim3(kSelThreads), 0, s, scores, N, k,
+                       coords_in, kept, coords_out);
+  else if (N <= 64 * kSelThreads)
+    hipLaunchKernelGGL(topk_select_reg_kernel<64>, dim3(B), dim3(kSelThreads), 0, s, scores, N, k,
+                       coords_in, kept, coords_out);
+  else
+    hipLaunchKernelGGL(topk_select_kernel, dim3(B), dim3(kSelThreads), 0, s, scores, N, k, coords_in,
+                       kept, coords_out);
   return check_launch("topk_select_kernel");
 }
 
