@@ -1,6 +1,7 @@
 // C ABI of libnsattn.so: host-side validation and kernel dispatch.  No kernel lives here.
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 
 #include "ns_common.h"
 
@@ -119,6 +120,17 @@ size_t ns_attn_workspace_bytes(const ns_attn_desc *desc) {
   return attn_workspace_layout(*desc).total;
 }
 
+// Kernel choice for the patch queries.
+static ns_status launch_patch_attention(const AttnArgs &a) {
+  // NSATTN_KERNEL=persist selects the persistent-wave variant of the MFMA kernel (same results)
+  const char *e = getenv("NSATTN_KERNEL");
+  if (mfma_attn_supported(a.d)) {
+    if (e && e[0] == 'p' && persist_attn_supported(a.d)) return launch_attn_persist(a);
+    return launch_attn_mfma(a);
+  }
+  return launch_attn_generic(a);
+}
+
 // Shared by ns_attn_forward and the timing aid: validation, workspace carving, block lists.
 static ns_status prepare_attn(const ns_attn_desc *desc, const void *q, const void *k, const void *v,
                               void *out, void *workspace, size_t workspace_bytes, void *stream,
@@ -163,7 +175,7 @@ ns_status ns_attn_forward(const ns_attn_desc *desc, const void *q, const void *k
   ns_status st = prepare_attn(desc, q, k, v, out, workspace, workspace_bytes, stream, a, partials);
   if (st != NS_OK) return st;
   const ns_attn_desc &d = a.d;
-  st = mfma_attn_supported(d) ? launch_attn_mfma(a) : launch_attn_generic(a);
+  st = launch_patch_attention(a);
   if (st != NS_OK) return st;
   // the global query's row: chunk partials, then the merge that also writes out[:, :, 0, :]
   st = launch_cls_row(d, q, k, v, cls_logits, partials, true, a.stream);
@@ -183,9 +195,8 @@ ns_status ns_attn_patch_kernel_time(const ns_attn_desc *desc, const void *q, con
   hipEvent_t e0, e1;
   if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
     return fail(NS_ERR_HIP, "hipEventCreate failed");
-  const bool mfma = mfma_attn_supported(a.d);
   hipEventRecord(e0, a.stream);
-  for (int i = 0; i < reps && st == NS_OK; i++) st = mfma ? launch_attn_mfma(a) : launch_attn_generic(a);
+  for (int i = 0; i < reps && st == NS_OK; i++) st = launch_patch_attention(a);
   hipEventRecord(e1, a.stream);
   hipError_t e = hipEventSynchronize(e1);
   float ms = 0.f;

@@ -75,6 +75,8 @@ ns_status launch_block_lists(const ns_attn_desc &d, int32_t *lists, int32_t *cou
 ns_status launch_attn_generic(const AttnArgs &a);
 bool mfma_attn_supported(const ns_attn_desc &d);
 ns_status launch_attn_mfma(const AttnArgs &a);
+bool persist_attn_supported(const ns_attn_desc &d);
+ns_status launch_attn_persist(const AttnArgs &a);
 
 // global-query (CLS) row: per-chunk partials, then a combine.
 constexpr int kClsChunk = 512;                      // keys per workgroup of the row kernel

@@ -117,3 +117,20 @@ def test_invalid_call_launches_nothing(nb):
     assert e.value.code == nb.NS_ERR_INVALID_ARG
     torch.cuda.synchronize()
     assert bool((out == 7.0).all())
+
+
+@pytest.mark.parametrize("gh,gw,block", [(24, 40, 8), (8, 8, 8), (32, 32, 16), (48, 48, 8), (64, 64, 8)])
+def test_persistent_kernel_variant(nb, gh, gw, block, monkeypatch):
+    # the alternative persistent-wave kernel computes the same function
+    monkeypatch.setenv("NSATTN_KERNEL", "persist")
+    run_case(nb, 303, 2, 5, gh, gw, block, "bf16")
+
+
+def test_persistent_kernel_variant_overflow_fallback(nb, monkeypatch):
+    monkeypatch.setenv("NSATTN_KERNEL", "persist")
+    q, k, v = synth.small_case(7, 1, 2, 64, 16, 16, "bf16")
+    q = synth.round_to_bf16(q * 12.0)
+    ref = oracle.ns_attn(q, k, v, 16, 16, 8, 1.0)
+    out = nb.ns_attn_forward(*(to_dev(a, "bf16") for a in (q, k, v)), 16, 16, 8, 1.0)
+    torch.cuda.synchronize()
+    assert_attn_close(to_np(out), ref, "bf16", "large logits, persistent kernel")
