@@ -1,0 +1,49 @@
+"""CPU oracle of one pre-LayerNorm transformer block around the sparse attention
+(test infrastructure, not product code).
+
+    h = x + Wproj * Attn(LN1(x)) + bproj;   y = h + W2 * gelu(W1 * LN2(h) + b1) + b2
+
+Textbook definitions in float64: LayerNorm over the channel axis with biased variance, exact
+(erf) GELU, y = x W^T + b linear maps; the attention and the importance scores are the C
+oracle's (paper, Methodology: sparse attention inside the backbone's attention layers, pruning
+scores from the global token's attention weights).  Nothing is rounded between the steps.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+from . import cls_scores, ns_attn
+
+_erf = np.vectorize(math.erf, otypes=[np.float64])
+
+
+def layer_norm(x, gamma, beta, eps):
+    mu = x.mean(axis=-1, keepdims=True)
+    var = ((x - mu) ** 2).mean(axis=-1, keepdims=True)
+    return (x - mu) / np.sqrt(var + eps) * gamma + beta
+
+
+def gelu(x):
+    return 0.5 * x * (1.0 + _erf(x / math.sqrt(2.0)))
+
+
+def vit_block(x, w, grid_h, grid_w, block, heads, ln_eps=1e-6, scale=None, coords=None, want_scores=False):
+    """x [B,T,dim]; w: dict of numpy arrays named as in the C ABI's ns_vit_block_weights."""
+    x = np.asarray(x, dtype=np.float64)
+    B, T, dim = x.shape
+    D = dim // heads
+    scale = D ** -0.5 if scale is None else scale
+    f = {k: np.asarray(v, dtype=np.float64) for k, v in w.items()}
+    a = layer_norm(x, f["ln1_g"], f["ln1_b"], ln_eps)
+    qkv = a @ f["w_qkv"].T + f["b_qkv"]                       # [B,T,3*dim], rows q | k | v
+    q, k, v = (qkv[..., i * dim:(i + 1) * dim].reshape(B, T, heads, D).transpose(0, 2, 1, 3) for i in range(3))
+    att = ns_attn(q, k, v, grid_h, grid_w, block, scale, coords=coords)       # [B,H,T,D]
+    att = att.transpose(0, 2, 1, 3).reshape(B, T, dim)
+    h = x + att @ f["w_proj"].T + f["b_proj"]
+    m = gelu(layer_norm(h, f["ln2_g"], f["ln2_b"], ln_eps) @ f["w_fc1"].T + f["b_fc1"])
+    y = h + m @ f["w_fc2"].T + f["b_fc2"]
+    if want_scores:
+        return y, cls_scores(q, k, scale)
+    return y

@@ -244,3 +244,46 @@ def topk_filter(scores, k, x=None, coords=None, kept_idx=None, y=None, coords_ou
                            _ptr(y), _ptr(coords_out), _ptr(ws), 0 if ws is None else ws.numel(),
                            _stream(stream)))
     return kept_idx, y, coords_out
+
+
+WEIGHT_NAMES = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_proj", "b_proj", "ln2_g", "ln2_b",
+                "w_fc1", "b_fc1", "w_fc2", "b_fc2")
+
+
+def vit_block_forward(x, weights, grid_h, grid_w, block, heads, ln_eps=1e-6, scale=None, coords=None,
+                      want_scores=False, out=None, workspace=None, stream=None):
+    """One pre-LayerNorm transformer block around the sparse attention.
+
+    x [B,T,dim] bf16 contiguous; weights: dict of device tensors (matrices bf16 [out,in], vectors
+    fp32).  Returns x_out [B,T,dim] (and the importance scores [B,T-1] with want_scores)."""
+    if x.dtype != torch.bfloat16 or not x.is_contiguous():
+        raise ValueError("x must be a contiguous bfloat16 tensor [B,T,dim]")
+    B, T, dim = x.shape
+    for n in WEIGHT_NAMES:
+        t = weights[n]
+        want = torch.bfloat16 if n.startswith("w_") else torch.float32
+        if t.dtype != want or not t.is_contiguous() or t.device != x.device:
+            raise ValueError("weight %s must be a contiguous %s tensor on %s" % (n, want, x.device))
+    mlp = weights["w_fc1"].shape[0]
+    d = ns_vit_block_desc()
+    a = d.attn
+    a.batch, a.heads, a.head_dim = B, heads, dim // heads
+    a.grid_h, a.grid_w, a.block, a.radius, a.n_global = grid_h, grid_w, block, 1, 1
+    a.dtype, a.tokens = NS_BF16, T
+    a.scale = float(dim // heads) ** -0.5 if scale is None else float(scale)
+    if coords is not None:
+        if coords.dtype != torch.int32 or not coords.is_contiguous():
+            raise ValueError("coords must be a contiguous int32 tensor [B, T-1]")
+        a.coords = coords.data_ptr()
+    d.dim, d.mlp_dim, d.ln_eps = dim, mlp, float(ln_eps)
+    w = ns_vit_block_weights()
+    for n in WEIGHT_NAMES:
+        setattr(w, n, weights[n].data_ptr())
+    if out is None:
+        out = torch.empty_like(x)
+    scores = torch.empty((B, T - 1), dtype=torch.float32, device=x.device) if want_scores else None
+    nbytes = lib.vit_block_workspace_bytes(ctypes.byref(d))
+    ws = _workspace(max(nbytes, 1), x.device, workspace)
+    _check(lib.vit_block_forward(ctypes.byref(d), ctypes.byref(w), _ptr(x), _ptr(out), _ptr(scores), _ptr(ws),
+                                 ws.numel(), _stream(stream)))
+    return (out, scores) if want_scores else out

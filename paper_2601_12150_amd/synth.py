@@ -158,3 +158,24 @@ def raster_coords(grid_h: int, grid_w: int) -> np.ndarray:
     """Packed (r << 16 | c) of every patch of the full grid, raster order: [grid_h*grid_w] int32."""
     r, c = np.divmod(np.arange(grid_h * grid_w, dtype=np.int64), grid_w)
     return ((r << 16) | c).astype(np.int32)
+
+
+def make_block_weights(dim: int, mlp_dim: int, seed: int = 0, dtype: str = "bf16", ln_random: bool = False):
+    """Random-init weights of one transformer block: matrices ~N(0, 0.02^2) (rounded to `dtype`),
+    biases ~N(0, 0.02^2) fp32 (zero-init biases would hide a dropped bias), LayerNorm gamma=1, beta=0
+    (or random with ln_random, for tests).  Names as in the C ABI's ns_vit_block_weights."""
+    g = _rng(seed, 70)
+    def mat(o, i):
+        return _finish(np.float32(0.02) * g.standard_normal((o, i), dtype=np.float32), dtype)
+    def vec(n):
+        return (np.float32(0.02) * g.standard_normal(n, dtype=np.float32)).astype(np.float32)
+    w = {"w_qkv": mat(3 * dim, dim), "b_qkv": vec(3 * dim), "w_proj": mat(dim, dim), "b_proj": vec(dim),
+         "w_fc1": mat(mlp_dim, dim), "b_fc1": vec(mlp_dim), "w_fc2": mat(dim, mlp_dim), "b_fc2": vec(dim)}
+    for n in ("ln1", "ln2"):
+        if ln_random:
+            w[n + "_g"] = (1.0 + 0.1 * g.standard_normal(dim)).astype(np.float32)
+            w[n + "_b"] = (0.1 * g.standard_normal(dim)).astype(np.float32)
+        else:
+            w[n + "_g"] = np.ones(dim, dtype=np.float32)
+            w[n + "_b"] = np.zeros(dim, dtype=np.float32)
+    return w

@@ -1,0 +1,41 @@
+"""Pin for the transformer-block oracle: with at most two blocks per side the sparse attention
+is dense attention, and the block must equal a textbook pre-LN block assembled from library
+routines (torch LayerNorm / linear / GELU / scaled_dot_product_attention in float64)."""
+import numpy as np
+import torch
+import torch.nn.functional as F
+
+from oracle import vit_block as ov
+from paper_2601_12150_amd import synth
+
+
+def test_block_equals_library_pre_ln_block_when_attention_is_dense():
+    rng = np.random.default_rng(3)
+    B, g, heads, D, mlp = 2, 6, 3, 8, 40
+    dim, T = heads * D, 1 + g * g
+    x = rng.standard_normal((B, T, dim))
+    w = synth.make_block_weights(dim, mlp, seed=5, dtype="f32", ln_random=True)
+    y, scores = ov.vit_block(x, w, g, g, 3, heads, ln_eps=1e-5, want_scores=True)
+
+    t = {k: torch.from_numpy(np.asarray(v, dtype=np.float64)) for k, v in w.items()}
+    tx = torch.from_numpy(x)
+    a = F.layer_norm(tx, (dim,), t["ln1_g"], t["ln1_b"], 1e-5)
+    qkv = F.linear(a, t["w_qkv"], t["b_qkv"]).reshape(B, T, 3, heads, D).permute(2, 0, 3, 1, 4)
+    att = F.scaled_dot_product_attention(qkv[0], qkv[1], qkv[2])
+    h = tx + F.linear(att.permute(0, 2, 1, 3).reshape(B, T, dim), t["w_proj"], t["b_proj"])
+    m = F.gelu(F.linear(F.layer_norm(h, (dim,), t["ln2_g"], t["ln2_b"], 1e-5), t["w_fc1"], t["b_fc1"]))
+    ref = h + F.linear(m, t["w_fc2"], t["b_fc2"])
+    # the C attention oracle takes q, k, v as float32: that rounding (6e-8 relative) is the only difference
+    np.testing.assert_allclose(y, ref.numpy(), rtol=0, atol=1e-9)
+    p = torch.softmax(qkv[0][:, :, 0:1] @ qkv[1].transpose(-1, -2) * D ** -0.5, dim=-1)[:, :, 0, 1:].mean(dim=1)
+    np.testing.assert_allclose(scores, p.numpy(), rtol=0, atol=1e-10)
+
+
+def test_layer_norm_and_gelu_special_values():
+    x = np.array([[1.0, 2.0, 3.0, 6.0]])
+    out = ov.layer_norm(x, np.ones(4), np.zeros(4), 0.0)
+    np.testing.assert_allclose(out.mean(), 0.0, atol=1e-15)
+    np.testing.assert_allclose((out ** 2).mean(), 1.0, atol=1e-14)
+    np.testing.assert_allclose(ov.gelu(np.array([0.0, 1e3, -1e3])), [0.0, 1e3, 0.0], atol=1e-12)
+    # gelu(1) = 0.5 * (1 + erf(1/sqrt 2)) = Phi(1)
+    np.testing.assert_allclose(ov.gelu(np.array([1.0])), [0.8413447460685429], atol=1e-15)
