@@ -168,6 +168,31 @@ ns_status vit_block_forward(const ns_vit_block_desc *desc, const ns_vit_block_we
                             size_t workspace_bytes, void *stream);
 
 /*
+ * A stack of `layers` such blocks with one pruning stage (paper, "Time-Efficiency Optimization":
+ * the pruning is applied once, after several initial layers, and shortens the sequence for all
+ * subsequent layers).  Blocks 0 .. prune_after-1 run on the full grid; the importance scores of
+ * block prune_after-1's attention select keep_k patches per image (topk_filter); the remaining
+ * blocks run on [CLS; kept patches] with the mask evaluated on the kept patches' original grid
+ * positions.  prune_after == 0 or keep_k == 0 disables pruning.
+ *   block       shape of every block; block.attn describes the full grid (coords must be NULL)
+ *   weights     HOST array [layers] of per-block device weight pointers
+ *   x_in   in   [B, T, dim] bf16
+ *   x_out  out  [B, 1 + keep_k, dim] bf16 with pruning, else [B, T, dim]
+ *   kept_idx out, nullable [B, keep_k] int32: the kept patch indices, ascending
+ */
+typedef struct ns_vit_desc {
+  ns_vit_block_desc block;
+  int32_t layers;
+  int32_t prune_after;
+  int32_t keep_k;
+} ns_vit_desc;
+
+size_t vit_workspace_bytes(const ns_vit_desc *desc);
+ns_status vit_forward(const ns_vit_desc *desc, const ns_vit_block_weights *weights, const void *x_in,
+                      void *x_out, int32_t *kept_idx, void *workspace, size_t workspace_bytes,
+                      void *stream);
+
+/*
  * Measurement aid for benchmarks (not part of the method): enqueues `reps` launches of the
  * patch-query attention kernel alone (the dominant kernel of ns_attn_forward; no CLS row)
  * on `stream`, bracketed by HIP events recorded on that stream, WAITS for them, and stores

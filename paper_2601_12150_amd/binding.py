@@ -21,7 +21,8 @@ NS_F32, NS_BF16 = 0, 1
 
 EXPORTS = ["ns_attn_workspace_bytes", "ns_attn_forward", "cls_scores_workspace_bytes", "cls_scores",
            "cls_scores_from_logits", "topk_filter_workspace_bytes", "topk_filter",
-           "vit_block_workspace_bytes", "vit_block_forward", "ns_attn_patch_kernel_time", "ns_last_error",
+           "vit_block_workspace_bytes", "vit_block_forward", "vit_workspace_bytes", "vit_forward",
+           "ns_attn_patch_kernel_time", "ns_last_error",
            "ns_version"]
 
 
@@ -51,6 +52,11 @@ class ns_vit_block_weights(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in
                 ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_proj", "b_proj", "ln2_g", "ln2_b",
                  "w_fc1", "b_fc1", "w_fc2", "b_fc2")]
+
+
+class ns_vit_desc(ctypes.Structure):
+    _fields_ = [("block", ns_vit_block_desc), ("layers", ctypes.c_int32), ("prune_after", ctypes.c_int32),
+                ("keep_k", ctypes.c_int32)]
 
 
 def _load() -> ctypes.CDLL:
@@ -83,6 +89,11 @@ def _load() -> ctypes.CDLL:
     lib.vit_block_forward.restype = ctypes.c_int
     lib.vit_block_forward.argtypes = [ctypes.POINTER(ns_vit_block_desc),
                                       ctypes.POINTER(ns_vit_block_weights), vp, vp, vp, vp, sz, vp]
+    lib.vit_workspace_bytes.restype = sz
+    lib.vit_workspace_bytes.argtypes = [ctypes.POINTER(ns_vit_desc)]
+    lib.vit_forward.restype = ctypes.c_int
+    lib.vit_forward.argtypes = [ctypes.POINTER(ns_vit_desc), ctypes.POINTER(ns_vit_block_weights), vp, vp, vp, vp,
+                                sz, vp]
     lib.ns_last_error.restype = ctypes.c_char_p
     lib.ns_version.restype = ctypes.c_char_p
     return lib
@@ -287,3 +298,39 @@ def vit_block_forward(x, weights, grid_h, grid_w, block, heads, ln_eps=1e-6, sca
     _check(lib.vit_block_forward(ctypes.byref(d), ctypes.byref(w), _ptr(x), _ptr(out), _ptr(scores), _ptr(ws),
                                  ws.numel(), _stream(stream)))
     return (out, scores) if want_scores else out
+
+
+def vit_forward(x, layer_weights, grid_h, grid_w, block, heads, prune_after=0, keep_k=0, ln_eps=1e-6,
+                scale=None, out=None, workspace=None, stream=None):
+    """A stack of blocks with one pruning stage after block `prune_after` (keep_k patches kept).
+
+    x [B,T,dim] bf16; layer_weights: list of weight dicts (see vit_block_forward).
+    Returns (x_out [B, 1+keep_k or T, dim], kept_idx [B,keep_k] or None)."""
+    if x.dtype != torch.bfloat16 or not x.is_contiguous():
+        raise ValueError("x must be a contiguous bfloat16 tensor [B,T,dim]")
+    B, T, dim = x.shape
+    d = ns_vit_desc()
+    a = d.block.attn
+    a.batch, a.heads, a.head_dim = B, heads, dim // heads
+    a.grid_h, a.grid_w, a.block, a.radius, a.n_global = grid_h, grid_w, block, 1, 1
+    a.dtype, a.tokens = NS_BF16, T
+    a.scale = float(dim // heads) ** -0.5 if scale is None else float(scale)
+    d.block.dim, d.block.mlp_dim, d.block.ln_eps = dim, layer_weights[0]["w_fc1"].shape[0], float(ln_eps)
+    d.layers, d.prune_after, d.keep_k = len(layer_weights), int(prune_after), int(keep_k)
+    warr = (ns_vit_block_weights * len(layer_weights))()
+    for i, lw in enumerate(layer_weights):
+        for n in WEIGHT_NAMES:
+            t = lw[n]
+            want = torch.bfloat16 if n.startswith("w_") else torch.float32
+            if t.dtype != want or not t.is_contiguous() or t.device != x.device:
+                raise ValueError("layer %d weight %s must be a contiguous %s tensor on %s" % (i, n, want, x.device))
+            setattr(warr[i], n, t.data_ptr())
+    pruning = prune_after > 0 and keep_k > 0
+    if out is None:
+        out = torch.empty((B, 1 + keep_k if pruning else T, dim), dtype=x.dtype, device=x.device)
+    kept = torch.empty((B, keep_k), dtype=torch.int32, device=x.device) if pruning else None
+    nbytes = lib.vit_workspace_bytes(ctypes.byref(d))
+    ws = _workspace(max(nbytes, 1), x.device, workspace)
+    _check(lib.vit_forward(ctypes.byref(d), warr, _ptr(x), _ptr(out), _ptr(kept), _ptr(ws), ws.numel(),
+                           _stream(stream)))
+    return out, kept

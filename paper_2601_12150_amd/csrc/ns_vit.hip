@@ -257,6 +257,46 @@ ns_status block_attn_desc(const ns_vit_block_desc *d, ns_attn_desc &ad) {
   return NS_OK;
 }
 
+// coords[b][j] = (r << 16 | c) of patch j of the full raster grid
+__global__ __launch_bounds__(256) void raster_coords_kernel(int32_t *coords, int n, int grid_w) {
+  const int j = blockIdx.x * 256 + threadIdx.x;
+  if (j < n) coords[(size_t)blockIdx.y * n + j] = ((j / grid_w) << 16) | (j % grid_w);
+}
+
+struct StackWorkspace {
+  size_t xa, xb, scores, kept, coords_in, coords_out, block_ws, total;
+};
+
+StackWorkspace stack_layout(const ns_vit_desc &d, size_t block_ws_bytes) {
+  StackWorkspace w;
+  const ns_attn_desc &a = d.block.attn;
+  const size_t xbytes = (size_t)a.batch * a.tokens * d.block.dim * 2, N = (size_t)a.tokens - a.n_global;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
+  w.xa = take(xbytes);
+  w.xb = take(xbytes);
+  w.scores = take((size_t)a.batch * N * 4);
+  w.kept = take((size_t)a.batch * N * 4);
+  w.coords_in = take((size_t)a.batch * N * 4);
+  w.coords_out = take((size_t)a.batch * N * 4);
+  w.block_ws = off;
+  off += align_up(block_ws_bytes, 256);
+  w.total = off;
+  return w;
+}
+
+ns_status check_stack(const ns_vit_desc *d, bool &prune) {
+  if (!d) return fail(NS_ERR_INVALID_ARG, "descriptor is NULL");
+  if (d->layers < 1) return fail(NS_ERR_INVALID_ARG, "layers must be positive");
+  if (d->block.attn.coords) return fail(NS_ERR_INVALID_ARG, "the stack starts from the full grid: attn.coords must be NULL");
+  prune = d->prune_after > 0 && d->keep_k > 0;
+  if (d->prune_after < 0 || d->prune_after > d->layers) return fail(NS_ERR_INVALID_ARG, "prune_after out of range");
+  if (prune && d->keep_k > d->block.attn.tokens - d->block.attn.n_global)
+    return fail(NS_ERR_INVALID_ARG, "keep_k exceeds the number of patches");
+  if (d->keep_k < 0) return fail(NS_ERR_INVALID_ARG, "keep_k must not be negative");
+  return NS_OK;
+}
+
 }  // namespace
 }  // namespace ns
 
@@ -319,6 +359,68 @@ ns_status vit_block_forward(const ns_vit_block_desc *desc, const ns_vit_block_we
   st = launch_gemm(ln, static_cast<const uint16_t *>(w->w_fc1), w->b_fc1, nullptr, hid, M, mlp, dim, true, s);
   if (st != NS_OK) return st;
   return launch_gemm(hid, static_cast<const uint16_t *>(w->w_fc2), w->b_fc2, h, y, M, dim, mlp, false, s);
+}
+
+}  // extern "C"
+
+extern "C" {
+
+size_t vit_workspace_bytes(const ns_vit_desc *desc) {
+  bool prune;
+  if (check_stack(desc, prune) != NS_OK) return 0;
+  const size_t bw = vit_block_workspace_bytes(&desc->block);   // the full grid needs the most
+  if (bw == 0) return 0;
+  return stack_layout(*desc, bw).total;
+}
+
+ns_status vit_forward(const ns_vit_desc *desc, const ns_vit_block_weights *weights, const void *x_in,
+                      void *x_out, int32_t *kept_idx, void *workspace, size_t workspace_bytes,
+                      void *stream) {
+  bool prune;
+  ns_status st = check_stack(desc, prune);
+  if (st != NS_OK) return st;
+  const size_t bw = vit_block_workspace_bytes(&desc->block);
+  if (bw == 0) return NS_ERR_INVALID_ARG;   // message set by the block validation
+  if (!weights || !x_in || !x_out) return fail(NS_ERR_INVALID_ARG, "weights, x_in and x_out must not be NULL");
+  const StackWorkspace L = stack_layout(*desc, bw);
+  if (!workspace) return fail(NS_ERR_WORKSPACE, "workspace is NULL, %zu bytes needed", L.total);
+  if (reinterpret_cast<uintptr_t>(workspace) % 256) return fail(NS_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+  if (workspace_bytes < L.total) return fail(NS_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, L.total);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  unsigned char *ws = static_cast<unsigned char *>(workspace);
+  void *buf[2] = {ws + L.xa, ws + L.xb};
+  float *scores = reinterpret_cast<float *>(ws + L.scores);
+  int32_t *kept = kept_idx ? kept_idx : reinterpret_cast<int32_t *>(ws + L.kept);
+  int32_t *cin = reinterpret_cast<int32_t *>(ws + L.coords_in), *cout = reinterpret_cast<int32_t *>(ws + L.coords_out);
+
+  ns_vit_block_desc bd = desc->block;
+  const ns_attn_desc full = desc->block.attn;
+  const int N = full.tokens - full.n_global;
+  const void *cur = x_in;
+  int flip = 0;
+  for (int l = 0; l < desc->layers; l++) {
+    const bool last = l + 1 == desc->layers, scoring = prune && l + 1 == desc->prune_after;
+    // the last block writes x_out directly unless the pruning stage still follows it
+    void *dst = (last && !scoring) ? x_out : buf[flip];
+    st = vit_block_forward(&bd, &weights[l], cur, dst, scoring ? scores : nullptr, ws + L.block_ws, bw, s);
+    if (st != NS_OK) return st;
+    cur = dst;
+    flip ^= 1;
+    if (scoring) {
+      dim3 grid((N + 255) / 256, full.batch);
+      hipLaunchKernelGGL(raster_coords_kernel, grid, dim3(256), 0, s, cin, N, full.grid_w);
+      st = check_launch("raster_coords_kernel");
+      if (st != NS_OK) return st;
+      void *y = last ? x_out : buf[flip];
+      st = topk_filter(full.batch, N, desc->keep_k, scores, cur, bd.dim, NS_BF16, cin, kept, y, cout, nullptr, 0, s);
+      if (st != NS_OK) return st;
+      cur = y;
+      flip ^= 1;
+      bd.attn.tokens = full.n_global + desc->keep_k;
+      bd.attn.coords = cout;
+    }
+  }
+  return NS_OK;
 }
 
 }  // extern "C"
