@@ -49,6 +49,9 @@ def main() -> int:
                     help="also run one plain copy of known size (the row-gather kernel with every row kept) "
                          "so that byte counters of a profiler can be scaled")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target duration of the oracle sample")
+    ap.add_argument("--vit", action="store_true",
+                    help="also time the 24-layer ViT-L/16-shaped stack (dim 1024, MLP 4096, 128x128 grid, B=1, "
+                         "pruning to 60 %% after layer 12) and report it under stages")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -158,8 +161,15 @@ def main() -> int:
 
     stages = None
     cpu = None
+    n_sets = len(sets)
     if not args.no_stages:
         stages = measure_stages(nb, torch, sets, cfg, g, blk, k, C, B, H, T, D, ws, desc0, flops_layer)
+    if args.vit:
+        stages = dict(stages or {})
+        n_sets = len(sets)
+        sets.clear()
+        torch.cuda.empty_cache()
+        stages.update(measure_vit_stack(nb, torch, np, synth))
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(np, cfg, q, kk, v, g, blk, k, B, H, T, args.cpu_seconds)
 
@@ -170,7 +180,7 @@ def main() -> int:
                                   "neighbourhood, keep %d%% (k=%d)" % (cfg.name, B, g, g, T, H, D, blk, blk,
                                                                         cfg.keep_pct, k),
                       "step": "ns_attn_forward + cls_scores_from_logits + topk_filter(select+gather)",
-                      "input_sets_rotated": len(sets),
+                      "input_sets_rotated": n_sets,
                       "background_fraction": info.get("background_fraction")},
            "roofline": roofline, "cpu_baseline": cpu, "stages": stages}
     print(json.dumps(out))
@@ -210,6 +220,36 @@ def measure_stages(nb, torch, sets, cfg, g, blk, k, C, B, H, T, D, ws, desc0, fl
         "gather_GBps": bytes_gather / max(t_filter - t_select, 1e-9) / 1e9,
         "hbm_peak_GBps": PEAK_HBM / 1e9,
     }
+
+
+def measure_vit_stack(nb, torch, np, synth, layers=24, dim=1024, mlp=4096, heads=16, g=128, blk=8, after=12):
+    """24 pre-LN blocks on [1, 1+128*128, 1024] bf16 tokens, pruning to 60 % after block 12.  Weights are
+    random (N(0, 0.02^2)); one set is generated and uploaded per layer.  The input tokens are synthetic
+    N(0,1) embeddings (the patch embedding itself is not part of this build)."""
+    N = g * g
+    keep = (N * 60 + 99) // 100
+    ws = []
+    for i in range(layers):
+        w = synth.make_block_weights(dim, mlp, seed=100 + i)
+        ws.append({kk: (torch.from_numpy(vv).to(torch.bfloat16) if kk.startswith("w_") else torch.from_numpy(vv)).cuda()
+                   for kk, vv in w.items()})
+    x = torch.randn(1, 1 + N, dim, device="cuda").to(torch.bfloat16)
+    import ctypes
+    out = torch.empty((1, 1 + keep, dim), dtype=torch.bfloat16, device="cuda")
+    wsb = torch.empty(6 << 30, dtype=torch.uint8, device="cuda")
+    for _ in range(2):
+        nb.vit_forward(x, ws, g, g, blk, heads, prune_after=after, keep_k=keep, out=out, workspace=wsb)
+    torch.cuda.synchronize()
+    n = 5
+    t = time.perf_counter()
+    for _ in range(n):
+        nb.vit_forward(x, ws, g, g, blk, heads, prune_after=after, keep_k=keep, out=out, workspace=wsb)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t) / n
+    per_tok = 2.0 * dim * (3 * dim + dim + 2 * mlp)
+    gemm_flops = per_tok * ((1 + N) * after + (1 + keep) * (layers - after))
+    return {"vit_l24_forward_ms": dt * 1e3, "vit_l24_tokens_per_s": (1 + N) / dt,
+            "vit_l24_gemm_tflops_if_all_gemm": gemm_flops / dt / 1e12, "vit_l24_kept": keep}
 
 
 def cpu_baseline(np, cfg, q, kk, v, g, blk, k, B, H, T, seconds):
