@@ -128,6 +128,8 @@ static ns_status launch_patch_attention(const AttnArgs &a) {
     if (e && e[0] == 'p' && persist_attn_supported(a.d)) return launch_attn_persist(a);
     return launch_attn_mfma(a);
   }
+  // NSATTN_KERNEL=generic keeps the fp32 FMA kernel for a pruned sequence
+  if (ragged_attn_supported(a.d) && a.geom.lists && !(e && e[0] == 'g')) return launch_attn_ragged(a);
   return launch_attn_generic(a);
 }
 

@@ -1,0 +1,295 @@
+// bf16 MFMA neighbourhood attention for patch queries of a PRUNED sequence (gfx950), blocks of at
+// most 8x8 tokens.
+//
+// After pruning (paper, "Time-Efficiency Optimization") the sequence is [CLS; surviving patches] and
+// the mask is still defined on the survivors' original grid positions (paper, "Memory-Efficiency
+// Optimization": adjacency "in the original pixel space").  block_lists_kernel has bucketed the
+// survivors by block; a block of side b <= 8 holds at most 64 of them, so every (query block, key
+// block) pair is one MFMA tile with the rows beyond the block's fill masked.
+//
+// Same register formulation as ns_attn_mfma.hip: S^T = K Q^T and O^T += V^T P^T with
+// v_mfma_f32_32x32x16_bf16, P kept in registers, K fragments gathered straight from global memory
+// (one row address per lane), V gathered global -> LDS with direct 16-byte transfers and read
+// transposed with ds_read_b64_tr_b16.  The softmax keeps a running maximum per query (this
+// kernel is not the tuned one: no fixed exponent reference, no sub-block pipeline); the next
+// tile's K and V are requested before the current tile is processed.
+#include "ns_common.h"
+
+namespace ns {
+
+namespace {
+
+struct RaggedParams {
+  const uint16_t *q, *k, *v;
+  uint16_t *out;
+  int64_t qsb, qsh, qst, osb, osh, ost;
+  float c;               // scale * log2(e)
+  int nbh, nbw, cap;     // blocks per side, slots per block in `lists`
+  int heads;
+  const int32_t *lists;  // [B, nbh*nbw, cap] token indices
+  const int32_t *counts; // [B, nbh*nbw]
+};
+
+typedef s16x4 __attribute__((address_space(3))) *lds_s16x4_ptr;
+
+__device__ __forceinline__ float rswap_max(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float rswap_sum(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ void rdma16(const char *base, uint32_t voff, uint32_t lds) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(lds), "v"(voff), "s"(base) : "memory", "m0");
+}
+
+// grid (ceil(nblocks/4), H, B), 256 threads: one wave per query block.
+__global__ __launch_bounds__(256, 2) void attn_mfma_ragged_kernel(RaggedParams p) {
+  const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  const int l32 = lane & 31, hh = lane >> 5;
+  const int nblocks = p.nbh * p.nbw;
+  const int blk = blockIdx.x * 4 + wave, h = blockIdx.y, b = blockIdx.z;
+  if (blk >= nblocks) return;                 // no workgroup barriers below
+  const int32_t *cnts = p.counts + (size_t)b * nblocks;
+  const int32_t *lst = p.lists + (size_t)b * nblocks * p.cap;
+  const int qcnt = __builtin_amdgcn_readfirstlane(cnts[blk]);
+  if (qcnt == 0) return;
+  const int R = blk / p.nbw, C = blk % p.nbw;
+
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  unsigned char *vlds = smem + wave * 16384;  // two V tiles, row-major [key][64] bf16, swizzled
+  const uint32_t lds_base = (uint32_t)(size_t)((__attribute__((address_space(3))) unsigned char *)vlds);
+
+  const char *qb = reinterpret_cast<const char *>(p.q + b * p.qsb + h * p.qsh);
+  const char *kb = reinterpret_cast<const char *>(p.k + b * p.qsb + h * p.qsh);
+  const char *vb = reinterpret_cast<const char *>(p.v + b * p.qsb + h * p.qsh);
+  const uint32_t rowB = (uint32_t)p.qst * 2u;
+
+  // token of slot `lane` of a block; slots beyond the fill repeat slot 0 (a valid row: its logits
+  // are masked, its weights are zero, its output is not stored)
+  auto slot_token = [&](int blk2, int cnt) { return lst[(size_t)blk2 * p.cap + (lane < cnt ? lane : 0)]; };
+
+  // ---- Q as B operand: lane (query l32 + 32*nt, half hh) holds channels 32*hh + 8*s + j
+  const int qtok = slot_token(blk, qcnt);
+  bf16x8 qf[2][4];
+  int qrow[2];
+#pragma unroll
+  for (int nt = 0; nt < 2; nt++) {
+    qrow[nt] = __shfl(qtok, l32 + 32 * nt);
+    const char *row = qb + (size_t)qrow[nt] * rowB + 64 * hh;
+#pragma unroll
+    for (int s = 0; s < 4; s++) qf[nt][s] = *reinterpret_cast<const bf16x8 *>(row + 16 * s);
+  }
+
+  // transposed V reads (layout argument in ns_attn_mfma.hip)
+  unsigned char *vrd[2][2];
+  {
+    const int g = lane >> 4, s = lane & 15;
+    const int dbyte = (16 * (g & 1) + 4 * (s & 3)) * 2;
+#pragma unroll
+    for (int half = 0; half < 2; half++) {
+      const int key = 8 * half + 4 * hh + (s >> 2);
+      const int off = key * 128 + (dbyte ^ (((key >> 1) & 1) << 6));
+      vrd[0][half] = vlds + off;
+      vrd[1][half] = vlds + (off ^ 64);
+    }
+  }
+  const uint32_t vchunk = 16u * ((lane & 7) ^ (((lane >> 4) & 1) << 2));   // swizzled source chunk
+
+  // ---- state initialised by the global token (key 0): m = its logit, l = 1, O = v_0
+  float m[2], l[2];
+  f32x16 o[2][2];
+  {
+    bf16x8 k0[4];
+#pragma unroll
+    for (int s = 0; s < 4; s++) k0[s] = *reinterpret_cast<const bf16x8 *>(kb + 64 * hh + 16 * s);
+#pragma unroll
+    for (int nt = 0; nt < 2; nt++) {
+      float acc = 0.f;
+#pragma unroll
+      for (int s = 0; s < 4; s++)
+#pragma unroll
+        for (int j = 0; j < 8; j++) acc = __builtin_fmaf((float)qf[nt][s][j], (float)k0[s][j], acc);
+      m[nt] = rswap_sum(acc) * p.c;
+      l[nt] = hh == 0 ? 1.f : 0.f;
+    }
+#pragma unroll
+    for (int dt = 0; dt < 2; dt++)
+#pragma unroll
+      for (int ig = 0; ig < 4; ig++) {
+        const bf16x4 v4 = *reinterpret_cast<const bf16x4 *>(vb + (32 * dt + 8 * ig + 4 * hh) * 2);
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+          o[dt][0][4 * ig + e] = (float)v4[e];
+          o[dt][1][4 * ig + e] = (float)v4[e];
+        }
+      }
+  }
+
+  // ---- non-empty neighbour blocks as a bit mask over the 3x3 positions
+  uint32_t nbmask = 0;
+  for (int nb = 0; nb < 9; nb++) {
+    const int R2 = R + nb / 3 - 1, C2 = C + nb % 3 - 1;
+    if (R2 < 0 || R2 >= p.nbh || C2 < 0 || C2 >= p.nbw) continue;
+    if (cnts[R2 * p.nbw + C2] > 0) nbmask |= 1u << nb;
+  }
+  nbmask = __builtin_amdgcn_readfirstlane(nbmask);   // the query block itself is non-empty: mask != 0
+
+  // requests of one key tile: K fragments into registers, V into an LDS buffer
+  auto request = [&](int nb, bf16x8 (&kf)[2][4], int buf, int &cnt) {
+    const int blk2 = (R + nb / 3 - 1) * p.nbw + (C + nb % 3 - 1);
+    cnt = __builtin_amdgcn_readfirstlane(cnts[blk2]);
+    const int tok = slot_token(blk2, cnt);
+#pragma unroll
+    for (int it = 0; it < 8; it++) {
+      const uint32_t vt = (uint32_t)__shfl(tok, it * 8 + (lane >> 3));
+      rdma16(vb, vt * rowB + vchunk, lds_base + buf * 8192 + it * 1024);
+    }
+#pragma unroll
+    for (int mt = 0; mt < 2; mt++) {
+      const uint32_t kt = (uint32_t)__shfl(tok, l32 + 32 * mt);
+      const char *row = kb + (size_t)kt * rowB + 64 * hh;
+#pragma unroll
+      for (int s = 0; s < 4; s++) kf[mt][s] = *reinterpret_cast<const bf16x8 *>(row + 16 * s);
+    }
+  };
+  auto stage_a = [&](const bf16x8 (&kf)[2][4], int mt, int nt) {
+    f32x16 s = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < 4; ks++) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[mt][ks], qf[nt][ks], s, 0, 0, 0);
+    return s;
+  };
+  auto stage_c = [&](int mt, int nt, const bf16x8 (&pf)[2], int buf) {
+#pragma unroll
+    for (int sp = 0; sp < 2; sp++)
+#pragma unroll
+      for (int dt = 0; dt < 2; dt++) {
+        const int off = buf * 8192 + (2 * mt + sp) * 2048;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vrd[dt][0] + off));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vrd[dt][1] + off));
+        const bf16x4 a = __builtin_bit_cast(bf16x4, lo), b2 = __builtin_bit_cast(bf16x4, hi);
+        const bf16x8 vf = {a[0], a[1], a[2], a[3], b2[0], b2[1], b2[2], b2[3]};
+        o[dt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[sp], o[dt][nt], 0, 0, 0);
+      }
+  };
+  // one key tile: kf / buf / cnt describe it; its requests are complete
+  auto process = [&](const bf16x8 (&kf)[2][4], int buf, int cnt) {
+#pragma unroll
+    for (int nt = 0; nt < 2; nt++) {
+      f32x16 s0 = stage_a(kf, 0, nt), s1 = stage_a(kf, 1, nt);
+      if (cnt < 64) {
+        // register e of a 32x32 block is key 8*(e/4) + 4*hh + e%4 (+32 for the second block)
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+          const int key = 8 * (e >> 2) + 4 * hh + (e & 3);
+          s0[e] = key < cnt ? s0[e] : -INFINITY;
+          s1[e] = key + 32 < cnt ? s1[e] : -INFINITY;
+        }
+      }
+      float mx0 = fmaxf(s0[0], s0[1]), mx1 = fmaxf(s1[0], s1[1]);
+#pragma unroll
+      for (int e = 2; e < 16; e += 2) {
+        mx0 = fmaxf(fmaxf(mx0, s0[e]), s0[e + 1]);
+        mx1 = fmaxf(fmaxf(mx1, s1[e]), s1[e + 1]);
+      }
+      // the tile holds at least one key, and m starts finite: m_new is finite
+      const float m_new = fmaxf(m[nt], rswap_max(fmaxf(mx0, mx1)) * p.c);
+      const float alpha = __builtin_amdgcn_exp2f(m[nt] - m_new);
+      m[nt] = m_new;
+      const float nm = -m_new;
+      float ls = 0.f;
+      bf16x8 pa[2], pb[2];
+#pragma unroll
+      for (int e = 0; e < 16; e += 2) {
+        const float a0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s0[e], p.c, nm));
+        const float a1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s0[e + 1], p.c, nm));
+        const float b0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[e], p.c, nm));
+        const float b1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[e + 1], p.c, nm));
+        ls += (a0 + a1) + (b0 + b1);
+        const bf16x2 ka = __builtin_bit_cast(bf16x2, pack_bf16(a0, a1));
+        const bf16x2 kb2 = __builtin_bit_cast(bf16x2, pack_bf16(b0, b1));
+        pa[e >> 3][e & 7] = ka[0]; pa[e >> 3][(e & 7) + 1] = ka[1];
+        pb[e >> 3][e & 7] = kb2[0]; pb[e >> 3][(e & 7) + 1] = kb2[1];
+      }
+      l[nt] = __builtin_fmaf(l[nt], alpha, ls);
+#pragma unroll
+      for (int e = 0; e < 16; e++) { o[0][nt][e] *= alpha; o[1][nt][e] *= alpha; }
+      stage_c(0, nt, pa, buf);
+      stage_c(1, nt, pb, buf);
+    }
+  };
+
+  bf16x8 kfa[2][4], kfb[2][4];
+  int cnta = 0, cntb = 0;
+  int nb = __builtin_ctz(nbmask);
+  nbmask &= nbmask - 1;
+  request(nb, kfa, 0, cnta);
+  while (true) {
+    // tile in (kfa, buffer 0); request the next one into (kfb, buffer 1) first
+    const bool more1 = nbmask != 0;
+    if (more1) { nb = __builtin_ctz(nbmask); nbmask &= nbmask - 1; request(nb, kfb, 1, cntb); }
+    // this tile's V transfers are older than everything requested just now: at most the 16 new
+    // requests may still be in flight
+    if (more1) asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    process(kfa, 0, cnta);
+    // the tile's LDS reads have returned before the next transfer into its buffer is requested
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    if (!more1) break;
+    const bool more2 = nbmask != 0;
+    if (more2) { nb = __builtin_ctz(nbmask); nbmask &= nbmask - 1; request(nb, kfa, 0, cnta); }
+    if (more2) asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    process(kfb, 1, cntb);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    if (!more2) break;
+  }
+
+  // ---- normalise and store the rows that exist: lane (query, hh) owns channels 32*dt + 8*ig + 4*hh + 0..3
+  char *ob = reinterpret_cast<char *>(p.out + b * p.osb + h * p.osh);
+#pragma unroll
+  for (int nt = 0; nt < 2; nt++) {
+    const float inv = 1.f / rswap_sum(l[nt]);
+    if (l32 + 32 * nt >= qcnt) continue;
+    char *row = ob + (size_t)qrow[nt] * (size_t)(p.ost * 2) + 8 * hh;
+#pragma unroll
+    for (int dt = 0; dt < 2; dt++)
+#pragma unroll
+      for (int ig = 0; ig < 4; ig++) {
+        uint2 u = {pack_bf16(o[dt][nt][4 * ig] * inv, o[dt][nt][4 * ig + 1] * inv),
+                   pack_bf16(o[dt][nt][4 * ig + 2] * inv, o[dt][nt][4 * ig + 3] * inv)};
+        *reinterpret_cast<uint2 *>(row + 64 * dt + 16 * ig) = u;
+      }
+  }
+}
+
+}  // namespace
+
+bool ragged_attn_supported(const ns_attn_desc &d) {
+  return d.dtype == NS_BF16 && d.head_dim == 64 && d.radius == 1 && d.n_global == 1 &&
+         d.coords != nullptr && d.block <= 8 && d.scale > 0.f && d.heads <= 65535 && d.batch <= 65535 &&
+         (long long)d.tokens * d.q_stride_t * 2 < 0x7fffffffLL &&
+         (long long)d.tokens * d.out_stride_t * 2 < 0x7fffffffLL;
+}
+
+ns_status launch_attn_ragged(const AttnArgs &a) {
+  const ns_attn_desc &d = a.d;
+  RaggedParams p;
+  p.q = static_cast<const uint16_t *>(a.q);
+  p.k = static_cast<const uint16_t *>(a.k);
+  p.v = static_cast<const uint16_t *>(a.v);
+  p.out = static_cast<uint16_t *>(a.out);
+  p.qsb = d.q_stride_b; p.qsh = d.q_stride_h; p.qst = d.q_stride_t;
+  p.osb = d.out_stride_b; p.osh = d.out_stride_h; p.ost = d.out_stride_t;
+  p.c = d.scale * kLog2e;
+  p.nbh = a.geom.nbh; p.nbw = a.geom.nbw; p.cap = a.geom.cap;
+  p.heads = d.heads;
+  p.lists = a.geom.lists; p.counts = a.geom.counts;
+  const long long gx = ((long long)p.nbh * p.nbw + 3) / 4;
+  if (gx > 0x7fffffffLL) return fail(NS_ERR_UNSUPPORTED, "launch grid too large");
+  hipLaunchKernelGGL(attn_mfma_ragged_kernel, dim3((unsigned)gx, d.heads, d.batch), dim3(256), 4 * 16384,
+                     a.stream, p);
+  return check_launch("attn_mfma_ragged_kernel");
+}
+
+}  // namespace ns

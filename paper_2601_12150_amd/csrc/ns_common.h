@@ -77,6 +77,8 @@ bool mfma_attn_supported(const ns_attn_desc &d);
 ns_status launch_attn_mfma(const AttnArgs &a);
 bool persist_attn_supported(const ns_attn_desc &d);
 ns_status launch_attn_persist(const AttnArgs &a);
+bool ragged_attn_supported(const ns_attn_desc &d);   // pruned sequence, blocks of at most 8x8
+ns_status launch_attn_ragged(const AttnArgs &a);
 
 // global-query (CLS) row: per-chunk partials, then a combine.
 constexpr int kClsChunk = 512;                      // keys per workgroup of the row kernel

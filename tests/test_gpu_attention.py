@@ -95,6 +95,37 @@ def test_pruned_sequence(nb, dtype, block):
     assert_attn_close(to_np(out), ref, dtype, "pruned sequence")
 
 
+@pytest.mark.parametrize("g,block,shuffle,gain", [(30, 8, False, 1.0), (30, 5, True, 1.0), (20, 3, False, 1.0),
+                                                  (32, 8, True, 12.0)])
+def test_pruned_sequence_mfma_kernel(nb, monkeypatch, g, block, shuffle, gain):
+    """bf16, head_dim 64, blocks of at most 8x8: the MFMA kernel for pruned sequences.  Covers grids
+    the block does not divide, survivors in arbitrary sequence order, logits large enough to need
+    the running maximum, and agreement with the fp32 FMA kernel on the same inputs."""
+    rng = np.random.default_rng(g * 100 + block)
+    N = g * g
+    keep = rng.random(N) < 0.6
+    r, c = np.divmod(np.arange(N), g)
+    keep[(r // block == 0) & (c // block == 0)] = False            # an empty corner block
+    kept = np.flatnonzero(keep)
+    if shuffle:
+        kept = rng.permutation(kept)
+    B, H = 2, 3
+    q, k, v = synth.small_case(77 + block, B, H, 64, 1, len(kept), "bf16")
+    q = synth.round_to_bf16(q * gain)
+    coords = np.ascontiguousarray(np.broadcast_to(synth.raster_coords(g, g)[kept], (B, len(kept))))
+    ref = oracle.ns_attn(q, k, v, g, g, block, 0.125, coords=coords)
+    dcoords = torch.from_numpy(coords).cuda()
+    dq, dk, dv = (to_dev(a, "bf16") for a in (q, k, v))
+    out = nb.ns_attn_forward(dq, dk, dv, g, g, block, 0.125, coords=dcoords)
+    torch.cuda.synchronize()
+    assert np.isfinite(to_np(out)).all()
+    assert_attn_close(to_np(out), ref, "bf16", "pruned sequence, MFMA kernel")
+    monkeypatch.setenv("NSATTN_KERNEL", "generic")
+    out_g = nb.ns_attn_forward(dq, dk, dv, g, g, block, 0.125, coords=dcoords)
+    torch.cuda.synchronize()
+    assert_attn_close(to_np(out_g), ref, "bf16", "pruned sequence, FMA kernel")
+
+
 def test_cls_by_products_and_determinism(nb):
     gh = gw = 24
     q, k, v = synth.small_case(55, 2, 4, 64, gh, gw, "bf16")
