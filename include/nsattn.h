@@ -168,6 +168,21 @@ ns_status vit_block_forward(const ns_vit_block_desc *desc, const ns_vit_block_we
                             size_t workspace_bytes, void *stream);
 
 /*
+ * One linear map of the block with its fused epilogue, exposed on its own for tests and
+ * measurement (the block applies it four times: QKV, attention projection, the two MLP layers of
+ * the standard ViT block the paper builds on):
+ *     y[m][n] = act( sum_k x[m][k] * w[n][k] + bias[n] ) + residual[m][n]
+ *   x        in  [M, K] bf16, row-major          w     in  [N, K] bf16 (out-features major)
+ *   bias     in  [N] fp32                        residual in, nullable [M, N] bf16
+ *   gelu     non-zero: act = exact (erf) GELU, else identity
+ *   y        out [M, N] bf16; must not alias x, w or residual
+ * fp32 accumulation, one rounding to bf16 at the end.  N must be a multiple of 128 and K of 64
+ * (NS_ERR_UNSUPPORTED otherwise); all pointers 16-byte aligned.  No workspace.
+ */
+ns_status linear_forward(int32_t M, int32_t N, int32_t K, const void *x, const void *w, const float *bias,
+                         const void *residual, int32_t gelu, void *y, void *stream);
+
+/*
  * A stack of `layers` such blocks with one pruning stage (paper, "Time-Efficiency Optimization":
  * the pruning is applied once, after several initial layers, and shortens the sequence for all
  * subsequent layers).  Blocks 0 .. prune_after-1 run on the full grid; the importance scores of

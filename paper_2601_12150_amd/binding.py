@@ -21,7 +21,7 @@ NS_F32, NS_BF16 = 0, 1
 
 EXPORTS = ["ns_attn_workspace_bytes", "ns_attn_forward", "cls_scores_workspace_bytes", "cls_scores",
            "cls_scores_from_logits", "topk_filter_workspace_bytes", "topk_filter",
-           "vit_block_workspace_bytes", "vit_block_forward", "vit_workspace_bytes", "vit_forward",
+           "vit_block_workspace_bytes", "vit_block_forward", "linear_forward", "vit_workspace_bytes", "vit_forward",
            "ns_attn_patch_kernel_time", "ns_last_error",
            "ns_version"]
 
@@ -91,6 +91,8 @@ def _load() -> ctypes.CDLL:
                                       ctypes.POINTER(ns_vit_block_weights), vp, vp, vp, vp, sz, vp]
     lib.vit_workspace_bytes.restype = sz
     lib.vit_workspace_bytes.argtypes = [ctypes.POINTER(ns_vit_desc)]
+    lib.linear_forward.restype = ctypes.c_int
+    lib.linear_forward.argtypes = [i32, i32, i32, vp, vp, vp, vp, i32, vp, vp]
     lib.vit_forward.restype = ctypes.c_int
     lib.vit_forward.argtypes = [ctypes.POINTER(ns_vit_desc), ctypes.POINTER(ns_vit_block_weights), vp, vp, vp, vp,
                                 sz, vp]
@@ -298,6 +300,25 @@ def vit_block_forward(x, weights, grid_h, grid_w, block, heads, ln_eps=1e-6, sca
     _check(lib.vit_block_forward(ctypes.byref(d), ctypes.byref(w), _ptr(x), _ptr(out), _ptr(scores), _ptr(ws),
                                  ws.numel(), _stream(stream)))
     return (out, scores) if want_scores else out
+
+
+def linear_forward(x, w, bias, residual=None, gelu=False, out=None, stream=None):
+    """y = act(x w^T + bias) + residual; x [M,K] bf16, w [N,K] bf16, bias [N] fp32, residual [M,N] bf16."""
+    for t, dt in ((x, torch.bfloat16), (w, torch.bfloat16), (bias, torch.float32)):
+        if t.dtype != dt or not t.is_contiguous():
+            raise ValueError("x, w must be contiguous bfloat16 and bias contiguous float32")
+    M, K = x.shape
+    N = w.shape[0]
+    if w.shape[1] != K or bias.numel() != N:
+        raise ValueError("shape mismatch")
+    if residual is not None and (residual.dtype != torch.bfloat16 or not residual.is_contiguous()
+                                 or tuple(residual.shape) != (M, N)):
+        raise ValueError("residual must be a contiguous bfloat16 tensor [M,N]")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.bfloat16, device=x.device)
+    _check(lib.linear_forward(M, N, K, _ptr(x), _ptr(w), _ptr(bias), _ptr(residual), 1 if gelu else 0, _ptr(out),
+                              _stream(stream)))
+    return out
 
 
 def vit_forward(x, layer_weights, grid_h, grid_w, block, heads, prune_after=0, keep_k=0, ln_eps=1e-6,

@@ -32,6 +32,25 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 }
 
 constexpr float kLog2e = 1.4426950408889634f;
+
+// GELU with the Gaussian error function, 0.5 x (1 + erf(x / sqrt 2)), written so that the
+// cancellation for negative x never happens: with z = |x| / sqrt 2 and E = erfc(z),
+//   gelu(x) = max(x, 0) - 0.5 |x| E.
+// erfc(z) = t (a1 + t (a2 + t (a3 + t (a4 + t a5)))) exp(-z^2), t = 1 / (1 + p z), is the rational
+// approximation 7.1.26 of Abramowitz & Stegun (absolute error below 1.5e-7, i.e. at the level of
+// fp32 rounding and far below the bf16 rounding of the result).
+__device__ __forceinline__ float gelu_erf(float x) {
+  const float ax = __builtin_fabsf(x);
+  const float z = ax * 0.70710678118654752f;
+  const float t = __builtin_amdgcn_rcpf(__builtin_fmaf(0.3275911f, z, 1.f));
+  float q = __builtin_fmaf(1.061405429f, t, -1.453152027f);
+  q = __builtin_fmaf(q, t, 1.421413741f);
+  q = __builtin_fmaf(q, t, -0.284496736f);
+  q = __builtin_fmaf(q, t, 0.254829592f);
+  const float e = __builtin_amdgcn_exp2f(-(z * z) * 1.4426950408889634f);
+  const float E = q * t * e;
+  return __builtin_fmaxf(x, 0.f) - 0.5f * ax * E;
+}
 constexpr float kLn2 = 0.6931471805599453f;
 
 // ---- geometry of the block neighbourhood ----------------------------------
@@ -92,6 +111,11 @@ ns_status launch_cls_combine(const ns_attn_desc &d, const float *partials, void 
 // lse given directly, or (lse == nullptr) recomputed from the row kernel's partials
 ns_status launch_cls_scores(int B, int H, int T, int G, const float *logits, const float *lse,
                             const float *partials, int nchunks, float *scores, hipStream_t s);
+
+// linear map with fused epilogue, 256 x 256 workgroup tiles (ns_gemm256.hip)
+bool gemm256_supported(int M, int N, int K);
+ns_status launch_gemm256(const uint16_t *a, const uint16_t *w, const float *bias, const uint16_t *r,
+                         uint16_t *c, int M, int N, int K, bool gelu, hipStream_t s);
 
 ns_status launch_topk_select(int B, int N, int k, const float *scores, const int32_t *coords_in,
                              int32_t *kept, int32_t *coords_out, hipStream_t s);

@@ -88,9 +88,6 @@ __device__ __forceinline__ void dma16(const char *base, uint32_t voff, uint32_t 
 
 typedef bf16x8 __attribute__((address_space(3))) *lds_bf16x8_ptr;
 
-__device__ __forceinline__ float gelu_erf(float x) {
-  return 0.5f * x * (1.f + erff(x * 0.70710678118654752f));
-}
 
 __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(GemmParams p) {
   const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
@@ -209,6 +206,9 @@ ns_status launch_layernorm(const uint16_t *x, const float *g, const float *b, ui
 
 ns_status launch_gemm(const uint16_t *a, const uint16_t *w, const float *bias, const uint16_t *r,
                       uint16_t *c, int M, int N, int K, bool gelu, hipStream_t s) {
+  // NSATTN_GEMM=128 keeps the 128 x 128 kernel for every shape
+  const char *e = getenv("NSATTN_GEMM");
+  if (gemm256_supported(M, N, K) && !(e && e[0] == '1')) return launch_gemm256(a, w, bias, r, c, M, N, K, gelu, s);
   if (N % 128 || K % 64) return fail(NS_ERR_UNSUPPORTED, "GEMM needs N %% 128 == 0 and K %% 64 == 0 (N=%d K=%d)", N, K);
   if ((long long)M * K * 2 >= 0x7fffffffLL || (long long)N * K * 2 >= 0x7fffffffLL)
     return fail(NS_ERR_UNSUPPORTED, "GEMM operand beyond 2 GiB");
@@ -371,6 +371,20 @@ size_t vit_workspace_bytes(const ns_vit_desc *desc) {
   const size_t bw = vit_block_workspace_bytes(&desc->block);   // the full grid needs the most
   if (bw == 0) return 0;
   return stack_layout(*desc, bw).total;
+}
+
+ns_status linear_forward(int32_t M, int32_t N, int32_t K, const void *x, const void *w, const float *bias,
+                         const void *residual, int32_t gelu, void *y, void *stream) {
+  if (M <= 0 || N <= 0 || K <= 0) return fail(NS_ERR_INVALID_ARG, "M, N, K must be positive");
+  if (!x || !w || !bias || !y) return fail(NS_ERR_INVALID_ARG, "x, w, bias and y must not be NULL");
+  const uintptr_t bits = reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(w) |
+                         reinterpret_cast<uintptr_t>(bias) | reinterpret_cast<uintptr_t>(residual) |
+                         reinterpret_cast<uintptr_t>(y);
+  if (bits % 16) return fail(NS_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
+  if (y == x || y == w || y == residual) return fail(NS_ERR_INVALID_ARG, "y must not alias an input");
+  return launch_gemm(static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(w), bias,
+                     static_cast<const uint16_t *>(residual), static_cast<uint16_t *>(y), M, N, K, gelu != 0,
+                     static_cast<hipStream_t>(stream));
 }
 
 ns_status vit_forward(const ns_vit_desc *desc, const ns_vit_block_weights *weights, const void *x_in,

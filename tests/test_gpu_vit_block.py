@@ -110,3 +110,32 @@ def test_stack_without_pruning_equals_repeated_blocks(nb):
         h = nb.vit_block_forward(h, w, g, g, block, heads)
     torch.cuda.synchronize()
     assert kept is None and torch.equal(out, h)
+
+
+@pytest.mark.parametrize("M,N,K,gelu,res", [
+    (1025, 1024, 1024, False, True),    # one extended row tile chain: 4 tiles, the last with a ninth slab
+    (577, 512, 256, True, False),       # remainder 65: a partial tile of its own (3 slabs)
+    (256, 256, 32, False, False),       # a single tile, a single k-slice
+    (300, 768, 2048, True, True),       # remainder 44 -> partial tile with two slabs; long k
+    (1154, 640, 512, False, True),      # N not a multiple of 256: the 128 x 128 kernel
+    (37, 128, 64, True, True),          # fewer rows than any tile
+])
+def test_linear_forward(nb, M, N, K, gelu, res):
+    """The fused linear map against float64 matmul / erf GELU on the same bf16 inputs."""
+    rng = np.random.default_rng(M + N + K)
+    x = synth.round_to_bf16(rng.standard_normal((M, K)).astype(np.float32))
+    w = synth.round_to_bf16((rng.standard_normal((N, K)) / np.sqrt(K)).astype(np.float32))
+    b = rng.standard_normal(N).astype(np.float32)
+    r = synth.round_to_bf16(rng.standard_normal((M, N)).astype(np.float32)) if res else None
+    ref = x.astype(np.float64) @ w.astype(np.float64).T + b
+    if gelu:
+        ref = ov.gelu(ref)
+    if res:
+        ref = ref + r
+    print("linear case M=%d N=%d K=%d gelu=%s residual=%s" % (M, N, K, gelu, res), flush=True)
+    dev = lambda a: torch.from_numpy(a).to(torch.bfloat16).cuda()
+    y = nb.linear_forward(dev(x), dev(w), torch.from_numpy(b).cuda(), None if r is None else dev(r), gelu=gelu)
+    torch.cuda.synchronize()
+    got = to_np(y).astype(np.float64)
+    # one rounding to bf16 (2^-9 relative) on top of fp32 accumulation
+    np.testing.assert_allclose(got, ref, rtol=2.0 ** -8, atol=1e-3)
