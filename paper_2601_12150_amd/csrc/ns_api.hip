@@ -136,7 +136,7 @@ static ns_status launch_patch_attention(const AttnArgs &a) {
 // Shared by ns_attn_forward and the timing aid: validation, workspace carving, block lists.
 static ns_status prepare_attn(const ns_attn_desc *desc, const void *q, const void *k, const void *v,
                               void *out, void *workspace, size_t workspace_bytes, void *stream,
-                              AttnArgs &a, float *&partials) {
+                              AttnArgs &a, float *&partials, bool reuse_lists = false) {
   ns_status st = validate_desc(desc, true);
   if (st != NS_OK) return st;
   if (!q || !k || !v || !out) return fail(NS_ERR_INVALID_ARG, "q, k, v and out must not be NULL");
@@ -160,8 +160,10 @@ static ns_status prepare_attn(const ns_attn_desc *desc, const void *q, const voi
   if (d.coords) {
     int32_t *lists = reinterpret_cast<int32_t *>(ws + w.lists_off);
     int32_t *counts = reinterpret_cast<int32_t *>(ws + w.counts_off);
-    st = launch_block_lists(d, lists, counts, s);
-    if (st != NS_OK) return st;
+    if (!reuse_lists) {
+      st = launch_block_lists(d, lists, counts, s);
+      if (st != NS_OK) return st;
+    }
     g.lists = lists; g.counts = counts;
   }
   return NS_OK;
@@ -170,11 +172,19 @@ static ns_status prepare_attn(const ns_attn_desc *desc, const void *q, const voi
 ns_status ns_attn_forward(const ns_attn_desc *desc, const void *q, const void *k, const void *v,
                           void *out, float *cls_logits, float *cls_lse, void *workspace,
                           size_t workspace_bytes, void *stream) {
+  return attn_forward_impl(desc, q, k, v, out, cls_logits, cls_lse, workspace, workspace_bytes, stream, false);
+}
+
+}  // extern "C"
+
+ns_status ns::attn_forward_impl(const ns_attn_desc *desc, const void *q, const void *k, const void *v,
+                                void *out, float *cls_logits, float *cls_lse, void *workspace,
+                                size_t workspace_bytes, void *stream, bool reuse_lists) {
   if ((cls_logits && !aligned(cls_logits, 4)) || (cls_lse && !aligned(cls_lse, 4)))
     return fail(NS_ERR_INVALID_ARG, "cls_logits / cls_lse misaligned");
   AttnArgs a;
   float *partials = nullptr;
-  ns_status st = prepare_attn(desc, q, k, v, out, workspace, workspace_bytes, stream, a, partials);
+  ns_status st = prepare_attn(desc, q, k, v, out, workspace, workspace_bytes, stream, a, partials, reuse_lists);
   if (st != NS_OK) return st;
   const ns_attn_desc &d = a.d;
   st = launch_patch_attention(a);
@@ -184,6 +194,8 @@ ns_status ns_attn_forward(const ns_attn_desc *desc, const void *q, const void *k
   if (st != NS_OK) return st;
   return launch_cls_combine(d, partials, out, cls_lse, true, a.stream);
 }
+
+extern "C" {
 
 ns_status ns_attn_patch_kernel_time(const ns_attn_desc *desc, const void *q, const void *k,
                                     const void *v, void *out, void *workspace,

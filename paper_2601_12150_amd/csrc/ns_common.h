@@ -90,6 +90,13 @@ struct AttnArgs {
   hipStream_t stream;
 };
 
+// ns_attn_forward with one more knob: reuse_lists = the per-block token lists that an earlier call
+// with the same descriptor, coords contents and workspace left in the workspace are still valid
+// (a stack of blocks after its pruning stage), so they are not rebuilt.
+ns_status attn_forward_impl(const ns_attn_desc *desc, const void *q, const void *k, const void *v, void *out,
+                            float *cls_logits, float *cls_lse, void *workspace, size_t workspace_bytes,
+                            void *stream, bool reuse_lists);
+
 ns_status launch_block_lists(const ns_attn_desc &d, int32_t *lists, int32_t *counts, hipStream_t s);
 ns_status launch_attn_generic(const AttnArgs &a);
 bool mfma_attn_supported(const ns_attn_desc &d);

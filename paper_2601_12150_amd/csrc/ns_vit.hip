@@ -302,6 +302,10 @@ ns_status check_stack(const ns_vit_desc *d, bool &prune) {
 
 using namespace ns;
 
+static ns_status block_forward_impl(const ns_vit_block_desc *desc, const ns_vit_block_weights *w,
+                                    const void *x_in, void *x_out, float *scores_out, void *workspace,
+                                    size_t workspace_bytes, void *stream, bool reuse_lists);
+
 extern "C" {
 
 size_t vit_block_workspace_bytes(const ns_vit_block_desc *desc) {
@@ -314,6 +318,15 @@ size_t vit_block_workspace_bytes(const ns_vit_block_desc *desc) {
 ns_status vit_block_forward(const ns_vit_block_desc *desc, const ns_vit_block_weights *w,
                             const void *x_in, void *x_out, float *scores_out, void *workspace,
                             size_t workspace_bytes, void *stream) {
+  return block_forward_impl(desc, w, x_in, x_out, scores_out, workspace, workspace_bytes, stream, false);
+}
+
+}  // extern "C"
+
+// reuse_lists: see attn_forward_impl
+static ns_status block_forward_impl(const ns_vit_block_desc *desc, const ns_vit_block_weights *w,
+                                    const void *x_in, void *x_out, float *scores_out, void *workspace,
+                                    size_t workspace_bytes, void *stream, bool reuse_lists) {
   ns_attn_desc ad;
   ns_status st = block_attn_desc(desc, ad);
   if (st != NS_OK) return st;
@@ -345,8 +358,8 @@ ns_status vit_block_forward(const ns_vit_block_desc *desc, const ns_vit_block_we
   if (st != NS_OK) return st;
   st = launch_gemm(ln, static_cast<const uint16_t *>(w->w_qkv), w->b_qkv, nullptr, qkv, M, 3 * dim, dim, false, s);
   if (st != NS_OK) return st;
-  st = ns_attn_forward(&ad, qkv, qkv + dim, qkv + 2 * dim, att, scores_out ? logits : nullptr,
-                       scores_out ? lse : nullptr, ws + L.attn_ws, L.total - L.attn_ws, s);
+  st = attn_forward_impl(&ad, qkv, qkv + dim, qkv + 2 * dim, att, scores_out ? logits : nullptr,
+                         scores_out ? lse : nullptr, ws + L.attn_ws, L.total - L.attn_ws, s, reuse_lists);
   if (st != NS_OK) return st;
   if (scores_out) {
     st = cls_scores_from_logits(ad.batch, ad.heads, ad.tokens, ad.n_global, logits, lse, scores_out, s);
@@ -360,8 +373,6 @@ ns_status vit_block_forward(const ns_vit_block_desc *desc, const ns_vit_block_we
   if (st != NS_OK) return st;
   return launch_gemm(hid, static_cast<const uint16_t *>(w->w_fc2), w->b_fc2, h, y, M, dim, mlp, false, s);
 }
-
-}  // extern "C"
 
 extern "C" {
 
@@ -412,12 +423,15 @@ ns_status vit_forward(const ns_vit_desc *desc, const ns_vit_block_weights *weigh
   const int N = full.tokens - full.n_global;
   const void *cur = x_in;
   int flip = 0;
+  bool lists_built = false;   // the pruned sequence's block lists stay valid from block to block
   for (int l = 0; l < desc->layers; l++) {
     const bool last = l + 1 == desc->layers, scoring = prune && l + 1 == desc->prune_after;
     // the last block writes x_out directly unless the pruning stage still follows it
     void *dst = (last && !scoring) ? x_out : buf[flip];
-    st = vit_block_forward(&bd, &weights[l], cur, dst, scoring ? scores : nullptr, ws + L.block_ws, bw, s);
+    st = block_forward_impl(&bd, &weights[l], cur, dst, scoring ? scores : nullptr, ws + L.block_ws, bw, s,
+                            lists_built);
     if (st != NS_OK) return st;
+    lists_built = bd.attn.coords != nullptr;
     cur = dst;
     flip ^= 1;
     if (scoring) {
