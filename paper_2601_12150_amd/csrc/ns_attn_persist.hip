@@ -1,29 +1,37 @@
 // Persistent bf16 MFMA neighbourhood attention for patch queries on the full grid (gfx950).
-// ALTERNATIVE kernel, selected with NSATTN_KERNEL=persist; the default is ns_attn_mfma.hip.  It is
-// correct (same parity tests) and hides memory latency better, but at present loses what it gains
-// to register moves between the vector and accumulator register files at the branches inside its
-// tile body (first/last key tile of a query tile); the default kernel is faster until those
-// branches are peeled into separate code paths.
+// Selected with NSATTN_KERNEL=persist (see launch_patch_attention for the default).
 //
 // Same mathematics and register formulation as ns_attn_mfma.hip (transposed products, P kept in
 // registers, fixed exponent reference with a checked fallback); what differs is how the chip is
-// occupied.  One wave per SIMD (up to 512 VGPRs, 40 KB of LDS each) lives for the whole launch and
-// walks a list of 64-query tiles.  All global traffic of the steady state is asynchronous and
-// request-ordered:
-//   K tile  global -> LDS (2-slot ring, coalesced 1 KB requests, XOR swizzle) -> registers one
-//           tile ahead of its use,
-//   V tile  global -> LDS (3-slot ring) -> ds_read_b64_tr_b16 at its use,
-//   Q, k_0, v_0 of the NEXT query tile global -> registers (ordinary loads) while the current
-//           one is computed.
-// Requests run two key tiles ahead and do not stop at query-tile boundaries, so neither the
-// per-query prologue nor any memory latency is exposed after the first tile of a wave.  The
-// waits on the LDS transfers are explicit vmcnt(N): vector loads complete in issue order, so "at
-// most N outstanding" means everything but the N youngest requests has arrived.  Extra requests
-// in flight (stores, next-query loads) can only make such a wait conservative, never early; and
-// the waits the compiler computes for its own loads are conservative for the same reason (it
-// does not count the transfers).  Only requests WITHOUT a register result are issued from asm:
-// a register written asynchronously by asm would look free to the register allocator.
+// occupied.  One wave per SIMD (single-wave workgroups, 38 KB of LDS each) lives for the whole
+// launch and walks a list of 64-query tiles.  Every global access of the steady state is an
+// asynchronous global -> LDS transfer or a store, request-ordered:
+//   K tile  in halves of 32 keys through a ring of three 4 KB half-slots (XOR swizzle), each half
+//           read into registers right after the previous contents of those registers were last used,
+//   V tile  in halves through a ring of two 8 KB slots, each half requested as soon as the half it
+//           replaces has been read; ds_read_b64_tr_b16 at its use,
+//   Q tile, k_0, v_0 of the NEXT query tile into a slot of their own, a whole query tile ahead.
+// Requests do not stop at query-tile boundaries, so neither the per-query prologue nor any memory
+// latency is exposed after the first tile of a wave.  No load with a register result is in
+// flight while transfers are issued: the compiler's wait for such a load would also wait for
+// every transfer issued after it (one in-order counter).
+//
+// Control flow.  The tile body contains no branches: a query tile is FIRST tile, a loop of MIDDLE
+// tiles, LAST tile (three instantiations of one body), and everything that happens once per
+// query tile (normalise, store, overflow check, next query's state) sits between them.  Ring
+// positions are run-time scalars, so the body does not depend on how many key tiles a query tile
+// has.  (Branches inside the body made the register allocator shuffle hundreds of values between
+// the vector and accumulator files per tile in an earlier version.)
+//
+// Waits.  Vector memory operations complete in issue order, so "at most N outstanding"
+// (s_waitcnt vmcnt(N)) means that everything but the N youngest has arrived.  Per key tile t the
+// body issues, in this order: K(t+2) first half [4 requests], K(t+2) second half [4], V(t+1)
+// second half [4], V(t+2) first half [4].  Before it reads the first half of K(t+1) and of V(t)
+// it allows the 16 requests issued after those; likewise before the second halves.  The FIRST
+// tile of a query tile additionally allows the 16 stores and 10 requests issued between the query
+// tiles.  All of these are issued from asm, one instruction each, so the counts are exact.
 #include "ns_common.h"
+#include <type_traits>
 
 namespace ns {
 
@@ -45,6 +53,17 @@ typedef s16x4 __attribute__((address_space(3))) *lds_s16x4_ptr;
 typedef bf16x8 __attribute__((address_space(3))) *lds_bf16x8_ptr;
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
+constexpr int kStoresPerQuery = 16;   // 8-byte stores of one query tile's output
+constexpr int kQueryRequests = 10;    // transfers of the next query tile: 8 (Q) + 1 (k_0) + 1 (v_0)
+constexpr int kBodyWindow = 16;       // requests the body issues after the ones it is about to use
+// LDS map of a wave, bytes
+constexpr uint32_t KRING = 0;         // three half-slots of 4096
+constexpr uint32_t VRING = 12288;     // two slots of 8192
+constexpr uint32_t QSLOT = 28672;     // 64 query rows of 128 bytes, swizzled like K
+constexpr uint32_t K0ROW = 36864;     // k_0 in the first 128 bytes of a 1 KB request
+constexpr uint32_t V0ROW = 37888;     // v_0 likewise
+constexpr uint32_t kLdsUsed = 38912;
+
 __device__ __forceinline__ float hswap_max(float x) {
   auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
   return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
@@ -59,38 +78,39 @@ __device__ __forceinline__ void dma16(const char *base, uint32_t voff, uint32_t 
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
                :: "s"(lds), "v"(voff), "s"(base) : "memory", "m0");
 }
+// 8 bytes per lane to global memory, issued from asm so that it is exactly one request.
+__device__ __forceinline__ void store8(void *ptr, u32x2 v) {
+  asm volatile("global_store_dwordx2 %0, %1, off" :: "v"(ptr), "v"(v) : "memory");
+}
 template <int N>
 __device__ __forceinline__ void wait_vm() {
   asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
 
+#define NS_U(x) __builtin_amdgcn_readfirstlane(x)
+
 template <int LOG2B>
-__global__ __launch_bounds__(64) void attn_mfma_persist_kernel(PersistParams p) {
+__global__ __launch_bounds__(64, 2) void attn_mfma_persist_kernel(PersistParams p) {
   constexpr int B_ = 1 << LOG2B;
   constexpr int TPB = (B_ * B_) / 64;
   constexpr int TROWS = 64 / B_;
-  // one wave per workgroup: four of them share a CU (one per SIMD, by their register count), each
-  // with its own 40 KB of LDS, so LDS addresses stay small and no workgroup-level state exists
   const int lane = threadIdx.x;
   const int l32 = lane & 31, hh = lane >> 5;
 
   // ---- this wave's query tiles: XCD x owns a contiguous range of the (image-major) tile list,
   // its waves sweep that range together (tile = lo + slot + j*slots), so the XCD's L2 holds one
-  // or two head-images' K and V at a time
-  // (integer division runs on the vector ALU; readfirstlane puts the uniform results back into
-  // scalar registers so that everything derived from them stays scalar)
-#define NS_U(x) __builtin_amdgcn_readfirstlane(x)
+  // or two head-images' K and V at a time.  (Integer division runs on the vector ALU;
+  // readfirstlane puts the uniform results back into scalar registers.)
   const int xcd = NS_U((int)blockIdx.x % p.xcds), slot = NS_U((int)blockIdx.x / p.xcds);
   const int slots = p.slots;
   const int lo = NS_U((int)((long long)p.tiles_total * xcd / p.xcds));
   const int hi = NS_U((int)((long long)p.tiles_total * (xcd + 1) / p.xcds));
-  const int qt = lo + slot;
-  if (qt >= hi) return;
+  if (lo + slot >= hi) return;
+  const int nq_wave = (hi - (lo + slot) + slots - 1) / slots;      // query tiles of this wave
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  unsigned char *wlds = smem;                 // [0,16K): K ring (2 slots), [16K,40K): V ring (3 slots)
+  unsigned char *wlds = smem;
   const uint32_t lds_base = (uint32_t)(size_t)((__attribute__((address_space(3))) unsigned char *)wlds);
-  constexpr uint32_t VRING = 16384;
 
   const uint32_t rowB = (uint32_t)p.qst * 2u;
   const uint32_t gridrowB = (uint32_t)p.grid_w * rowB;
@@ -98,7 +118,7 @@ __global__ __launch_bounds__(64) void attn_mfma_persist_kernel(PersistParams p) 
   auto tile_base = [&](int R2, int C2, int sub) { return 1 + (R2 * B_ + sub * TROWS) * p.grid_w + C2 * B_; };
 
   // ---- per-lane constants
-  // DMA source: LDS slot `lane` of chunk `it` holds row it*8 + lane/8, physical 16-byte chunk lane%8.
+  // DMA source: LDS slot `lane` of request `it` holds row it*8 + lane/8, physical 16-byte chunk lane%8.
   // K: logical chunk = physical ^ ((row>>1)&7); V: logical = physical ^ 4*((row>>1)&1).
   // For V, (row>>1)&1 does not depend on `it`; for K, (row>>1)&7 = (4*(it&1) + (row%8 >> 1)) & 7, so
   // even and odd requests use one offset register each.
@@ -109,11 +129,12 @@ __global__ __launch_bounds__(64) void attn_mfma_persist_kernel(PersistParams p) 
   const uint32_t dma_voff = (uint32_t)tile_off(drow) * rowB + 16u * ((lane & 7) ^ (((drow >> 1) & 1) << 2));
   auto dstep = [&](int it) { return LOG2B == 3 ? it * gridrowB : (it >> 1) * gridrowB + (it & 1) * 8u * rowB; };
   // K fragment reads: lane (row l32 [+32], half hh) needs logical chunks 4*hh + s
-  unsigned char *krd[4];
+  const uint32_t krd0 = l32 * 128;
+  uint32_t krd[4];
 #pragma unroll
-  for (int s = 0; s < 4; s++) krd[s] = wlds + l32 * 128 + 16 * ((4 * hh + s) ^ ((l32 >> 1) & 7));
+  for (int s = 0; s < 4; s++) krd[s] = krd0 + 16 * ((4 * hh + s) ^ ((l32 >> 1) & 7));
   // V transposed reads (see ns_attn_mfma.hip for the layout argument)
-  unsigned char *vrd[2][2];
+  uint32_t vrd[2][2];
   {
     const int g = lane >> 4, s = lane & 15;
     const int dbyte = (16 * (g & 1) + 4 * (s & 3)) * 2;
@@ -121,23 +142,21 @@ __global__ __launch_bounds__(64) void attn_mfma_persist_kernel(PersistParams p) 
     for (int half = 0; half < 2; half++) {
       const int key = 8 * half + 4 * hh + (s >> 2);
       const int off = key * 128 + (dbyte ^ (((key >> 1) & 1) << 6));
-      vrd[0][half] = wlds + VRING + off;
-      vrd[1][half] = wlds + VRING + (off ^ 64);
+      vrd[0][half] = VRING + off;
+      vrd[1][half] = VRING + (off ^ 64);
     }
   }
   const uint32_t qoff0 = (uint32_t)tile_off(l32) * rowB + 64u * hh;
   const uint32_t qoff1 = (uint32_t)tile_off(l32 + 32) * rowB + 64u * hh;
 
-  // ---- cursors over this wave's flattened (query tile, key tile) sequence
-  struct Cursor {
-    int qt;                  // query tile id; clamped to the wave's last one
-    int i, ntiles;           // key tile index within the query tile
-    int R0, C0, ncols, R, C, qsub;
+  // ---- query tiles and key tiles as scalar descriptors
+  struct Query {
+    int ntiles, R0, C0, ncols, R, C, qsub;
     const char *qb, *kb, *vb;
     char *ob;
   };
-  auto open_query = [&](Cursor &c, int t) {
-    c.qt = t;
+  auto open_query = [&](Query &c, int j) {          // j-th query tile of this wave, clamped to the last
+    const int t = lo + slot + min(j, nq_wave - 1) * slots;
     const int img = NS_U(t / p.tiles_per_image), rem = t - img * p.tiles_per_image;
     const int b = NS_U(img / p.heads), h = img - b * p.heads;
     const int blk = rem / TPB;               // TPB is a power of two
@@ -147,66 +166,64 @@ __global__ __launch_bounds__(64) void attn_mfma_persist_kernel(PersistParams p) 
     const int R1 = min(c.R + 1, p.nbh - 1), C1 = min(c.C + 1, p.nbw - 1);
     c.ncols = C1 - c.C0 + 1;
     c.ntiles = (R1 - c.R0 + 1) * c.ncols * TPB;
-    c.i = 0;
     const int64_t ho = b * p.qsb + h * p.qsh;
     c.qb = reinterpret_cast<const char *>(p.q + ho);
     c.kb = reinterpret_cast<const char *>(p.k + ho);
     c.vb = reinterpret_cast<const char *>(p.v + ho);
     c.ob = reinterpret_cast<char *>(p.out + b * p.osb + h * p.osh);
   };
-  auto key_base = [&](const Cursor &c) {
-    const int sub = c.i & (TPB - 1), nbi = c.i / TPB;
+  struct Tile { const char *kb, *vb; };     // K and V rows of key 0 of a key tile
+  auto key_tile = [&](const Query &c, int i) {
+    const int sub = i & (TPB - 1), nbi = i / TPB;
     const int dR = (nbi >= c.ncols) + (nbi >= 2 * c.ncols);
-    return (uint32_t)tile_base(c.R0 + dR, c.C0 + nbi - dR * c.ncols, sub) * rowB;
+    const uint32_t off = (uint32_t)tile_base(c.R0 + dR, c.C0 + nbi - dR * c.ncols, sub) * rowB;
+    Tile t;
+    t.kb = c.kb + off; t.vb = c.vb + off;
+    return t;
   };
-  // next key tile; past the wave's last key tile the cursor stays on it (requests repeat, harmless)
-  auto advance = [&](Cursor &c) {
-    if (c.i + 1 < c.ntiles) { c.i++; return; }
-    if (c.qt + slots < hi) open_query(c, c.qt + slots);
-  };
-  auto dma_k = [&](const Cursor &c, int slot) {
-    const char *t = c.kb + key_base(c);
+  // half: 0 = keys 0..31 (requests 0..3), 1 = keys 32..63; dst: byte offset of the 4 KB destination
+  auto dma_k_half = [&](const Tile &t, int half, uint32_t dst) {
 #pragma unroll
-    for (int it = 0; it < 8; it++) dma16(t + dstep(it), dma_koff[it & 1], lds_base + slot * 8192 + it * 1024);
+    for (int i = 0; i < 4; i++)
+      dma16(t.kb + dstep(4 * half + i), dma_koff[i & 1], lds_base + KRING + dst + i * 1024);
   };
-  auto dma_v = [&](const Cursor &c, int slot) {
-    const char *t = c.vb + key_base(c);
+  auto dma_v_half = [&](const Tile &t, int par, int half) {
 #pragma unroll
-    for (int it = 0; it < 8; it++) dma16(t + dstep(it), dma_voff, lds_base + VRING + slot * 8192 + it * 1024);
+    for (int it = 4 * half; it < 4 * half + 4; it++)
+      dma16(t.vb + dstep(it), dma_voff, lds_base + VRING + par * 8192 + it * 1024);
+  };
+  // the query tile's rows (laid out and swizzled like a K tile) and the global token's key / value rows
+  auto dma_query = [&](const Query &c) {            // kQueryRequests requests
+    const char *t = c.qb + (uint32_t)tile_base(c.R, c.C, c.qsub) * rowB;
+#pragma unroll
+    for (int it = 0; it < 8; it++) dma16(t + dstep(it), dma_koff[it & 1], lds_base + QSLOT + it * 1024);
+    dma16(c.kb, 16u * (lane & 7), lds_base + K0ROW);
+    dma16(c.vb, 16u * (lane & 7), lds_base + V0ROW);
   };
 
   // ---- register state
-  bf16x8 qf[2][4], qn[2][4];       // Q fragments of the current / next query tile
-  bf16x8 k0n[4];                   // k_0 slice and v_0 slice of the next query tile's image
-  u32x2 v0n[2][4];
-  bf16x8 kfa[2][4], kfb[2][4];     // K fragments, alternating by key tile parity
+  bf16x8 qf[2][4];                 // Q fragments of the current query tile
+  bf16x8 kA[4], kB[4];             // K fragments: keys 0..31 / 32..63 of a key tile
   f32x16 o[2][2];
   float m[2], l[2], nm[2], la[2][2];
 
-  auto load_query = [&](const Cursor &c, bf16x8 (&qd)[2][4]) {
-    const char *t = c.qb + (uint32_t)tile_base(c.R, c.C, c.qsub) * rowB;
+  // Q fragments out of the query slot: lane (query l32 + 32*nt, half hh), logical chunks 4*hh + s
+  auto read_query = [&]() {
 #pragma unroll
-    for (int s = 0; s < 4; s++) {
-      qd[0][s] = *reinterpret_cast<const bf16x8 *>(t + qoff0 + 16 * s);
-      qd[1][s] = *reinterpret_cast<const bf16x8 *>(t + qoff1 + 16 * s);
-      k0n[s] = *reinterpret_cast<const bf16x8 *>(c.kb + 64 * hh + 16 * s);
-    }
+    for (int nt = 0; nt < 2; nt++)
 #pragma unroll
-    for (int dt = 0; dt < 2; dt++)
-#pragma unroll
-      for (int ig = 0; ig < 4; ig++)
-        v0n[dt][ig] = *reinterpret_cast<const u32x2 *>(c.vb + 8 * hh + 64 * dt + 16 * ig);
+      for (int s = 0; s < 4; s++) qf[nt][s] = *(lds_bf16x8_ptr)(wlds + QSLOT + nt * 4096 + krd[s]);
   };
   // the global token initialises the state: m = its logit (the fixed exponent reference),
-  // l = 1, O = v_0.  Uses qf (already the new query's) and k0n / v0n.
-  auto init_state = [&]() {
+  // l = 1, O = v_0.  k0: channels 32*hh + 8*s + j; v0: channels 32*dt + 8*ig + 4*hh + e.
+  auto init_state = [&](const bf16x8 (&k0)[4], const u32x2 (&v0)[2][4]) {
 #pragma unroll
     for (int nt = 0; nt < 2; nt++) {
       float acc = 0.f;
 #pragma unroll
       for (int s = 0; s < 4; s++)
 #pragma unroll
-        for (int j = 0; j < 8; j++) acc = __builtin_fmaf((float)qf[nt][s][j], (float)k0n[s][j], acc);
+        for (int j = 0; j < 8; j++) acc = __builtin_fmaf((float)qf[nt][s][j], (float)k0[s][j], acc);
       acc = hswap_sum(acc);
       m[nt] = acc * p.c;
       nm[nt] = -m[nt];
@@ -217,7 +234,7 @@ __global__ __launch_bounds__(64) void attn_mfma_persist_kernel(PersistParams p) 
     for (int dt = 0; dt < 2; dt++)
 #pragma unroll
       for (int ig = 0; ig < 4; ig++) {
-        const bf16x4 v4 = __builtin_bit_cast(bf16x4, v0n[dt][ig]);
+        const bf16x4 v4 = __builtin_bit_cast(bf16x4, v0[dt][ig]);
 #pragma unroll
         for (int e = 0; e < 4; e++) {
           o[dt][0][4 * ig + e] = (float)v4[e];
@@ -225,17 +242,26 @@ __global__ __launch_bounds__(64) void attn_mfma_persist_kernel(PersistParams p) 
         }
       }
   };
-  auto read_kf = [&](bf16x8 (&kf)[2][4], int slot) {
+  auto init_state_lds = [&]() {
+    bf16x8 k0[4];
+    u32x2 v0[2][4];
 #pragma unroll
-    for (int mt = 0; mt < 2; mt++)
+    for (int s = 0; s < 4; s++) k0[s] = *(lds_bf16x8_ptr)(wlds + K0ROW + 64 * hh + 16 * s);
 #pragma unroll
-      for (int s = 0; s < 4; s++)
-        kf[mt][s] = *(lds_bf16x8_ptr)(krd[s] + slot * 8192 + mt * 4096);
+    for (int dt = 0; dt < 2; dt++)
+#pragma unroll
+      for (int ig = 0; ig < 4; ig++)
+        v0[dt][ig] = *(u32x2 __attribute__((address_space(3))) *)(wlds + V0ROW + 64 * dt + 16 * ig + 8 * hh);
+    init_state(k0, v0);
   };
-  auto stage_a = [&](const bf16x8 (&kf)[2][4], const bf16x8 (&qq)[2][4], int mt, int nt) {
+  auto read_k_half = [&](bf16x8 (&kf)[4], uint32_t off) {     // off: byte offset of the half-slot
+#pragma unroll
+    for (int s = 0; s < 4; s++) kf[s] = *(lds_bf16x8_ptr)(wlds + KRING + krd[s] + off);
+  };
+  auto stage_a = [&](const bf16x8 (&kf)[4], int nt) {
     f32x16 s = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int ks = 0; ks < 4; ks++) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[mt][ks], qq[nt][ks], s, 0, 0, 0);
+    for (int ks = 0; ks < 4; ks++) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[nt][ks], s, 0, 0, 0);
     return s;
   };
   auto stage_b = [&](const f32x16 &s, int nt, bf16x8 (&pf)[2]) {
@@ -250,210 +276,241 @@ __global__ __launch_bounds__(64) void attn_mfma_persist_kernel(PersistParams p) 
       pf[i >> 3][(i & 7) + 1] = pk[1];
     }
   };
+  // O^T[:, nt] += V^T[:, keys 32*mt ..] P^T; voffs: V ring slot in bytes
   auto stage_c = [&](int mt, int nt, const bf16x8 (&pf)[2], uint32_t voffs) {
 #pragma unroll
     for (int sp = 0; sp < 2; sp++)
 #pragma unroll
       for (int dt = 0; dt < 2; dt++) {
         const uint32_t off = voffs + (2 * mt + sp) * 2048;
-        const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vrd[dt][0] + off));
-        const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vrd[dt][1] + off));
+        const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(wlds + vrd[dt][0] + off));
+        const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(wlds + vrd[dt][1] + off));
         const bf16x4 a = __builtin_bit_cast(bf16x4, lo4), b2 = __builtin_bit_cast(bf16x4, hi4);
         const bf16x8 vf = {a[0], a[1], a[2], a[3], b2[0], b2[1], b2[2], b2[3]};
         o[dt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[sp], o[dt][nt], 0, 0, 0);
       }
   };
 
-  Cursor cc, pc;                   // consumer, producer (two key tiles ahead)
-  open_query(cc, qt);
-  open_query(pc, qt);
+  // ---- the flattened (query tile, key tile) sequence.  cq: query tile being computed; nq: the
+  // one after it; the producer position (pq, pi) is three key tiles ahead of the consumer and
+  // therefore in cq or nq.  d1 / d2: key tiles t+1 and t+2 of the current key tile t.
+  Query cq, nq, pq;
+  int qj = 0;                        // index of cq among this wave's query tiles
+  open_query(cq, 0);
+  open_query(nq, 1);
+  pq = cq;
+  int pi = 0;
+  auto next_tile = [&]() {           // descriptor at the producer position, then advance it (no branches)
+    const Tile t = key_tile(pq, pi);
+    pi++;
+    const bool wrap = pi == pq.ntiles;
+    pi = wrap ? 0 : pi;
+    pq.ntiles = wrap ? nq.ntiles : pq.ntiles;
+    pq.R0 = wrap ? nq.R0 : pq.R0;
+    pq.C0 = wrap ? nq.C0 : pq.C0;
+    pq.ncols = wrap ? nq.ncols : pq.ncols;
+    pq.kb = wrap ? nq.kb : pq.kb;
+    pq.vb = wrap ? nq.vb : pq.vb;
+    return t;
+  };
+  Tile d0 = next_tile(), d1 = next_tile(), d2;
+  int par = 0;                       // V ring slot of the current key tile t
+  // K ring: with ka = 2t mod 3, half-slot ka holds K(t+1) second half, ka+2 its first half, and
+  // ka+1 (mod 3) is free
+  int ka = 0;
+  auto mod3 = [](int x) { return x >= 3 ? x - 3 : x; };
 
-  // ---- prologue: the only place where this wave waits for a full round trip
-  load_query(cc, qf);
-  dma_k(pc, 0); dma_v(pc, 0); advance(pc);
-  dma_k(pc, 1); dma_v(pc, 1); advance(pc);
-  wait_vm<0>();
-  init_state();
-  read_kf(kfa, 0);
-  f32x16 s00 = stage_a(kfa, qf, 0, 0);
-  bf16x8 p3[2];                    // weights of the previous tile's last sub-block (deferred stage C)
-  uint32_t vprev = 0;
+  // Everything key tile t0 needs and everything the steady state would have requested before it
+  // starts; all of it has landed on return.
+  auto prime = [&](const Tile &t0, const Tile &t1) {
+    const uint32_t hfree = mod3(ka + 1) * 4096u, hfirst = mod3(ka + 2) * 4096u, hsecond = ka * 4096u;
+    dma_k_half(t0, 0, hfree);
+    dma_k_half(t0, 1, hfirst);
+    dma_v_half(t0, par, 0);
+    dma_v_half(t0, par, 1);
+    wait_vm<0>();
+    read_k_half(kA, hfree);
+    read_k_half(kB, hfirst);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    dma_k_half(t1, 0, hfirst);
+    dma_k_half(t1, 1, hsecond);
+    dma_v_half(t1, 1 - par, 0);
+    wait_vm<0>();
+  };
 
-  int vslot = 0;                   // V ring slot of the current key tile
-  bool have_next_q = false;
+  f32x16 s00;
+  bf16x8 p3[2];                      // weights of the previous key tile's last sub-block (its stage C is deferred)
 
-  // One key tile.  kc: this tile's K fragments, kn: register set for the next tile's, kslot: K ring
-  // slot of this tile (the next tile's is 1 - kslot).
-  auto tile = [&](const bf16x8 (&kc)[2][4], bf16x8 (&kn)[2][4], int kslot, bool &done) {
-    const bool first = cc.i == 0, last = cc.i + 1 == cc.ntiles;
-    const uint32_t vcur = vslot * 8192u;
-    // K of the tile after next goes into this tile's ring slot (its fragments are in registers)
-    dma_k(pc, kslot);
-    if (first) {
-      // next query tile's Q, k_0, v_0: requested a whole query tile ahead
-      Cursor nq = cc;
-      have_next_q = cc.qt + slots < hi;
-      if (have_next_q) { open_query(nq, cc.qt + slots); load_query(nq, qn); }
-    }
+  // One key tile.  FIRST / LAST: first / last key tile of a query tile.
+  auto tile = [&](auto first_tag, auto last_tag) {
+    constexpr bool FIRST = decltype(first_tag)::value, LAST = decltype(last_tag)::value;
+    constexpr int W = kBodyWindow + (FIRST ? kStoresPerQuery + kQueryRequests : 0);
+    const uint32_t hfree = mod3(ka + 1) * 4096u, hfirst = mod3(ka + 2) * 4096u, hsecond = ka * 4096u;
+    const uint32_t vcur = par * 8192u, vnext = 8192u - vcur;
+    d2 = next_tile();
     bf16x8 p0[2], p1[2], p2[2];
     // step 0
-    const f32x16 s01 = stage_a(kc, qf, 0, 1);
+    dma_k_half(d2, 0, hfree);                        // K(t+2) keys 0..31
+    const f32x16 s01 = stage_a(kA, 1);
     stage_b(s00, 0, p0);
-    if (!first) stage_c(1, 1, p3, vprev);          // previous tile's last sub-block
-    // V of the tile after next: its ring slot was last read just above
-    dma_v(pc, vslot == 0 ? 2 : vslot - 1);
-    advance(pc);
-    // everything but the youngest requests (K, V of tile+2; V of tile+1 ...) has landed:
-    // this tile's V and the next tile's K are in LDS
-    wait_vm<24>();
-    read_kf(kn, 1 - kslot);
-    // step 1
-    const f32x16 s10 = stage_a(kc, qf, 1, 0);
+    if (!FIRST) stage_c(1, 1, p3, vnext);            // previous tile's last sub-block (keys 32..63 of its V)
+    // step 1: the first halves of K(t+1) and V(t) have landed
+    wait_vm<W>();
+    read_k_half(kA, hfirst);                         // K(t+1) keys 0..31
+    dma_k_half(d2, 1, hfirst);                       // K(t+2) keys 32..63 take their place
+    dma_v_half(d1, 1 - par, 1);                      // V(t+1) second half: that half was last read in step 0
+    const f32x16 s10 = stage_a(kB, 0);
     stage_b(s01, 1, p1);
     stage_c(0, 0, p0, vcur);
     // step 2
-    const f32x16 s11 = stage_a(kc, qf, 1, 1);
+    const f32x16 s11 = stage_a(kB, 1);
     stage_b(s10, 0, p2);
     stage_c(0, 1, p1, vcur);
-    if (!last) {
-      // step 3
-      s00 = stage_a(kn, qf, 0, 0);
-      stage_b(s11, 1, p3);
-      stage_c(1, 0, p2, vcur);
-      vprev = vcur;
-    } else {
-      // last key tile of this query tile: finish it, store, and switch to the next query tile
-      stage_b(s11, 1, p3);
-      stage_c(1, 0, p2, vcur);
-      stage_c(1, 1, p3, vcur);
-      l[0] += la[0][0] + la[0][1];
-      l[1] += la[1][0] + la[1][1];
-      float big = fmaxf(fabsf(l[0]), fabsf(l[1]));
+    // step 3: the second halves of K(t+1) and V(t) have landed
+    wait_vm<W>();
+    read_k_half(kB, hsecond);                        // K(t+1) keys 32..63
+    dma_v_half(d2, par, 0);                          // V(t+2) first half: that half was last read in step 2
+    if (!LAST) s00 = stage_a(kA, 0);                 // first sub-block of the next key tile
+    stage_b(s11, 1, p3);
+    stage_c(1, 0, p2, vcur);
+    if (LAST) stage_c(1, 1, p3, vcur);
+    d0 = d1; d1 = d2;
+    par ^= 1;
+    ka = mod3(ka + 2);
+  };
+  using T = std::true_type;
+  using F = std::false_type;
+
+  // ---- prologue: the only place where this wave waits for a full round trip
+  dma_query(cq);
+  prime(d0, d1);
+  read_query();
+  init_state_lds();
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the slot has been read: the next query tile may land in it
+  dma_query(nq);
+  s00 = stage_a(kA, 0);
+
+  while (true) {
+    tile(T{}, F{});
+    for (int i = cq.ntiles - 2; i > 0; i--) tile(F{}, F{});
+    tile(F{}, T{});
+
+    // ---- the query tile is complete
+    l[0] += la[0][0] + la[0][1];
+    l[1] += la[1][0] + la[1][1];
+    float big = fmaxf(fabsf(l[0]), fabsf(l[1]));
 #pragma unroll
-      for (int i = 0; i < 16; i++)
-        big = fmaxf(fmaxf(big, fmaxf(fabsf(o[0][0][i]), fabsf(o[0][1][i]))),
-                    fmaxf(fabsf(o[1][0][i]), fabsf(o[1][1][i])));
-      if (__any(!(big < 1e30f))) {
-        // ---- a weight overflowed: redo this query tile with a running maximum.  Drain the
-        // request pipeline first (the rings keep the data already requested for later tiles),
-        // stage V through the ring slot this tile has just finished with.
-        wait_vm<0>();
-        // k0n / v0n hold the NEXT query's rows by now; keep them and reload this image's
-        bf16x8 k0s[4];
-        u32x2 v0s[2][4];
+    for (int i = 0; i < 16; i++)
+      big = fmaxf(fmaxf(big, fmaxf(fabsf(o[0][0][i]), fabsf(o[0][1][i]))),
+                  fmaxf(fabsf(o[1][0][i]), fabsf(o[1][1][i])));
+    const bool bad = __any(!(big < 1e30f));
+    const int qbase = tile_base(cq.R, cq.C, cq.qsub);
+    auto store = [&]() {             // lane (query, hh) owns channels 32*dt + 8*ig + 4*hh + 0..3; kStoresPerQuery stores
 #pragma unroll
-        for (int s = 0; s < 4; s++) {
-          k0s[s] = k0n[s];
-          k0n[s] = *reinterpret_cast<const bf16x8 *>(cc.kb + 64 * hh + 16 * s);
-        }
+      for (int nt = 0; nt < 2; nt++) {
+        const float inv = 1.f / hswap_sum(l[nt]);
+        char *row = cq.ob + (size_t)(qbase + tile_off(l32 + 32 * nt)) * (size_t)(p.ost * 2) + 8 * hh;
 #pragma unroll
         for (int dt = 0; dt < 2; dt++)
 #pragma unroll
           for (int ig = 0; ig < 4; ig++) {
-            v0s[dt][ig] = v0n[dt][ig];
-            v0n[dt][ig] = *reinterpret_cast<const u32x2 *>(cc.vb + 8 * hh + 64 * dt + 16 * ig);
+            u32x2 u = {pack_bf16(o[dt][nt][4 * ig] * inv, o[dt][nt][4 * ig + 1] * inv),
+                       pack_bf16(o[dt][nt][4 * ig + 2] * inv, o[dt][nt][4 * ig + 3] * inv)};
+            store8(row + 64 * dt + 16 * ig, u);
           }
-        init_state();
-        Cursor rc = cc;
-        for (rc.i = 0; rc.i < rc.ntiles; rc.i++) {
-          const uint32_t base = key_base(rc);
-          // K fragments straight from global memory (tracked loads: the pipeline is drained)
-          bf16x8 kt[2][4];
-          const char *t = rc.kb + base;
-          const uint32_t kstep = (32 >> LOG2B) * gridrowB;
+      }
+    };
+    store();
+    if (bad) {
+      // ---- a weight overflowed: redo this query tile with a running maximum, fragments straight
+      // from global memory, V staged through ring slot 0; then restart the request pipeline at
+      // the next key tile (d0) and store again.
+      wait_vm<0>();
+      {
+        bf16x8 k0[4];
+        u32x2 v0[2][4];
 #pragma unroll
-          for (int mt = 0; mt < 2; mt++)
-#pragma unroll
-            for (int s = 0; s < 4; s++)
-              kt[mt][s] = *reinterpret_cast<const bf16x8 *>(t + mt * kstep + qoff0 + 16 * s);
-          dma_v(rc, vslot);
-          wait_vm<0>();
-#pragma unroll
-          for (int nt = 0; nt < 2; nt++) {
-            const f32x16 s0 = stage_a(kt, qf, 0, nt), s1 = stage_a(kt, qf, 1, nt);
-            float mx0 = fmaxf(s0[0], s0[1]), mx1 = fmaxf(s1[0], s1[1]);
-#pragma unroll
-            for (int e = 2; e < 16; e += 2) {
-              mx0 = fmaxf(fmaxf(mx0, s0[e]), s0[e + 1]);
-              mx1 = fmaxf(fmaxf(mx1, s1[e]), s1[e + 1]);
-            }
-            const float m_new = fmaxf(m[nt], hswap_max(fmaxf(mx0, mx1)) * p.c);
-            const float alpha = __builtin_amdgcn_exp2f(m[nt] - m_new);
-            m[nt] = m_new;
-            const float nmm = -m_new;
-            float ls = 0.f;
-            bf16x8 pa[2], pb[2];
-#pragma unroll
-            for (int e = 0; e < 16; e += 2) {
-              const float a0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s0[e], p.c, nmm));
-              const float a1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s0[e + 1], p.c, nmm));
-              const float b0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[e], p.c, nmm));
-              const float b1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[e + 1], p.c, nmm));
-              ls += (a0 + a1) + (b0 + b1);
-              const bf16x2 ka = __builtin_bit_cast(bf16x2, pack_bf16(a0, a1));
-              const bf16x2 kb2 = __builtin_bit_cast(bf16x2, pack_bf16(b0, b1));
-              pa[e >> 3][e & 7] = ka[0]; pa[e >> 3][(e & 7) + 1] = ka[1];
-              pb[e >> 3][e & 7] = kb2[0]; pb[e >> 3][(e & 7) + 1] = kb2[1];
-            }
-            l[nt] = __builtin_fmaf(l[nt], alpha, ls);
-#pragma unroll
-            for (int e = 0; e < 16; e++) { o[0][nt][e] *= alpha; o[1][nt][e] *= alpha; }
-            stage_c(0, nt, pa, vcur);
-            stage_c(1, nt, pb, vcur);
-          }
-          asm volatile("" ::: "memory");
-        }
-        // put the next query's rows back
-#pragma unroll
-        for (int s = 0; s < 4; s++) k0n[s] = k0s[s];
+        for (int s = 0; s < 4; s++) k0[s] = *reinterpret_cast<const bf16x8 *>(cq.kb + 64 * hh + 16 * s);
 #pragma unroll
         for (int dt = 0; dt < 2; dt++)
 #pragma unroll
-          for (int ig = 0; ig < 4; ig++) v0n[dt][ig] = v0s[dt][ig];
+          for (int ig = 0; ig < 4; ig++)
+            v0[dt][ig] = *reinterpret_cast<const u32x2 *>(cq.vb + 8 * hh + 64 * dt + 16 * ig);
+        init_state(k0, v0);
       }
-      // ---- normalise and store: lane (query, hh) owns channels 32*dt + 8*ig + 4*hh + 0..3
-      {
-        const int qbase = tile_base(cc.R, cc.C, cc.qsub);
+      for (int i = 0; i < cq.ntiles; i++) {
+        const Tile t = key_tile(cq, i);
+        bf16x8 kt[2][4];
+        const uint32_t kstep = (32 >> LOG2B) * gridrowB;
+#pragma unroll
+        for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+          for (int s = 0; s < 4; s++)
+            kt[mt][s] = *reinterpret_cast<const bf16x8 *>(t.kb + mt * kstep + qoff0 + 16 * s);
+        dma_v_half(t, 0, 0);
+        dma_v_half(t, 0, 1);
+        wait_vm<0>();                 // also the K fragments above
 #pragma unroll
         for (int nt = 0; nt < 2; nt++) {
-          const float inv = 1.f / hswap_sum(l[nt]);
-          char *row = cc.ob + (size_t)(qbase + tile_off(l32 + 32 * nt)) * (size_t)(p.ost * 2) + 8 * hh;
+          const f32x16 s0 = stage_a(kt[0], nt), s1 = stage_a(kt[1], nt);
+          float mx0 = fmaxf(s0[0], s0[1]), mx1 = fmaxf(s1[0], s1[1]);
 #pragma unroll
-          for (int dt = 0; dt < 2; dt++)
+          for (int e = 2; e < 16; e += 2) {
+            mx0 = fmaxf(fmaxf(mx0, s0[e]), s0[e + 1]);
+            mx1 = fmaxf(fmaxf(mx1, s1[e]), s1[e + 1]);
+          }
+          const float m_new = fmaxf(m[nt], hswap_max(fmaxf(mx0, mx1)) * p.c);
+          const float alpha = __builtin_amdgcn_exp2f(m[nt] - m_new);
+          m[nt] = m_new;
+          const float nmm = -m_new;
+          float ls = 0.f;
+          bf16x8 pa[2], pb[2];
 #pragma unroll
-            for (int ig = 0; ig < 4; ig++) {
-              uint2 u = {pack_bf16(o[dt][nt][4 * ig] * inv, o[dt][nt][4 * ig + 1] * inv),
-                         pack_bf16(o[dt][nt][4 * ig + 2] * inv, o[dt][nt][4 * ig + 3] * inv)};
-              *reinterpret_cast<uint2 *>(row + 64 * dt + 16 * ig) = u;
-            }
+          for (int e = 0; e < 16; e += 2) {
+            const float a0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s0[e], p.c, nmm));
+            const float a1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s0[e + 1], p.c, nmm));
+            const float b0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[e], p.c, nmm));
+            const float b1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[e + 1], p.c, nmm));
+            ls += (a0 + a1) + (b0 + b1);
+            const bf16x2 ka = __builtin_bit_cast(bf16x2, pack_bf16(a0, a1));
+            const bf16x2 kb2 = __builtin_bit_cast(bf16x2, pack_bf16(b0, b1));
+            pa[e >> 3][e & 7] = ka[0]; pa[e >> 3][(e & 7) + 1] = ka[1];
+            pb[e >> 3][e & 7] = kb2[0]; pb[e >> 3][(e & 7) + 1] = kb2[1];
+          }
+          l[nt] = __builtin_fmaf(l[nt], alpha, ls);
+#pragma unroll
+          for (int e = 0; e < 16; e++) { o[0][nt][e] *= alpha; o[1][nt][e] *= alpha; }
+          stage_c(0, nt, pa, 0);
+          stage_c(1, nt, pb, 0);
         }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // V reads done before the next transfer into the slot
       }
-      if (!have_next_q) { done = true; return; }
-      // ---- next query tile: its Q, k_0, v_0 were requested at this one's first key tile
-#pragma unroll
-      for (int nt = 0; nt < 2; nt++)
-#pragma unroll
-        for (int s = 0; s < 4; s++) qf[nt][s] = qn[nt][s];
-      init_state();
-      s00 = stage_a(kn, qf, 0, 0);
+      store();
+      // the query slot already holds the next query tile (requested before this query tile
+      // began, drained above); restart the key-tile requests at the next key tile
+      prime(d0, d1);
     }
-    vslot = vslot == 2 ? 0 : vslot + 1;
-    advance(cc);
-  };
+    if (++qj >= nq_wave) break;
 
-  bool done = false;
-  while (true) {
-    tile(kfa, kfb, 0, done);
-    if (done) break;
-    tile(kfb, kfa, 1, done);
-    if (done) break;
+    // ---- next query tile: its Q, k_0, v_0 were requested a whole query tile ago (they are older
+    // than everything the waits of this query tile's second key tile allowed to be in flight)
+    cq = nq;
+    open_query(nq, qj + 1);
+    read_query();
+    init_state_lds();
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    dma_query(nq);                   // always issued (clamped to the last query tile): the FIRST tile counts on it
+    s00 = stage_a(kA, 0);
   }
+  wait_vm<0>();                      // requests past the end of the sequence (they repeat its last key tile)
 }
 
 }  // namespace
 
 bool persist_attn_supported(const ns_attn_desc &d) {
-  return mfma_attn_supported(d);
+  // every query tile needs at least 4 key tiles: its FIRST and LAST tile are different code, and
+  // the request pipeline never runs more than one query tile ahead
+  return mfma_attn_supported(d) && d.grid_h / d.block >= 2 && d.grid_w / d.block >= 2;
 }
 
 ns_status launch_attn_persist(const AttnArgs &a) {
@@ -485,7 +542,8 @@ ns_status launch_attn_persist(const AttnArgs &a) {
   p.xcds = (num_cus % 8 == 0) ? 8 : 1;
   p.num_wgs = num_cus * 4;                   // one single-wave workgroup per SIMD
   p.slots = p.num_wgs / p.xcds;
-  const size_t lds = 40960;
+  static_assert(kLdsUsed <= 40960, "LDS map");
+  const size_t lds = 40960;                  // a quarter of a CU's LDS: four workgroups per CU, one per SIMD
   if (d.block == 8)
     hipLaunchKernelGGL(attn_mfma_persist_kernel<3>, dim3(p.num_wgs), dim3(64), lds, a.stream, p);
   else
