@@ -146,7 +146,8 @@ def main() -> int:
     flops_kernel = 4.0 * D * patch_pairs * H * B          # QK^T + PV of the patch rows
     flops_layer = 4.0 * D * (patch_pairs + cls_pairs) * H * B
     achieved = flops_kernel / (kernel_ms * 1e-3)
-    roofline = {"bound": "mfma", "kernel": "attn_mfma_kernel", "achieved": achieved / 1e12,
+    kernel_name = nb.ns_attn_patch_kernel_name(sets[0]["q"], g, g, blk, cfg.scale)
+    roofline = {"bound": "mfma", "kernel": kernel_name, "achieved": achieved / 1e12,
                 "peak": PEAK_BF16_MFMA / 1e12, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_MFMA,
                 "traffic": None, "kernel_ms": kernel_ms, "kernel_ms_warm_cache": warm_ms,
                 "flops_per_launch": flops_kernel,
@@ -154,7 +155,7 @@ def main() -> int:
 
     # traffic measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by the calibration copy) is
     # recorded in profiles/; it is reported here when the record is for this workload
-    traffic_file = os.path.join(ROOT, "profiles", "attn_mfma_kernel_%s_traffic.json" % cfg.name)
+    traffic_file = os.path.join(ROOT, "profiles", "%s_%s_traffic.json" % (kernel_name, cfg.name))
     if os.path.exists(traffic_file):
         with open(traffic_file) as f:
             roofline["traffic"] = json.load(f).get("hbm_bytes_per_launch")

@@ -220,6 +220,13 @@ ns_status ns_attn_patch_kernel_time(const ns_attn_desc *desc, const void *q, con
                                     size_t workspace_bytes, int32_t reps, float *avg_ms,
                                     void *stream);
 
+/*
+ * Name of the kernel that ns_attn_forward launches for the patch queries of `desc` on the current
+ * device (the one ns_attn_patch_kernel_time measures); "" for an invalid descriptor.  Host only,
+ * launches nothing.
+ */
+const char *ns_attn_patch_kernel_name(const ns_attn_desc *desc);
+
 /* Message for the last error returned on this thread (static storage; never free it). */
 const char *ns_last_error(void);
 

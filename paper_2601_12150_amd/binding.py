@@ -22,7 +22,7 @@ NS_F32, NS_BF16 = 0, 1
 EXPORTS = ["ns_attn_workspace_bytes", "ns_attn_forward", "cls_scores_workspace_bytes", "cls_scores",
            "cls_scores_from_logits", "topk_filter_workspace_bytes", "topk_filter",
            "vit_block_workspace_bytes", "vit_block_forward", "linear_forward", "vit_workspace_bytes", "vit_forward",
-           "ns_attn_patch_kernel_time", "ns_last_error",
+           "ns_attn_patch_kernel_time", "ns_attn_patch_kernel_name", "ns_last_error",
            "ns_version"]
 
 
@@ -75,6 +75,8 @@ def _load() -> ctypes.CDLL:
     lib.ns_attn_patch_kernel_time.argtypes = [dp, vp, vp, vp, vp, vp, sz, i32,
                                               ctypes.POINTER(ctypes.c_float), vp]
     lib.cls_scores_workspace_bytes.restype = sz
+    lib.ns_attn_patch_kernel_name.restype = ctypes.c_char_p
+    lib.ns_attn_patch_kernel_name.argtypes = [dp]
     lib.cls_scores_workspace_bytes.argtypes = [dp]
     lib.cls_scores.restype = ctypes.c_int
     lib.cls_scores.argtypes = [dp, vp, vp, vp, vp, sz, vp]
@@ -196,6 +198,14 @@ def ns_attn_patch_kernel_time(q, k, v, grid_h, grid_w, block, scale=None, coords
                                          0 if ws is None else ws.numel(), int(reps), ctypes.byref(ms),
                                          _stream(stream)))
     return float(ms.value)
+
+
+def ns_attn_patch_kernel_name(q, grid_h, grid_w, block, scale=None, coords=None) -> str:
+    """Name of the kernel ns_attn_forward launches for the patch queries of this problem."""
+    B, H, T, D = q.shape
+    desc = make_desc(q, grid_h, grid_w, block, scale, None, coords)
+    desc.out_stride_b, desc.out_stride_h, desc.out_stride_t = desc.q_stride_b, desc.q_stride_h, desc.q_stride_t
+    return lib.ns_attn_patch_kernel_name(ctypes.byref(desc)).decode()
 
 
 def cls_scores(q, k, scale=None, n_global=1, scores=None, workspace=None, stream=None):

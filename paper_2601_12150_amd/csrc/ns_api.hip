@@ -120,17 +120,47 @@ size_t ns_attn_workspace_bytes(const ns_attn_desc *desc) {
   return attn_workspace_layout(*desc).total;
 }
 
-// Kernel choice for the patch queries.
-static ns_status launch_patch_attention(const AttnArgs &a) {
-  // NSATTN_KERNEL=persist selects the persistent-wave variant of the MFMA kernel (same results)
+// Kernel choice for the patch queries.  On the full grid with bf16, head_dim 64 and 8x8 or 16x16
+// blocks there are three MFMA kernels that compute the same function: the sweep (8x8 blocks; key
+// tiles shared along a row of blocks; wants at least two rows of blocks per CU to fill the chip),
+// the persistent one-wave-per-SIMD kernel (needs two blocks per grid side), and the plain
+// one-wave-per-query-tile kernel.  A pruned sequence takes the MFMA kernel for block lists when
+// the blocks are at most 8x8, and everything else the fp32 FMA kernel.
+// NSATTN_KERNEL = sweep | persist | mfma | generic forces one of them where it applies.
+enum PatchKernel { PK_SWEEP, PK_PERSIST, PK_MFMA, PK_RAGGED, PK_GENERIC };
+
+static PatchKernel choose_patch_kernel(const ns_attn_desc &d, bool have_lists) {
   const char *e = getenv("NSATTN_KERNEL");
-  if (mfma_attn_supported(a.d)) {
-    if (e && e[0] == 'p' && persist_attn_supported(a.d)) return launch_attn_persist(a);
-    return launch_attn_mfma(a);
+  const char force = e ? e[0] : 0;
+  if (mfma_attn_supported(d)) {
+    static int num_cus = 0;
+    if (num_cus == 0) {
+      int dev = 0;
+      hipDeviceProp_t prop;
+      num_cus = (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+                    ? prop.multiProcessorCount : 256;
+    }
+    const long long strips = (long long)d.batch * d.heads * (d.grid_h / d.block);
+    const bool sweep_ok = sweep_attn_supported(d), persist_ok = persist_attn_supported(d);
+    if (force == 's' && sweep_ok) return PK_SWEEP;
+    if (force == 'p' && persist_ok) return PK_PERSIST;
+    if (force == 'm') return PK_MFMA;
+    if (sweep_ok && strips >= 2LL * num_cus) return PK_SWEEP;
+    if (persist_ok) return PK_PERSIST;
+    return PK_MFMA;
   }
-  // NSATTN_KERNEL=generic keeps the fp32 FMA kernel for a pruned sequence
-  if (ragged_attn_supported(a.d) && a.geom.lists && !(e && e[0] == 'g')) return launch_attn_ragged(a);
-  return launch_attn_generic(a);
+  if (ragged_attn_supported(d) && have_lists && force != 'g') return PK_RAGGED;
+  return PK_GENERIC;
+}
+
+static ns_status launch_patch_attention(const AttnArgs &a) {
+  switch (choose_patch_kernel(a.d, a.geom.lists != nullptr)) {
+    case PK_SWEEP: return launch_attn_sweep(a);
+    case PK_PERSIST: return launch_attn_persist(a);
+    case PK_MFMA: return launch_attn_mfma(a);
+    case PK_RAGGED: return launch_attn_ragged(a);
+    default: return launch_attn_generic(a);
+  }
 }
 
 // Shared by ns_attn_forward and the timing aid: validation, workspace carving, block lists.
@@ -221,6 +251,17 @@ ns_status ns_attn_patch_kernel_time(const ns_attn_desc *desc, const void *q, con
   if (e != hipSuccess) return fail(NS_ERR_HIP, "event timing: %s", hipGetErrorString(e));
   *avg_ms = ms / (float)reps;
   return NS_OK;
+}
+
+const char *ns_attn_patch_kernel_name(const ns_attn_desc *desc) {
+  if (validate_desc(desc, true) != NS_OK) return "";
+  switch (choose_patch_kernel(*desc, desc->coords != nullptr)) {
+    case PK_SWEEP: return "attn_sweep_kernel";
+    case PK_PERSIST: return "attn_mfma_persist_kernel";
+    case PK_MFMA: return "attn_mfma_kernel";
+    case PK_RAGGED: return "attn_mfma_ragged_kernel";
+    default: return "attn_generic_kernel";
+  }
 }
 
 size_t cls_scores_workspace_bytes(const ns_attn_desc *desc) {

@@ -156,7 +156,12 @@ __global__ __launch_bounds__(64, 2) void attn_mfma_persist_kernel(PersistParams 
     char *ob;
   };
   auto open_query = [&](Query &c, int j) {          // j-th query tile of this wave, clamped to the last
-    const int t = lo + slot + min(j, nq_wave - 1) * slots;
+    // (the slot is rotated from one query tile to the next, so that a wave does not stay in one
+    // block column: border columns have fewer key tiles)
+    const int jj = min(j, nq_wave - 1);
+    const int base = lo + jj * slots;
+    const int width = min(slots, hi - base);
+    const int t = base + NS_U((slot + 37 * jj) % width);
     const int img = NS_U(t / p.tiles_per_image), rem = t - img * p.tiles_per_image;
     const int b = NS_U(img / p.heads), h = img - b * p.heads;
     const int blk = rem / TPB;               // TPB is a power of two
@@ -214,18 +219,25 @@ __global__ __launch_bounds__(64, 2) void attn_mfma_persist_kernel(PersistParams 
 #pragma unroll
       for (int s = 0; s < 4; s++) qf[nt][s] = *(lds_bf16x8_ptr)(wlds + QSLOT + nt * 4096 + krd[s]);
   };
-  // the global token initialises the state: m = its logit (the fixed exponent reference),
-  // l = 1, O = v_0.  k0: channels 32*hh + 8*s + j; v0: channels 32*dt + 8*ig + 4*hh + e.
+  auto read_k_half = [&](bf16x8 (&kf)[4], uint32_t off) {     // off: byte offset of the half-slot
+#pragma unroll
+    for (int s = 0; s < 4; s++) kf[s] = *(lds_bf16x8_ptr)(wlds + KRING + krd[s] + off);
+  };
+  auto stage_a = [&](const bf16x8 (&kf)[4], int nt) {
+    f32x16 s = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < 4; ks++) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[nt][ks], s, 0, 0, 0);
+    return s;
+  };
+  // The global token initialises the state: m = its logit (the fixed exponent reference), l = 1,
+  // O = v_0.  k0: channels 32*hh + 8*s + j, i.e. the fragment of a key tile whose 32 rows are all
+  // k_0, so every register of its product with Q is q . k_0: the reference comes out of the same
+  // MFMA as all the other logits.  v0: channels 32*dt + 8*ig + 4*hh + e.
   auto init_state = [&](const bf16x8 (&k0)[4], const u32x2 (&v0)[2][4]) {
 #pragma unroll
     for (int nt = 0; nt < 2; nt++) {
-      float acc = 0.f;
-#pragma unroll
-      for (int s = 0; s < 4; s++)
-#pragma unroll
-        for (int j = 0; j < 8; j++) acc = __builtin_fmaf((float)qf[nt][s][j], (float)k0[s][j], acc);
-      acc = hswap_sum(acc);
-      m[nt] = acc * p.c;
+      const f32x16 s = stage_a(k0, nt);
+      m[nt] = s[0] * p.c;
       nm[nt] = -m[nt];
       l[nt] = hh == 0 ? 1.f : 0.f;
       la[nt][0] = 0.f; la[nt][1] = 0.f;
@@ -253,16 +265,6 @@ __global__ __launch_bounds__(64, 2) void attn_mfma_persist_kernel(PersistParams 
       for (int ig = 0; ig < 4; ig++)
         v0[dt][ig] = *(u32x2 __attribute__((address_space(3))) *)(wlds + V0ROW + 64 * dt + 16 * ig + 8 * hh);
     init_state(k0, v0);
-  };
-  auto read_k_half = [&](bf16x8 (&kf)[4], uint32_t off) {     // off: byte offset of the half-slot
-#pragma unroll
-    for (int s = 0; s < 4; s++) kf[s] = *(lds_bf16x8_ptr)(wlds + KRING + krd[s] + off);
-  };
-  auto stage_a = [&](const bf16x8 (&kf)[4], int nt) {
-    f32x16 s = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int ks = 0; ks < 4; ks++) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[nt][ks], s, 0, 0, 0);
-    return s;
   };
   auto stage_b = [&](const f32x16 &s, int nt, bf16x8 (&pf)[2]) {
 #pragma unroll

@@ -1,0 +1,447 @@
+// bf16 MFMA neighbourhood attention for 8x8 blocks: a workgroup sweeps a row of query blocks and
+// shares every key tile among the query blocks that need it (gfx950).
+//
+// Why.  With one wave per query block and private key tiles, every K and V tile is fetched from
+// L2 nine times (once per query block of its neighbourhood); measured, that L2 -> LDS traffic
+// (about 1 GB per launch on a 128 x 128 grid with batch 2 and 16 heads) costs as much time as
+// the arithmetic.  Here a workgroup of 4 waves owns one row of blocks of one (batch, head) image.
+// It walks the key blocks of the three block rows R-1, R, R+1 column by column; each key tile is
+// brought into LDS once (direct global -> LDS transfers, XOR-swizzled, 3-slot ring) and used by
+// the query blocks of columns c-1, c, c+1.  Wave w owns query blocks w, w+4, w+8, ...: a block q
+// is busy during columns q-1 .. q+1, the wave then has one column off, in which it normalises
+// and stores q and loads the rows of q+4.  So three of the four waves compute at any time, every
+// key tile costs a third of the L2 traffic, and with two workgroups per CU (two waves per SIMD)
+// the off-time of one wave is the other's compute time.
+//
+// Mathematics and register formulation are those of ns_attn_mfma.hip: S^T = K Q^T and
+// O^T += V^T P^T with v_mfma_f32_32x32x16_bf16, P kept in registers, the global token's logit as
+// fixed exponent reference, a check for overflow at the end of each query block and a redo with
+// a running maximum for the (rare) blocks that fail it.
+//
+// Synchronisation: one s_barrier per key tile.  Each wave issues a quarter of a tile's transfers
+// and waits for its own share (vector memory operations complete in issue order, so
+// "at most N outstanding" means all but the N youngest have arrived); the barrier then makes the
+// tile visible to all and, at the same time, tells that everybody is done with the slot that
+// the next transfer overwrites.
+#include "ns_common.h"
+
+namespace ns {
+
+namespace {
+
+struct SweepParams {
+  const uint16_t *q, *k, *v;
+  uint16_t *out;
+  int64_t qsb, qsh, qst, osb, osh, ost;
+  float c;              // scale * log2(e)
+  int grid_w, nbh, nbw;
+  int heads;
+  int strips;           // batch * heads * nbh
+};
+
+typedef s16x4 __attribute__((address_space(3))) *lds_s16x4_ptr;
+typedef bf16x8 __attribute__((address_space(3))) *lds_bf16x8_ptr;
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr uint32_t kSlot = 16384;     // one key tile: K [64][64] bf16, then V [64][64] bf16
+constexpr uint32_t kVOff = 8192;
+constexpr int kSlots = 3;
+constexpr uint32_t kK0Row = 3 * 16384;         // k_0 in the first 128 bytes of a 1 KB transfer
+constexpr uint32_t kV0Row = 3 * 16384 + 1024;  // v_0 likewise
+
+__device__ __forceinline__ float sswap_max(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float sswap_sum(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+// 16 bytes per lane, global -> LDS at lds + 16*lane, no registers.
+__device__ __forceinline__ void sdma16(const char *base, uint32_t voff, uint32_t lds) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(lds), "v"(voff), "s"(base) : "memory", "m0");
+}
+// 8 bytes per lane to global memory, issued from asm so that it is exactly one request.
+__device__ __forceinline__ void sstore8(void *ptr, u32x2 v) {
+  asm volatile("global_store_dwordx2 %0, %1, off" :: "v"(ptr), "v"(v) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void swait_vm() {
+  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+
+#define NS_U(x) __builtin_amdgcn_readfirstlane(x)
+
+// grid: one workgroup of 256 threads per strip (row of blocks of one image)
+__global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
+  const int tid = threadIdx.x, wave = NS_U(tid >> 6), lane = tid & 63;
+  const int l32 = lane & 31, hh = lane >> 5;
+
+  // consecutive strips (neighbouring block rows of one image share two of their three key rows)
+  // go to the same XCD: workgroups are dealt round-robin to the 8 XCDs
+  int sid = blockIdx.x;
+  if (p.strips % 8 == 0) sid = (sid & 7) * (p.strips / 8) + (sid >> 3);
+  const int img = NS_U(sid / p.nbh), R = sid - img * p.nbh;
+  const int b = NS_U(img / p.heads), h = img - b * p.heads;
+  const char *qb = reinterpret_cast<const char *>(p.q + b * p.qsb + h * p.qsh);
+  const char *kb = reinterpret_cast<const char *>(p.k + b * p.qsb + h * p.qsh);
+  const char *vb = reinterpret_cast<const char *>(p.v + b * p.qsb + h * p.qsh);
+  char *ob = reinterpret_cast<char *>(p.out + b * p.osb + h * p.osh);
+
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const uint32_t lds_base = (uint32_t)(size_t)((__attribute__((address_space(3))) unsigned char *)smem);
+
+  const uint32_t rowB = (uint32_t)p.qst * 2u;
+  const uint32_t gridrowB = (uint32_t)p.grid_w * rowB;
+  // token (grid row 8*Rb + i/8, grid column 8*Cb + i%8) is row i of the tile of block (Rb, Cb)
+  auto block_token = [&](int Rb, int Cb) { return 1 + Rb * 8 * p.grid_w + Cb * 8; };
+  auto block_base = [&](int Rb, int Cb) { return (uint32_t)block_token(Rb, Cb) * rowB; };
+  auto tile_off = [&](int i) { return (uint32_t)((i >> 3) * p.grid_w + (i & 7)) * rowB; };
+
+  // ---- per-lane constants
+  // transfers: request `it` of a tile is its rows 8*it .. 8*it+7 (one grid row of the block);
+  // LDS slot `lane` holds row it*8 + lane/8, physical 16-byte chunk lane%8, which is logical chunk
+  // (lane%8) ^ ((row>>1)&7) for K and (lane%8) ^ 4*((row>>1)&1) for V.  This wave issues requests
+  // 2*wave and 2*wave+1 of K and of V; (row>>1)&7 = (4*(it&1) + (lane/8 >> 1)) & 7.
+  const int drow = lane >> 3;
+  const uint32_t dma_koff[2] = {drow * rowB + 16u * ((lane & 7) ^ ((drow >> 1) & 7)),
+                                drow * rowB + 16u * ((lane & 7) ^ ((4 + (drow >> 1)) & 7))};
+  const uint32_t dma_voff = drow * rowB + 16u * ((lane & 7) ^ (((drow >> 1) & 1) << 2));
+  // K fragment reads: lane (row l32 [+32], half hh) needs logical chunks 4*hh + s
+  uint32_t krd[4];
+#pragma unroll
+  for (int s = 0; s < 4; s++) krd[s] = l32 * 128 + 16 * ((4 * hh + s) ^ ((l32 >> 1) & 7));
+  // V transposed reads (see ns_attn_mfma.hip for the layout argument)
+  uint32_t vrd[2][2];
+  {
+    const int g = lane >> 4, s = lane & 15;
+    const int dbyte = (16 * (g & 1) + 4 * (s & 3)) * 2;
+#pragma unroll
+    for (int half = 0; half < 2; half++) {
+      const int key = 8 * half + 4 * hh + (s >> 2);
+      const int off = key * 128 + (dbyte ^ (((key >> 1) & 1) << 6));
+      vrd[0][half] = kVOff + off;
+      vrd[1][half] = kVOff + (off ^ 64);
+    }
+  }
+  const uint32_t qoff0 = tile_off(l32) + 64u * hh;
+  const uint32_t qoff1 = tile_off(l32 + 32) + 64u * hh;
+
+  // ---- the key tiles of this strip, column by column
+  const int r0 = max(R - 1, 0), r1 = min(R + 1, p.nbh - 1);
+  const int nr = r1 - r0 + 1, ncols = p.nbw, steps = ncols * nr;
+  // this wave's share (4 requests) of the transfers of the next key tile in column-major order
+  // into the next ring slot; past the last tile it repeats that one (into a slot nobody reads)
+  int ic = 0, ir = 0, islot = 0;     // column, row within the column and ring slot of the tile to request
+  auto issue_next = [&]() {
+    const uint32_t base = block_base(r0 + ir, ic);
+    const uint32_t dst = lds_base + (uint32_t)islot * kSlot + (uint32_t)wave * 2048u;
+#pragma unroll
+    for (int j = 0; j < 2; j++) {
+      const char *src = kb + base + (size_t)(2 * wave + j) * gridrowB;
+      sdma16(src, dma_koff[j], dst + j * 1024);
+    }
+#pragma unroll
+    for (int j = 0; j < 2; j++) {
+      const char *src = vb + base + (size_t)(2 * wave + j) * gridrowB;
+      sdma16(src, dma_voff, dst + kVOff + j * 1024);
+    }
+    islot = islot == kSlots - 1 ? 0 : islot + 1;
+    const bool last = ic == ncols - 1 && ir == nr - 1;
+    const bool wrap = ir == nr - 1;
+    ic = last ? ic : (wrap ? ic + 1 : ic);
+    ir = last ? ir : (wrap ? 0 : ir + 1);
+  };
+
+  // ---- register state of the query block in progress
+  bf16x8 qf[2][4];
+  f32x16 o[2][2];
+  float m[2], l[2], nm[2], la[2][2];
+
+  auto stage_a = [&](const bf16x8 (&kf)[4], int nt) {
+    f32x16 s = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < 4; ks++) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[nt][ks], s, 0, 0, 0);
+    return s;
+  };
+  auto stage_b = [&](const f32x16 &s, int nt, bf16x8 (&pf)[2]) {
+#pragma unroll
+    for (int i = 0; i < 16; i += 2) {
+      const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], p.c, nm[nt]));
+      const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i + 1], p.c, nm[nt]));
+      la[nt][0] += p0;
+      la[nt][1] += p1;
+      const bf16x2 pk = __builtin_bit_cast(bf16x2, pack_bf16(p0, p1));
+      pf[i >> 3][i & 7] = pk[0];
+      pf[i >> 3][(i & 7) + 1] = pk[1];
+    }
+  };
+  // O^T[:, nt] += V^T[:, keys 32*mt ..] P^T; slot: byte offset of the key tile's ring slot
+  auto stage_c = [&](int mt, int nt, const bf16x8 (&pf)[2], uint32_t slot) {
+#pragma unroll
+    for (int sp = 0; sp < 2; sp++)
+#pragma unroll
+      for (int dt = 0; dt < 2; dt++) {
+        const uint32_t off = slot + (2 * mt + sp) * 2048;
+        const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(smem + vrd[dt][0] + off));
+        const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(smem + vrd[dt][1] + off));
+        const bf16x4 a = __builtin_bit_cast(bf16x4, lo4), b2 = __builtin_bit_cast(bf16x4, hi4);
+        const bf16x8 vf = {a[0], a[1], a[2], a[3], b2[0], b2[1], b2[2], b2[3]};
+        o[dt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[sp], o[dt][nt], 0, 0, 0);
+      }
+  };
+  // Q fragments of query block qc by ordinary loads
+  auto load_block = [&](int qc) {
+    const char *t = qb + block_base(R, qc);
+#pragma unroll
+    for (int s = 0; s < 4; s++) {
+      qf[0][s] = *reinterpret_cast<const bf16x8 *>(t + qoff0 + 16 * s);
+      qf[1][s] = *reinterpret_cast<const bf16x8 *>(t + qoff1 + 16 * s);
+    }
+  };
+  // The state the global token gives a query block: m = its logit (the fixed exponent reference),
+  // l = 1, O = v_0.  k_0 and v_0 sit in LDS for the whole strip.  The k_0 fragment is that of a
+  // key tile whose rows are all k_0, so every register of its product with Q is q . k_0.
+  auto init_block = [&]() {
+    bf16x8 k0[4];
+#pragma unroll
+    for (int s = 0; s < 4; s++) k0[s] = *(lds_bf16x8_ptr)(smem + kK0Row + 64 * hh + 16 * s);
+#pragma unroll
+    for (int nt = 0; nt < 2; nt++) {
+      const f32x16 s = stage_a(k0, nt);
+      m[nt] = s[0] * p.c;
+      nm[nt] = -m[nt];
+      l[nt] = hh == 0 ? 1.f : 0.f;
+      la[nt][0] = 0.f; la[nt][1] = 0.f;
+    }
+#pragma unroll
+    for (int dt = 0; dt < 2; dt++)
+#pragma unroll
+      for (int ig = 0; ig < 4; ig++) {
+        const u32x2 v2 = *(u32x2 __attribute__((address_space(3))) *)(smem + kV0Row + 64 * dt + 16 * ig + 8 * hh);
+        const bf16x4 v4 = __builtin_bit_cast(bf16x4, v2);
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+          o[dt][0][4 * ig + e] = (float)v4[e];
+          o[dt][1][4 * ig + e] = (float)v4[e];
+        }
+      }
+  };
+  uint32_t badmask = 0;              // bit j: this wave's j-th query block has to be redone
+  // Normalised rows of the finished block, packed: lane (query, hh) owns channels
+  // 32*dt + 8*ig + 4*hh + 0..3.  Also notes whether a weight overflowed the fixed reference
+  // (then some sum or output is not finite).
+  u32x2 packed[2][2][4];
+  auto finish_math = [&](int qc) {
+    l[0] += la[0][0] + la[0][1];
+    l[1] += la[1][0] + la[1][1];
+    float big = fmaxf(fabsf(l[0]), fabsf(l[1]));
+#pragma unroll
+    for (int i = 0; i < 16; i++)
+      big = fmaxf(fmaxf(big, fmaxf(fabsf(o[0][0][i]), fabsf(o[0][1][i]))),
+                  fmaxf(fabsf(o[1][0][i]), fabsf(o[1][1][i])));
+    if (__any(!(big < 1e30f))) badmask |= 1u << (qc >> 2);
+#pragma unroll
+    for (int nt = 0; nt < 2; nt++) {
+      const float inv = 1.f / sswap_sum(l[nt]);
+#pragma unroll
+      for (int dt = 0; dt < 2; dt++)
+#pragma unroll
+        for (int ig = 0; ig < 4; ig++)
+          packed[nt][dt][ig] = u32x2{pack_bf16(o[dt][nt][4 * ig] * inv, o[dt][nt][4 * ig + 1] * inv),
+                                     pack_bf16(o[dt][nt][4 * ig + 2] * inv, o[dt][nt][4 * ig + 3] * inv)};
+    }
+  };
+  constexpr int kStores = 16;        // requests of store_block
+  auto store_block = [&](int qc) {
+    char *t = ob + (size_t)block_token(R, qc) * (size_t)(p.ost * 2);
+#pragma unroll
+    for (int nt = 0; nt < 2; nt++) {
+      const int i = l32 + 32 * nt;
+      char *row = t + (size_t)((i >> 3) * p.grid_w + (i & 7)) * (size_t)(p.ost * 2) + 8 * hh;
+#pragma unroll
+      for (int dt = 0; dt < 2; dt++)
+#pragma unroll
+        for (int ig = 0; ig < 4; ig++) sstore8(row + 64 * dt + 16 * ig, packed[nt][dt][ig]);
+    }
+  };
+
+  // ---- prologue: the first three key tiles are requested, the first has landed
+  int qc = wave;                     // this wave's query block in progress
+  if (wave == 0) {                   // the global token's rows, 8 lanes x 16 bytes each (the other lanes repeat them)
+    sdma16(kb, 16u * (lane & 7), lds_base + kK0Row);
+    sdma16(vb, 16u * (lane & 7), lds_base + kV0Row);
+  }
+  issue_next();
+  issue_next();
+  issue_next();
+  swait_vm<8>();                     // k_0, v_0 and tile 0
+  __syncthreads();
+  // (loading and consuming the rows under ONE condition matters: the compiler places its waits
+  // per program point, not per path, and a load that looks pending at the loop head would put a
+  // full wait into every key tile)
+  if (qc < ncols) {
+    load_block(qc);
+    init_block();
+  }
+
+  int c = 0, ri = 0, cslot = 0;      // column, row within the column and ring slot of key tile s
+  for (int s = 0; s < steps; s++) {
+    const uint32_t slot = (uint32_t)cslot * kSlot;
+    if (qc < ncols && c + 1 >= qc && c <= qc + 1) {
+      // ---- key tile s against this wave's query block
+      bf16x8 kA[4], kB[4], p0[2], p1[2], p2[2], p3[2];
+#pragma unroll
+      for (int t = 0; t < 4; t++) {
+        kA[t] = *(lds_bf16x8_ptr)(smem + slot + krd[t]);
+        kB[t] = *(lds_bf16x8_ptr)(smem + slot + 4096 + krd[t]);
+      }
+      const f32x16 s00 = stage_a(kA, 0);
+      const f32x16 s01 = stage_a(kA, 1);
+      stage_b(s00, 0, p0);
+      const f32x16 s10 = stage_a(kB, 0);
+      stage_b(s01, 1, p1);
+      stage_c(0, 0, p0, slot);
+      const f32x16 s11 = stage_a(kB, 1);
+      stage_b(s10, 0, p2);
+      stage_c(0, 1, p1, slot);
+      stage_b(s11, 1, p3);
+      stage_c(1, 0, p2, slot);
+      stage_c(1, 1, p3, slot);
+      swait_vm<4>();     // tile s+1: this wave's share has landed (its share of tile s+2 may still be in flight)
+    } else if (qc < ncols && c > qc + 1) {
+      // ---- the column off: finish the block, start this wave's next one.  Order: request the
+      // next block's rows, normalise the finished one, consume the rows (that wait also covers
+      // every transfer issued so far), and only then store, so that no wait sees the stores
+      // except the one below, which allows for them.
+      const int qdone = qc;
+      qc += 4;
+      const bool next = qc < ncols;
+      if (next) {
+        load_block(qc);
+        finish_math(qdone);
+        init_block();
+      } else {
+        finish_math(qdone);
+      }
+      store_block(qdone);
+      swait_vm<4 + kStores>();
+    } else {
+      swait_vm<4>();
+    }
+    // everybody's share of tile s+1 has landed; and everybody is done with tile s, whose slot tile s+3 takes
+    __syncthreads();
+    issue_next();
+    cslot = cslot == kSlots - 1 ? 0 : cslot + 1;
+    ri++;
+    if (ri == nr) { ri = 0; c++; }
+  }
+  swait_vm<0>();
+  if (qc < ncols) {                  // the block whose last column was the strip's last
+    finish_math(qc);
+    store_block(qc);
+  }
+  __syncthreads();                   // the ring is free: each wave takes 16 KB of it below
+
+  // ---- query blocks in which a weight overflowed (their stored rows are not finite): once more
+  // with a running maximum, fragments straight from global memory, V staged through LDS
+  const uint32_t mine = (uint32_t)wave * 16384u;
+  for (int j = 0; badmask; j++, badmask >>= 1) {
+    if (!(badmask & 1)) continue;
+    const int qr = wave + 4 * j;
+    load_block(qr);
+    init_block();
+    for (int cc = max(qr - 1, 0); cc <= min(qr + 1, ncols - 1); cc++)
+      for (int rr = r0; rr <= r1; rr++) {
+        const uint32_t base = block_base(rr, cc);
+        bf16x8 kt[2][4];
+#pragma unroll
+        for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+          for (int t = 0; t < 4; t++)
+            kt[mt][t] = *reinterpret_cast<const bf16x8 *>(kb + base + mt * 4 * gridrowB + qoff0 + 16 * t);
+#pragma unroll
+        for (int it = 0; it < 8; it++)
+          sdma16(vb + base + (size_t)it * gridrowB, dma_voff, lds_base + mine + kVOff + it * 1024);
+        swait_vm<0>();               // also the K fragments above
+#pragma unroll
+        for (int nt = 0; nt < 2; nt++) {
+          const f32x16 s0 = stage_a(kt[0], nt), s1 = stage_a(kt[1], nt);
+          float mx0 = fmaxf(s0[0], s0[1]), mx1 = fmaxf(s1[0], s1[1]);
+#pragma unroll
+          for (int e = 2; e < 16; e += 2) {
+            mx0 = fmaxf(fmaxf(mx0, s0[e]), s0[e + 1]);
+            mx1 = fmaxf(fmaxf(mx1, s1[e]), s1[e + 1]);
+          }
+          const float m_new = fmaxf(m[nt], sswap_max(fmaxf(mx0, mx1)) * p.c);
+          const float alpha = __builtin_amdgcn_exp2f(m[nt] - m_new);
+          m[nt] = m_new;
+          const float nmm = -m_new;
+          float ls = 0.f;
+          bf16x8 pa[2], pb[2];
+#pragma unroll
+          for (int e = 0; e < 16; e += 2) {
+            const float a0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s0[e], p.c, nmm));
+            const float a1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s0[e + 1], p.c, nmm));
+            const float b0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[e], p.c, nmm));
+            const float b1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[e + 1], p.c, nmm));
+            ls += (a0 + a1) + (b0 + b1);
+            const bf16x2 ka = __builtin_bit_cast(bf16x2, pack_bf16(a0, a1));
+            const bf16x2 kb2 = __builtin_bit_cast(bf16x2, pack_bf16(b0, b1));
+            pa[e >> 3][e & 7] = ka[0]; pa[e >> 3][(e & 7) + 1] = ka[1];
+            pb[e >> 3][e & 7] = kb2[0]; pb[e >> 3][(e & 7) + 1] = kb2[1];
+          }
+          l[nt] = __builtin_fmaf(l[nt], alpha, ls);
+#pragma unroll
+          for (int e = 0; e < 16; e++) { o[0][nt][e] *= alpha; o[1][nt][e] *= alpha; }
+          stage_c(0, nt, pa, mine);
+          stage_c(1, nt, pb, mine);
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // V reads done before the next transfer into the slot
+      }
+    const uint32_t keep = badmask;
+    finish_math(qr);                 // (its overflow note is void here)
+    badmask = keep;
+    store_block(qr);
+  }
+}
+
+}  // namespace
+
+bool sweep_attn_supported(const ns_attn_desc &d) {
+  return mfma_attn_supported(d) && d.block == 8;
+}
+
+ns_status launch_attn_sweep(const AttnArgs &a) {
+  const ns_attn_desc &d = a.d;
+  SweepParams p;
+  p.q = static_cast<const uint16_t *>(a.q);
+  p.k = static_cast<const uint16_t *>(a.k);
+  p.v = static_cast<const uint16_t *>(a.v);
+  p.out = static_cast<uint16_t *>(a.out);
+  p.qsb = d.q_stride_b; p.qsh = d.q_stride_h; p.qst = d.q_stride_t;
+  p.osb = d.out_stride_b; p.osh = d.out_stride_h; p.ost = d.out_stride_t;
+  p.c = d.scale * kLog2e;
+  p.grid_w = d.grid_w;
+  p.nbh = d.grid_h / 8;
+  p.nbw = d.grid_w / 8;
+  p.heads = d.heads;
+  const long long strips = (long long)d.batch * d.heads * p.nbh;
+  if (strips > 0x7fffffffLL) return fail(NS_ERR_UNSUPPORTED, "launch grid too large");
+  // a wave records the query blocks it has to redo in a 32-bit mask
+  if (p.nbw > 128) return launch_attn_mfma(a);
+  p.strips = (int)strips;
+  static bool attr_set = false;
+  const int lds = 4 * 16384;        // three ring slots and the global token's rows; the redo gives each wave a slot
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(attn_sweep_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+      return fail(NS_ERR_HIP, "cannot reserve %d bytes of LDS", lds);
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(attn_sweep_kernel, dim3((unsigned)strips), dim3(256), lds, a.stream, p);
+  return check_launch("attn_sweep_kernel");
+}
+
+}  // namespace ns

@@ -103,6 +103,8 @@ bool mfma_attn_supported(const ns_attn_desc &d);
 ns_status launch_attn_mfma(const AttnArgs &a);
 bool persist_attn_supported(const ns_attn_desc &d);
 ns_status launch_attn_persist(const AttnArgs &a);
+bool sweep_attn_supported(const ns_attn_desc &d);    // 8x8 blocks: key tiles shared along a row of blocks
+ns_status launch_attn_sweep(const AttnArgs &a);
 bool ragged_attn_supported(const ns_attn_desc &d);   // pruned sequence, blocks of at most 8x8
 ns_status launch_attn_ragged(const AttnArgs &a);
 

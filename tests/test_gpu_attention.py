@@ -150,18 +150,35 @@ def test_invalid_call_launches_nothing(nb):
     assert bool((out == 7.0).all())
 
 
-@pytest.mark.parametrize("gh,gw,block", [(24, 40, 8), (8, 8, 8), (32, 32, 16), (48, 48, 8), (64, 64, 8)])
-def test_persistent_kernel_variant(nb, gh, gw, block, monkeypatch):
-    # the alternative persistent-wave kernel computes the same function
-    monkeypatch.setenv("NSATTN_KERNEL", "persist")
+@pytest.mark.parametrize("variant", ["mfma", "persist", "sweep"])
+@pytest.mark.parametrize("gh,gw,block", [(24, 40, 8), (8, 8, 8), (32, 32, 16), (48, 48, 8), (64, 64, 8), (96, 64, 16), (16, 72, 8), (40, 8, 8)])
+def test_persistent_kernel_variant(nb, gh, gw, block, variant, monkeypatch):
+    # the persistent-wave kernels compute the same function (grids too small for them fall back)
+    monkeypatch.setenv("NSATTN_KERNEL", variant)
     run_case(nb, 303, 2, 5, gh, gw, block, "bf16")
 
 
-def test_persistent_kernel_variant_overflow_fallback(nb, monkeypatch):
-    monkeypatch.setenv("NSATTN_KERNEL", "persist")
+@pytest.mark.parametrize("variant", ["mfma", "persist", "sweep"])
+def test_persistent_kernel_variant_overflow_fallback(nb, variant, monkeypatch):
+    monkeypatch.setenv("NSATTN_KERNEL", variant)
     q, k, v = synth.small_case(7, 1, 2, 64, 16, 16, "bf16")
     q = synth.round_to_bf16(q * 12.0)
     ref = oracle.ns_attn(q, k, v, 16, 16, 8, 1.0)
     out = nb.ns_attn_forward(*(to_dev(a, "bf16") for a in (q, k, v)), 16, 16, 8, 1.0)
     torch.cuda.synchronize()
+    assert np.isfinite(to_np(out)).all()
     assert_attn_close(to_np(out), ref, "bf16", "large logits, persistent kernel")
+
+
+@pytest.mark.parametrize("variant", ["mfma", "persist", "sweep"])
+def test_persistent_kernel_partial_overflow(nb, variant, monkeypatch):
+    """Only some query tiles overflow the fixed exponent reference: those are redone, the others not."""
+    monkeypatch.setenv("NSATTN_KERNEL", variant)
+    q, k, v = synth.small_case(11, 1, 3, 64, 32, 32, "bf16")
+    q[:, :, 1 + 5 * 32:1 + 9 * 32] *= 14.0          # a band of grid rows with large logits
+    q = synth.round_to_bf16(q)
+    ref = oracle.ns_attn(q, k, v, 32, 32, 8, 1.0)
+    out = nb.ns_attn_forward(*(to_dev(a, "bf16") for a in (q, k, v)), 32, 32, 8, 1.0)
+    torch.cuda.synchronize()
+    assert np.isfinite(to_np(out)).all()
+    assert_attn_close(to_np(out), ref, "bf16", "partly large logits, persistent kernel")
