@@ -4,6 +4,7 @@
 #include <stdlib.h>
 
 #include "ns_common.h"
+#include <algorithm>
 
 namespace ns {
 
@@ -85,7 +86,9 @@ AttnWorkspace attn_workspace_layout(const ns_attn_desc &d) {
   AttnWorkspace w;
   size_t off = 0;
   w.partials_off = off;
-  off += align_up((size_t)d.batch * d.heads * cls_num_chunks(d.tokens) * kClsPartialFloats * 4, 256);
+  // (the sweep kernel leaves 4 records per row of blocks instead of one per 512 keys)
+  const size_t nrec = std::max<size_t>(cls_num_chunks(d.tokens), d.block > 0 ? 4 * (size_t)((d.grid_h + d.block - 1) / d.block) : 0);
+  off += align_up((size_t)d.batch * d.heads * nrec * kClsPartialFloats * 4, 256);
   w.lists_off = w.counts_off = off;
   if (d.coords) {
     const size_t nbh = (d.grid_h + d.block - 1) / d.block, nbw = (d.grid_w + d.block - 1) / d.block;
@@ -155,7 +158,7 @@ static PatchKernel choose_patch_kernel(const ns_attn_desc &d, bool have_lists) {
 
 static ns_status launch_patch_attention(const AttnArgs &a) {
   switch (choose_patch_kernel(a.d, a.geom.lists != nullptr)) {
-    case PK_SWEEP: return launch_attn_sweep(a);
+    case PK_SWEEP: return launch_attn_sweep(a, nullptr, nullptr);
     case PK_PERSIST: return launch_attn_persist(a);
     case PK_MFMA: return launch_attn_mfma(a);
     case PK_RAGGED: return launch_attn_ragged(a);
@@ -217,6 +220,12 @@ ns_status ns::attn_forward_impl(const ns_attn_desc *desc, const void *q, const v
   ns_status st = prepare_attn(desc, q, k, v, out, workspace, workspace_bytes, stream, a, partials, reuse_lists);
   if (st != NS_OK) return st;
   const ns_attn_desc &d = a.d;
+  if (choose_patch_kernel(d, a.geom.lists != nullptr) == PK_SWEEP) {
+    // this kernel computes the global query's partials and logits on the way
+    st = launch_attn_sweep(a, cls_logits, partials);
+    if (st != NS_OK) return st;
+    return launch_cls_combine(d, partials, out, cls_lse, true, a.stream, sweep_cls_chunks(d));
+  }
   st = launch_patch_attention(a);
   if (st != NS_OK) return st;
   // the global query's row: chunk partials, then the merge that also writes out[:, :, 0, :]
@@ -240,7 +249,9 @@ ns_status ns_attn_patch_kernel_time(const ns_attn_desc *desc, const void *q, con
   if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
     return fail(NS_ERR_HIP, "hipEventCreate failed");
   hipEventRecord(e0, a.stream);
-  for (int i = 0; i < reps && st == NS_OK; i++) st = launch_patch_attention(a);
+  const bool sweep = choose_patch_kernel(a.d, a.geom.lists != nullptr) == PK_SWEEP;
+  for (int i = 0; i < reps && st == NS_OK; i++)
+    st = sweep ? launch_attn_sweep(a, nullptr, partials) : launch_patch_attention(a);
   hipEventRecord(e1, a.stream);
   hipError_t e = hipEventSynchronize(e1);
   float ms = 0.f;

@@ -18,6 +18,14 @@
 // fixed exponent reference, a check for overflow at the end of each query block and a redo with
 // a running maximum for the (rare) blocks that fail it.
 //
+// The global (CLS) query rides along: it attends to every key, and every key tile of block row R
+// passes through the LDS of strip R exactly once.  In column c the wave that has its column off,
+// (c+2) mod 4, multiplies that tile with q_0 as well (the same two MFMA products with q_0 in every
+// column of the B operand), keeps a running (max, sum, weighted V sum) for the global query in
+// LDS and writes the raw logits.  Each wave leaves one partial record per strip in the format of
+// the chunked row kernel; cls_combine_kernel merges them.  K and V are thus read once per launch
+// instead of twice.
+//
 // Synchronisation: one s_barrier per key tile.  Each wave issues a quarter of a tile's transfers
 // and waits for its own share (vector memory operations complete in issue order, so
 // "at most N outstanding" means all but the N youngest have arrived); the barrier then makes the
@@ -37,6 +45,10 @@ struct SweepParams {
   int grid_w, nbh, nbw;
   int heads;
   int strips;           // batch * heads * nbh
+  int tokens;
+  float scale;
+  float *cls_logits;    // [B,H,T] raw logits of the global query, or NULL
+  float *cls_partials;  // [B,H,4*nbh,66] softmax partials of the global query, or NULL: no global row
 };
 
 typedef s16x4 __attribute__((address_space(3))) *lds_s16x4_ptr;
@@ -48,6 +60,10 @@ constexpr uint32_t kVOff = 8192;
 constexpr int kSlots = 3;
 constexpr uint32_t kK0Row = 3 * 16384;         // k_0 in the first 128 bytes of a 1 KB transfer
 constexpr uint32_t kV0Row = 3 * 16384 + 1024;  // v_0 likewise
+constexpr uint32_t kQ0Row = 3 * 16384 + 2048;  // q_0 likewise
+constexpr uint32_t kClsState = 3 * 16384 + 3072;   // per wave 512 B: o[64], m, l of the global query's partial
+constexpr uint32_t kClsLogit = 3 * 16384 + 3072 + 4 * 512;   // per wave 256 B: a tile's 64 logits
+constexpr float kEmptyMax = -1e30f;
 
 __device__ __forceinline__ float sswap_max(float x) {
   auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
@@ -61,6 +77,10 @@ __device__ __forceinline__ float sswap_sum(float x) {
 __device__ __forceinline__ void sdma16(const char *base, uint32_t voff, uint32_t lds) {
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
                :: "s"(lds), "v"(voff), "s"(base) : "memory", "m0");
+}
+// 4 bytes per lane to global memory, one request.
+__device__ __forceinline__ void sstore4(void *ptr, float v) {
+  asm volatile("global_store_dword %0, %1, off" :: "v"(ptr), "v"(v) : "memory");
 }
 // 8 bytes per lane to global memory, issued from asm so that it is exactly one request.
 __device__ __forceinline__ void sstore8(void *ptr, u32x2 v) {
@@ -267,16 +287,141 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
     }
   };
 
+  // ---- the global query's share of a key tile (see the head of the file).  State in LDS per
+  // wave: o[64] in channel order, then the running maximum (log2 domain) and the sum.
+  float *const cls_state = reinterpret_cast<float *>(smem + kClsState + wave * 512);
+  float *const cls_logit = reinterpret_cast<float *>(smem + kClsLogit + wave * 256);
+  float *const logit_row = p.cls_logits ? p.cls_logits + ((size_t)b * p.heads + h) * p.tokens : nullptr;
+  auto cls_duty = [&](uint32_t slot, int col, bool with_global_key) {
+    // q_0 as B operand, the same in all 32 columns: channels 32*hh + 8*s + j
+    bf16x8 q0f[4], kA[4], kB[4];
+#pragma unroll
+    for (int t = 0; t < 4; t++) {
+      q0f[t] = *(lds_bf16x8_ptr)(smem + kQ0Row + 64 * hh + 16 * t);
+      kA[t] = *(lds_bf16x8_ptr)(smem + slot + krd[t]);
+      kB[t] = *(lds_bf16x8_ptr)(smem + slot + 4096 + krd[t]);
+    }
+    f32x16 sa = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, sb = sa;
+#pragma unroll
+    for (int ks = 0; ks < 4; ks++) {
+      sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kA[ks], q0f[ks], sa, 0, 0, 0);
+      sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kB[ks], q0f[ks], sb, 0, 0, 0);
+    }
+    // register e of sa is key 8*(e/4) + 4*hh + e%4 of the tile (sb: + 32), whatever the column
+    if (logit_row) {
+      if (l32 == 0) {
+#pragma unroll
+        for (int g = 0; g < 4; g++) {
+          const f32x4 va = {sa[4 * g] * p.scale, sa[4 * g + 1] * p.scale, sa[4 * g + 2] * p.scale, sa[4 * g + 3] * p.scale};
+          const f32x4 vb2 = {sb[4 * g] * p.scale, sb[4 * g + 1] * p.scale, sb[4 * g + 2] * p.scale, sb[4 * g + 3] * p.scale};
+          *reinterpret_cast<f32x4 *>(cls_logit + 8 * g + 4 * hh) = va;
+          *reinterpret_cast<f32x4 *>(cls_logit + 32 + 8 * g + 4 * hh) = vb2;
+        }
+      }
+      // lane = key of the tile: token (grid row 8R + lane/8, grid column 8*col + lane%8)
+      const float x = cls_logit[lane];
+      sstore4(logit_row + block_token(R, col) + (lane >> 3) * p.grid_w + (lane & 7), x);
+    }
+    float mx = fmaxf(sa[0], sb[0]);
+#pragma unroll
+    for (int e = 1; e < 16; e++) mx = fmaxf(mx, fmaxf(sa[e], sb[e]));
+    mx = sswap_max(mx) * p.c;
+    float m2 = cls_state[64], l0 = cls_state[65];
+    float k0logit = 0.f;
+    if (with_global_key) {
+      // key 0 (the global token itself) belongs to the first tile of the image
+      bf16x8 k0[4];
+#pragma unroll
+      for (int t = 0; t < 4; t++) k0[t] = *(lds_bf16x8_ptr)(smem + kK0Row + 64 * hh + 16 * t);
+      f32x16 s0 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < 4; ks++) s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0[ks], q0f[ks], s0, 0, 0, 0);
+      k0logit = s0[0];
+      mx = fmaxf(mx, k0logit * p.c);
+      if (logit_row && lane == 0) sstore4(logit_row, k0logit * p.scale);
+    }
+    const float m_new = fmaxf(m2, mx);
+    const float alpha = __builtin_amdgcn_exp2f(m2 - m_new), nmm = -m_new;
+    float ls = 0.f;
+    bf16x8 pa[2], pb[2];
+#pragma unroll
+    for (int e = 0; e < 16; e += 2) {
+      const float a0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sa[e], p.c, nmm));
+      const float a1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sa[e + 1], p.c, nmm));
+      const float b0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sb[e], p.c, nmm));
+      const float b1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sb[e + 1], p.c, nmm));
+      ls += (a0 + a1) + (b0 + b1);
+      const bf16x2 ka = __builtin_bit_cast(bf16x2, pack_bf16(a0, a1));
+      const bf16x2 kb2 = __builtin_bit_cast(bf16x2, pack_bf16(b0, b1));
+      pa[e >> 3][e & 7] = ka[0]; pa[e >> 3][(e & 7) + 1] = ka[1];
+      pb[e >> 3][e & 7] = kb2[0]; pb[e >> 3][(e & 7) + 1] = kb2[1];
+    }
+    ls = sswap_sum(ls);                       // the two half-waves hold different keys
+    // O (one column's worth, the same in every column): channel 32*dt + 8*(e/4) + 4*hh + e%4
+    f32x16 oc[2];
+#pragma unroll
+    for (int dt = 0; dt < 2; dt++)
+#pragma unroll
+      for (int g = 0; g < 4; g++) {
+        const f32x4 v = *reinterpret_cast<const f32x4 *>(cls_state + 32 * dt + 8 * g + 4 * hh);
+#pragma unroll
+        for (int e = 0; e < 4; e++) oc[dt][4 * g + e] = v[e] * alpha;
+      }
+    float pk0 = 0.f;
+    if (with_global_key) {
+      pk0 = __builtin_amdgcn_exp2f(__builtin_fmaf(k0logit, p.c, nmm));
+      ls += pk0;
+#pragma unroll
+      for (int dt = 0; dt < 2; dt++)
+#pragma unroll
+        for (int g = 0; g < 4; g++) {
+          const u32x2 v2 = *(u32x2 __attribute__((address_space(3))) *)(smem + kV0Row + 64 * dt + 16 * g + 8 * hh);
+          const bf16x4 v4 = __builtin_bit_cast(bf16x4, v2);
+#pragma unroll
+          for (int e = 0; e < 4; e++) oc[dt][4 * g + e] = __builtin_fmaf(pk0, (float)v4[e], oc[dt][4 * g + e]);
+        }
+    }
+#pragma unroll
+    for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+      for (int sp = 0; sp < 2; sp++)
+#pragma unroll
+        for (int dt = 0; dt < 2; dt++) {
+          const uint32_t off = slot + (2 * mt + sp) * 2048;
+          const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(smem + vrd[dt][0] + off));
+          const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(smem + vrd[dt][1] + off));
+          const bf16x4 a = __builtin_bit_cast(bf16x4, lo4), b2 = __builtin_bit_cast(bf16x4, hi4);
+          const bf16x8 vf = {a[0], a[1], a[2], a[3], b2[0], b2[1], b2[2], b2[3]};
+          oc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, mt == 0 ? pa[sp] : pb[sp], oc[dt], 0, 0, 0);
+        }
+    if (l32 == 0) {
+#pragma unroll
+      for (int dt = 0; dt < 2; dt++)
+#pragma unroll
+        for (int g = 0; g < 4; g++) {
+          const f32x4 v = {oc[dt][4 * g], oc[dt][4 * g + 1], oc[dt][4 * g + 2], oc[dt][4 * g + 3]};
+          *reinterpret_cast<f32x4 *>(cls_state + 32 * dt + 8 * g + 4 * hh) = v;
+        }
+      if (hh == 0) {
+        cls_state[64] = m_new;
+        cls_state[65] = __builtin_fmaf(l0, alpha, ls);
+      }
+    }
+  };
+
   // ---- prologue: the first three key tiles are requested, the first has landed
   int qc = wave;                     // this wave's query block in progress
   if (wave == 0) {                   // the global token's rows, 8 lanes x 16 bytes each (the other lanes repeat them)
     sdma16(kb, 16u * (lane & 7), lds_base + kK0Row);
     sdma16(vb, 16u * (lane & 7), lds_base + kV0Row);
+    sdma16(qb, 16u * (lane & 7), lds_base + kQ0Row);
   }
+  cls_state[lane] = 0.f;             // this wave's partial of the global query: nothing seen yet
+  if (lane < 2) cls_state[64 + lane] = lane == 0 ? kEmptyMax : 0.f;
   issue_next();
   issue_next();
   issue_next();
-  swait_vm<8>();                     // k_0, v_0 and tile 0
+  swait_vm<8>();                     // k_0, v_0, q_0 and tile 0
   __syncthreads();
   // (loading and consuming the rows under ONE condition matters: the compiler places its waits
   // per program point, not per path, and a load that looks pending at the loop head would put a
@@ -289,6 +434,7 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
   int c = 0, ri = 0, cslot = 0;      // column, row within the column and ring slot of key tile s
   for (int s = 0; s < steps; s++) {
     const uint32_t slot = (uint32_t)cslot * kSlot;
+    int extra = 0;                   // stores issued in this step
     if (qc < ncols && c + 1 >= qc && c <= qc + 1) {
       // ---- key tile s against this wave's query block
       bf16x8 kA[4], kB[4], p0[2], p1[2], p2[2], p3[2];
@@ -309,7 +455,7 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
       stage_b(s11, 1, p3);
       stage_c(1, 0, p2, slot);
       stage_c(1, 1, p3, slot);
-      swait_vm<4>();     // tile s+1: this wave's share has landed (its share of tile s+2 may still be in flight)
+      extra = 0;
     } else if (qc < ncols && c > qc + 1) {
       // ---- the column off: finish the block, start this wave's next one.  Order: request the
       // next block's rows, normalise the finished one, consume the rows (that wait also covers
@@ -326,9 +472,22 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
         finish_math(qdone);
       }
       store_block(qdone);
-      swait_vm<4 + kStores>();
-    } else {
-      swait_vm<4>();
+      extra = kStores;
+    }
+    // the global query's share of the tile of this strip's own block row: the wave that has column c off
+    if (p.cls_partials && ri == R - r0 && wave == ((c + 2) & 3)) {
+      const bool first = R == 0 && c == 0;
+      cls_duty(slot, c, first);
+      if (logit_row) extra += first ? 2 : 1;
+    }
+    // tile s+1: this wave's share has landed (its share of tile s+2 and the stores above may still be in flight)
+    switch (extra) {
+      case 0: swait_vm<4>(); break;
+      case 1: swait_vm<5>(); break;
+      case 2: swait_vm<6>(); break;
+      case kStores: swait_vm<4 + kStores>(); break;
+      case kStores + 1: swait_vm<5 + kStores>(); break;
+      default: swait_vm<6 + kStores>(); break;
     }
     // everybody's share of tile s+1 has landed; and everybody is done with tile s, whose slot tile s+3 takes
     __syncthreads();
@@ -338,6 +497,15 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
     if (ri == nr) { ri = 0; c++; }
   }
   swait_vm<0>();
+  if (p.cls_partials) {
+    // this wave's partial of the global query's row: (max, sum, weighted V sum), natural-log units
+    float *rec = p.cls_partials + ((((size_t)b * p.heads + h) * (4 * p.nbh)) + (size_t)R * 4 + wave) * kClsPartialFloats;
+    rec[2 + lane] = cls_state[lane];
+    if (lane == 0) {
+      rec[0] = cls_state[64] * kLn2;
+      rec[1] = cls_state[65];
+    }
+  }
   if (qc < ncols) {                  // the block whose last column was the strip's last
     finish_math(qc);
     store_block(qc);
@@ -410,10 +578,10 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
 }  // namespace
 
 bool sweep_attn_supported(const ns_attn_desc &d) {
-  return mfma_attn_supported(d) && d.block == 8;
+  return mfma_attn_supported(d) && d.block == 8 && d.grid_w / 8 <= 128;
 }
 
-ns_status launch_attn_sweep(const AttnArgs &a) {
+ns_status launch_attn_sweep(const AttnArgs &a, float *cls_logits, float *cls_partials) {
   const ns_attn_desc &d = a.d;
   SweepParams p;
   p.q = static_cast<const uint16_t *>(a.q);
@@ -427,10 +595,14 @@ ns_status launch_attn_sweep(const AttnArgs &a) {
   p.nbh = d.grid_h / 8;
   p.nbw = d.grid_w / 8;
   p.heads = d.heads;
+  p.tokens = d.tokens;
+  p.scale = d.scale;
+  p.cls_logits = cls_logits;
+  p.cls_partials = cls_partials;
   const long long strips = (long long)d.batch * d.heads * p.nbh;
   if (strips > 0x7fffffffLL) return fail(NS_ERR_UNSUPPORTED, "launch grid too large");
   // a wave records the query blocks it has to redo in a 32-bit mask
-  if (p.nbw > 128) return launch_attn_mfma(a);
+  if (p.nbw > 128) return fail(NS_ERR_UNSUPPORTED, "more than 128 blocks per grid row");
   p.strips = (int)strips;
   static bool attr_set = false;
   const int lds = 4 * 16384;        // three ring slots and the global token's rows; the redo gives each wave a slot

@@ -212,8 +212,8 @@ ns_status launch_cls_row(const ns_attn_desc &d, const void *q, const void *k, co
 }
 
 ns_status launch_cls_combine(const ns_attn_desc &d, const float *partials, void *out, float *lse,
-                             bool with_v, hipStream_t s) {
-  const int nch = cls_num_chunks(d.tokens);
+                             bool with_v, hipStream_t s, int nchunks) {
+  const int nch = nchunks > 0 ? nchunks : cls_num_chunks(d.tokens);
   dim3 grid(d.heads, d.batch), blk(256);
   if (d.dtype == NS_F32) {
     if (with_v)

@@ -104,7 +104,10 @@ ns_status launch_attn_mfma(const AttnArgs &a);
 bool persist_attn_supported(const ns_attn_desc &d);
 ns_status launch_attn_persist(const AttnArgs &a);
 bool sweep_attn_supported(const ns_attn_desc &d);    // 8x8 blocks: key tiles shared along a row of blocks
-ns_status launch_attn_sweep(const AttnArgs &a);
+// cls_partials != NULL: the kernel also computes the global query's row, [B,H,4*nbh,66] partial records
+// (sweep_cls_chunks of them per head-image) and, with cls_logits, its raw logits [B,H,T]
+ns_status launch_attn_sweep(const AttnArgs &a, float *cls_logits, float *cls_partials);
+inline int sweep_cls_chunks(const ns_attn_desc &d) { return 4 * (d.grid_h / 8); }
 bool ragged_attn_supported(const ns_attn_desc &d);   // pruned sequence, blocks of at most 8x8
 ns_status launch_attn_ragged(const AttnArgs &a);
 
@@ -116,7 +119,7 @@ constexpr int kClsPartialFloats = 2 + 64;
 ns_status launch_cls_row(const ns_attn_desc &d, const void *q, const void *k, const void *v,
                          float *logits /* [B,H,T] */, float *partials, bool with_v, hipStream_t s);
 ns_status launch_cls_combine(const ns_attn_desc &d, const float *partials, void *out, float *lse,
-                             bool with_v, hipStream_t s);
+                             bool with_v, hipStream_t s, int nchunks = 0 /* 0: cls_num_chunks(tokens) */);
 // lse given directly, or (lse == nullptr) recomputed from the row kernel's partials
 ns_status launch_cls_scores(int B, int H, int T, int G, const float *logits, const float *lse,
                             const float *partials, int nchunks, float *scores, hipStream_t s);

@@ -126,8 +126,13 @@ def test_pruned_sequence_mfma_kernel(nb, monkeypatch, g, block, shuffle, gain):
     assert_attn_close(to_np(out_g), ref, "bf16", "pruned sequence, FMA kernel")
 
 
-def test_cls_by_products_and_determinism(nb):
-    gh = gw = 24
+@pytest.mark.parametrize("variant,gh,gw", [(None, 24, 24), ("sweep", 24, 24), ("sweep", 16, 40), ("sweep", 8, 8),
+                                           ("sweep", 40, 8), ("persist", 24, 24), ("mfma", 24, 24)])
+def test_cls_by_products_and_determinism(nb, monkeypatch, variant, gh, gw):
+    """Global-query by-products (raw logits, log-sum-exp) and its output row, for every way they are
+    produced: the chunked row kernel, and the sweep kernel that computes them on the way."""
+    if variant:
+        monkeypatch.setenv("NSATTN_KERNEL", variant)
     q, k, v = synth.small_case(55, 2, 4, 64, gh, gw, "bf16")
     dq, dk, dv = (to_dev(a, "bf16") for a in (q, k, v))
     out1, logits, lse = nb.ns_attn_forward(dq, dk, dv, gh, gw, 8, 0.125, want_cls=True)
@@ -135,6 +140,8 @@ def test_cls_by_products_and_determinism(nb):
     out3 = nb.ns_attn_forward(dq, dk, dv, gh, gw, 8, 0.125)
     torch.cuda.synchronize()
     assert torch.equal(out1, out2) and torch.equal(out2, out3), "results must be bit-identical across runs"
+    ref = oracle.ns_attn(q, k, v, gh, gw, 8, 0.125)
+    assert_attn_close(to_np(out1)[:, :, :1], ref[:, :, :1], "bf16", "global query row")
     _, ref_logits, ref_lse = oracle.cls_scores(q, k, 0.125, want_logits=True)
     np.testing.assert_allclose(to_np(logits), ref_logits, rtol=0, atol=2e-5)
     np.testing.assert_allclose(to_np(lse), ref_lse, rtol=0, atol=2e-5)
