@@ -125,7 +125,8 @@ size_t ns_attn_workspace_bytes(const ns_attn_desc *desc) {
 
 // Kernel choice for the patch queries.  On the full grid with bf16, head_dim 64 and 8x8 or 16x16
 // blocks there are three MFMA kernels that compute the same function: the sweep (8x8 blocks; key
-// tiles shared along a row of blocks; wants at least two rows of blocks per CU to fill the chip),
+// tiles shared along a row of blocks, the global query's row computed on the way; wants at least
+// one row of blocks per CU),
 // the persistent one-wave-per-SIMD kernel (needs two blocks per grid side), and the plain
 // one-wave-per-query-tile kernel.  A pruned sequence takes the MFMA kernel for block lists when
 // the blocks are at most 8x8, and everything else the fp32 FMA kernel.
@@ -148,7 +149,7 @@ static PatchKernel choose_patch_kernel(const ns_attn_desc &d, bool have_lists) {
     if (force == 's' && sweep_ok) return PK_SWEEP;
     if (force == 'p' && persist_ok) return PK_PERSIST;
     if (force == 'm') return PK_MFMA;
-    if (sweep_ok && strips >= 2LL * num_cus) return PK_SWEEP;
+    if (sweep_ok && strips >= num_cus) return PK_SWEEP;
     if (persist_ok) return PK_PERSIST;
     return PK_MFMA;
   }

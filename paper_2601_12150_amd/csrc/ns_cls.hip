@@ -169,18 +169,34 @@ __global__ __launch_bounds__(256) void cls_scores_kernel(const float *logits, co
                                                          int T_, int G, float *scores) {
   __shared__ float s_lse[1024];
   const int b = blockIdx.y, tid = threadIdx.x;
-  for (int h = tid; h < H; h += 256) {
-    if (lse) {
-      s_lse[h] = lse[(size_t)b * H + h];
-    } else {
+  if (lse) {
+    for (int h = tid; h < H; h += 256) s_lse[h] = lse[(size_t)b * H + h];
+  } else {
+    // 16 lanes per head: each merges every 16th record, then the 16 are merged pairwise (fixed order)
+    const int sub = tid & 15;
+    for (int h = tid >> 4; h < H; h += 16) {
       const float *rec = partials + ((size_t)b * H + h) * nchunks * kClsPartialFloats;
-      float M = -INFINITY;
-      for (int c = 0; c < nchunks; c++) M = fmaxf(M, rec[c * kClsPartialFloats]);
-      float L = 0.f;
-      for (int c = 0; c < nchunks; c++)
-        L = __builtin_fmaf(rec[c * kClsPartialFloats + 1],
-                           __builtin_amdgcn_exp2f((rec[c * kClsPartialFloats] - M) * kLog2e), L);
-      s_lse[h] = M + __builtin_amdgcn_logf(L) * kLn2;
+      float M = -INFINITY, L = 0.f;
+      for (int c = sub; c < nchunks; c += 16) {
+        const float mc = rec[c * kClsPartialFloats], lc = rec[c * kClsPartialFloats + 1];
+        const float Mn = fmaxf(M, mc);
+        L = L * __builtin_amdgcn_exp2f((M - Mn) * kLog2e) + lc * __builtin_amdgcn_exp2f((mc - Mn) * kLog2e);
+        M = Mn;
+      }
+#pragma unroll
+      for (int sft = 1; sft < 16; sft <<= 1) {
+        const float Mo = __shfl_xor(M, sft), Lo = __shfl_xor(L, sft);
+        const float Mn = fmaxf(M, Mo);
+        // a lane without records has M = -inf, L = 0: its weight is exp2(-inf) = 0 unless both are
+        // empty, which cannot happen for all 16 (there is at least one record)
+        const float wa = Mn == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((M - Mn) * kLog2e);
+        const float wb = Mn == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((Mo - Mn) * kLog2e);
+        // both lanes of a pair must add in the same order to agree bit for bit
+        const bool lowl = (sub & sft) == 0;
+        L = lowl ? L * wa + Lo * wb : Lo * wb + L * wa;
+        M = Mn;
+      }
+      if (sub == 0) s_lse[h] = M + __builtin_amdgcn_logf(L) * kLn2;
     }
   }
   __syncthreads();
