@@ -172,18 +172,24 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_reg_kernel(const floa
     return (uint32_t)__builtin_amdgcn_readlane((int)t, 15);
   };
   uint32_t tau = 0;
+  int slot = 0;      // exchange buffer of the next block_total (they alternate)
   for (int bit = 31; bit >= 0; bit--) {
     const uint32_t cand = tau | (1u << bit);
     uint32_t c = 0;   // wave-uniform: lives in a scalar register
 #pragma unroll
     for (int i = 0; i < KPT; i++) c += (uint32_t)__popcll(__ballot(key[i] >= cand));   // padding keys are 0 < cand
-    if (block_total(c, bit & 1) >= (uint32_t)k) tau = cand;
+    const uint32_t tot = block_total(c, slot);
+    slot ^= 1;
+    if (tot >= (uint32_t)k) tau = cand;
+    // exactly k keys are >= cand: they are the kept set, the remaining bits of the k-th key do
+    // not matter (below, every key >= tau is then either above it or one of `need` equal ones)
+    if (tot == (uint32_t)k) break;
   }
   uint32_t cg = 0;
 #pragma unroll
   for (int i = 0; i < KPT; i++) cg += (uint32_t)__popcll(__ballot(key[i] > tau));
   // every score above tau is kept; of those equal to it, the first `need` in index order
-  const uint32_t need = (uint32_t)k - block_total(cg, 1);   // slot 1: slot 0 may still be read (bit 0)
+  const uint32_t need = (uint32_t)k - block_total(cg, slot);
   // index order = (i, wave, lane); count per (i, wave), scan, then place
 #pragma unroll
   for (int i = 0; i < KPT; i++) {
