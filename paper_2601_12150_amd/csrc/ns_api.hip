@@ -249,16 +249,16 @@ ns_status ns_attn_patch_kernel_time(const ns_attn_desc *desc, const void *q, con
   hipEvent_t e0, e1;
   if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
     return fail(NS_ERR_HIP, "hipEventCreate failed");
-  hipEventRecord(e0, a.stream);
+  hipError_t e = hipEventRecord(e0, a.stream);
   const bool sweep = choose_patch_kernel(a.d, a.geom.lists != nullptr) == PK_SWEEP;
   for (int i = 0; i < reps && st == NS_OK; i++)
     st = sweep ? launch_attn_sweep(a, nullptr, partials) : launch_patch_attention(a);
-  hipEventRecord(e1, a.stream);
-  hipError_t e = hipEventSynchronize(e1);
+  if (e == hipSuccess) e = hipEventRecord(e1, a.stream);
+  if (e == hipSuccess) e = hipEventSynchronize(e1);
   float ms = 0.f;
   if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
-  hipEventDestroy(e0);
-  hipEventDestroy(e1);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
   if (st != NS_OK) return st;
   if (e != hipSuccess) return fail(NS_ERR_HIP, "event timing: %s", hipGetErrorString(e));
   *avg_ms = ms / (float)reps;

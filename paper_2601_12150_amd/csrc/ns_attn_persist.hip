@@ -1,5 +1,6 @@
 // Persistent bf16 MFMA neighbourhood attention for patch queries on the full grid (gfx950).
-// Selected with NSATTN_KERNEL=persist (see launch_patch_attention for the default).
+// The default for full grids with at least two blocks per side where the sweep kernel does not apply
+// (choose_patch_kernel in ns_api.hip); NSATTN_KERNEL=persist forces it.
 //
 // Same mathematics and register formulation as ns_attn_mfma.hip (transposed products, P kept in
 // registers, fixed exponent reference with a checked fallback); what differs is how the chip is
@@ -146,8 +147,7 @@ __global__ __launch_bounds__(64, 2) void attn_mfma_persist_kernel(PersistParams 
       vrd[1][half] = VRING + (off ^ 64);
     }
   }
-  const uint32_t qoff0 = (uint32_t)tile_off(l32) * rowB + 64u * hh;
-  const uint32_t qoff1 = (uint32_t)tile_off(l32 + 32) * rowB + 64u * hh;
+  const uint32_t qoff0 = (uint32_t)tile_off(l32) * rowB + 64u * hh;   // K rows straight from global memory (redo path)
 
   // ---- query tiles and key tiles as scalar descriptors
   struct Query {

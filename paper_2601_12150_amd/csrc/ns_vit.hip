@@ -145,8 +145,6 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(GemmParams p) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's share of tile kt has landed
     __syncthreads();                                    // everyone's has; everyone is done with tile kt-1
     if (kt + 1 < nk) issue(kt + 1, stage ^ 1);
-    const unsigned char *sa = nullptr;
-    (void)sa;
     bf16x8 fa[2][4], fw[2][4];
 #pragma unroll
     for (int t = 0; t < 2; t++)

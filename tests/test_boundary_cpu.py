@@ -101,3 +101,39 @@ def test_topk_and_scores_validation(nb):
     d = good_desc(nb)
     assert L.cls_scores(ctypes.byref(d), FAKE, FAKE, None, FAKE, 1 << 30, None) == nb.NS_ERR_INVALID_ARG
     assert L.cls_scores_workspace_bytes(ctypes.byref(d)) > 0
+
+
+def test_kernel_choice_policy(nb, monkeypatch):
+    """Which kernel serves which problem (host logic; without a device the CU count defaults to 256)."""
+    monkeypatch.delenv("NSATTN_KERNEL", raising=False)
+
+    def desc(B, H, g, block, dtype=None, coords=False):
+        d = nb.ns_attn_desc()
+        d.batch, d.heads, d.head_dim = B, H, 64
+        d.grid_h = d.grid_w = g
+        d.block, d.radius, d.n_global = block, 1, 1
+        d.dtype = nb.NS_BF16 if dtype is None else dtype
+        d.tokens = 1 + g * g if not coords else 1 + (g * g) // 2
+        d.scale = 0.125
+        T = d.tokens
+        d.q_stride_b, d.q_stride_h, d.q_stride_t = H * T * 64, T * 64, 64
+        d.out_stride_b, d.out_stride_h, d.out_stride_t = H * T * 64, T * 64, 64
+        d.coords = 0x40000 if coords else None
+        return d
+
+    name = lambda d: nb.lib.ns_attn_patch_kernel_name(ctypes.byref(d)).decode()
+    assert name(desc(2, 16, 128, 8)) == "attn_sweep_kernel"            # 512 rows of blocks
+    assert name(desc(1, 4, 24, 8)) == "attn_mfma_persist_kernel"        # too few rows of blocks for the sweep
+    assert name(desc(1, 16, 256, 16)) == "attn_mfma_persist_kernel"     # 16x16 blocks
+    assert name(desc(1, 2, 8, 8)) == "attn_mfma_kernel"                 # a single block
+    assert name(desc(1, 2, 24, 8, dtype=nb.NS_F32)) == "attn_generic_kernel"
+    assert name(desc(1, 2, 24, 4)) == "attn_generic_kernel"             # 4x4 blocks on the full grid
+    assert name(desc(1, 2, 24, 8, coords=True)) == "attn_mfma_ragged_kernel"
+    assert name(desc(1, 2, 32, 16, coords=True)) == "attn_generic_kernel"
+    monkeypatch.setenv("NSATTN_KERNEL", "mfma")
+    assert name(desc(2, 16, 128, 8)) == "attn_mfma_kernel"
+    monkeypatch.setenv("NSATTN_KERNEL", "persist")
+    assert name(desc(2, 16, 128, 8)) == "attn_mfma_persist_kernel"
+    bad = desc(2, 16, 128, 8)
+    bad.heads = 0
+    assert name(bad) == ""
