@@ -2,6 +2,8 @@
 something that is not the oracle -- a dense masked attention whose mask is written on
 pixel coordinates, a library attention routine, closed forms and invariants of the
 pattern described in the paper's "Memory-Efficiency Optimization" section."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -73,9 +75,13 @@ def test_pair_count_closed_form(gh, gw, block):
     assert oracle.count_pairs(1 + N, gw, block) == expect
 
 
-def test_survey_pair_counts_of_the_first_two_configs():
-    assert oracle.count_pairs(785, 28, 7) == 241669
-    assert oracle.count_pairs(4097, 64, 8) == 1990657
+def test_pair_counts_of_the_workload_grids():
+    """tests/golden/pair_counts.txt: counts fixed by the pattern for the measured grids."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "pair_counts.txt")
+    rows = [line.split() for line in open(path) if line.strip() and not line.startswith("#")]
+    assert len(rows) >= 3
+    for tokens, grid_w, block, pairs in rows:
+        assert oracle.count_pairs(int(tokens), int(grid_w), int(block)) == int(pairs)
 
 
 def test_locality_keys_outside_the_neighbourhood_do_not_matter():
