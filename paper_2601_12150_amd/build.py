@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libnsattn.so")
-SOURCES = ["ns_api.hip", "ns_attn_generic.hip", "ns_attn_mfma.hip", "ns_attn_persist.hip", "ns_attn_sweep.hip", "ns_attn_ragged.hip", "ns_gemm256.hip", "ns_cls.hip", "ns_topk.hip",
+SOURCES = ["ns_api.hip", "ns_attn_generic.hip", "ns_attn_mfma.hip", "ns_attn_persist.hip", "ns_attn_sweep.hip", "ns_attn_block16.hip", "ns_attn_ragged.hip", "ns_gemm256.hip", "ns_cls.hip", "ns_topk.hip",
            "ns_vit.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",

@@ -127,11 +127,12 @@ size_t ns_attn_workspace_bytes(const ns_attn_desc *desc) {
 // blocks there are three MFMA kernels that compute the same function: the sweep (8x8 blocks; key
 // tiles shared along a row of blocks, the global query's row computed on the way; wants at least
 // one row of blocks per CU),
-// the persistent one-wave-per-SIMD kernel (needs two blocks per grid side), and the plain
+// the block kernel (16x16 blocks; key tiles shared by a block's four query tiles; wants two blocks
+// per CU), the persistent one-wave-per-SIMD kernel (needs two blocks per grid side), and the plain
 // one-wave-per-query-tile kernel.  A pruned sequence takes the MFMA kernel for block lists when
 // the blocks are at most 8x8, and everything else the fp32 FMA kernel.
-// NSATTN_KERNEL = sweep | persist | mfma | generic forces one of them where it applies.
-enum PatchKernel { PK_SWEEP, PK_PERSIST, PK_MFMA, PK_RAGGED, PK_GENERIC };
+// NSATTN_KERNEL = sweep | block | persist | mfma | generic forces one of them where it applies.
+enum PatchKernel { PK_SWEEP, PK_BLOCK16, PK_PERSIST, PK_MFMA, PK_RAGGED, PK_GENERIC };
 
 static PatchKernel choose_patch_kernel(const ns_attn_desc &d, bool have_lists) {
   const char *e = getenv("NSATTN_KERNEL");
@@ -146,10 +147,14 @@ static PatchKernel choose_patch_kernel(const ns_attn_desc &d, bool have_lists) {
     }
     const long long strips = (long long)d.batch * d.heads * (d.grid_h / d.block);
     const bool sweep_ok = sweep_attn_supported(d), persist_ok = persist_attn_supported(d);
+    const long long blocks = strips * (d.grid_w / d.block);
+    const bool block16_ok = block16_attn_supported(d);
     if (force == 's' && sweep_ok) return PK_SWEEP;
+    if (force == 'b' && block16_ok) return PK_BLOCK16;
     if (force == 'p' && persist_ok) return PK_PERSIST;
     if (force == 'm') return PK_MFMA;
     if (sweep_ok && strips >= num_cus) return PK_SWEEP;
+    if (block16_ok && blocks >= 2LL * num_cus) return PK_BLOCK16;
     if (persist_ok) return PK_PERSIST;
     return PK_MFMA;
   }
@@ -160,6 +165,7 @@ static PatchKernel choose_patch_kernel(const ns_attn_desc &d, bool have_lists) {
 static ns_status launch_patch_attention(const AttnArgs &a) {
   switch (choose_patch_kernel(a.d, a.geom.lists != nullptr)) {
     case PK_SWEEP: return launch_attn_sweep(a, nullptr, nullptr);
+    case PK_BLOCK16: return launch_attn_block16(a);
     case PK_PERSIST: return launch_attn_persist(a);
     case PK_MFMA: return launch_attn_mfma(a);
     case PK_RAGGED: return launch_attn_ragged(a);
@@ -269,6 +275,7 @@ const char *ns_attn_patch_kernel_name(const ns_attn_desc *desc) {
   if (validate_desc(desc, true) != NS_OK) return "";
   switch (choose_patch_kernel(*desc, desc->coords != nullptr)) {
     case PK_SWEEP: return "attn_sweep_kernel";
+    case PK_BLOCK16: return "attn_block16_kernel";
     case PK_PERSIST: return "attn_mfma_persist_kernel";
     case PK_MFMA: return "attn_mfma_kernel";
     case PK_RAGGED: return "attn_mfma_ragged_kernel";

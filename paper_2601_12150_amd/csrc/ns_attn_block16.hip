@@ -1,0 +1,382 @@
+// bf16 MFMA neighbourhood attention for 16x16 blocks: the four 64-query tiles of a query block
+// share every key tile (gfx950).
+//
+// A 16x16 block is four tiles of 64 tokens (4 grid rows of 16), and all four have the same
+// neighbourhood: the up to 9 x 4 key tiles of the 3x3 blocks around it.  A workgroup of 4 waves
+// owns one query block, wave w its tile w; the key tiles pass through a 3-slot LDS ring (direct
+// global -> LDS transfers, a quarter of each issued by every wave, XOR-swizzled) and every wave
+// uses every one of them: one fetch from L2 instead of four, and no wave ever idles.  One
+// s_barrier per key tile makes the tile visible to all and frees the slot that the next transfer
+// overwrites.  Mathematics, register formulation, fixed exponent reference and the redo of query
+// tiles that overflow it are those of ns_attn_mfma.hip / ns_attn_sweep.hip.
+#include "ns_common.h"
+
+namespace ns {
+
+namespace {
+
+struct BlockParams {
+  const uint16_t *q, *k, *v;
+  uint16_t *out;
+  int64_t qsb, qsh, qst, osb, osh, ost;
+  float c;              // scale * log2(e)
+  int grid_w, nbh, nbw;
+  int heads;
+  int blocks;           // batch * heads * nbh * nbw
+};
+
+typedef s16x4 __attribute__((address_space(3))) *lds_s16x4_ptr;
+typedef bf16x8 __attribute__((address_space(3))) *lds_bf16x8_ptr;
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr uint32_t kSlot = 16384;     // one key tile: K [64][64] bf16, then V [64][64] bf16
+constexpr uint32_t kVOff = 8192;
+constexpr int kSlots = 3;
+constexpr uint32_t kK0Row = 3 * 16384;         // k_0 in the first 128 bytes of a 1 KB transfer
+constexpr uint32_t kV0Row = 3 * 16384 + 1024;  // v_0 likewise
+
+__device__ __forceinline__ float bswap_max(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float bswap_sum(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+// 16 bytes per lane, global -> LDS at lds + 16*lane, no registers.
+__device__ __forceinline__ void bdma16(const char *base, uint32_t voff, uint32_t lds) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(lds), "v"(voff), "s"(base) : "memory", "m0");
+}
+// 4 bytes per lane to global memory, one request.
+__device__ __forceinline__ void bstore4(void *ptr, float v) {
+  asm volatile("global_store_dword %0, %1, off" :: "v"(ptr), "v"(v) : "memory");
+}
+// 8 bytes per lane to global memory, issued from asm so that it is exactly one request.
+__device__ __forceinline__ void bstore8(void *ptr, u32x2 v) {
+  asm volatile("global_store_dwordx2 %0, %1, off" :: "v"(ptr), "v"(v) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void bwait_vm() {
+  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+
+#define NS_U(x) __builtin_amdgcn_readfirstlane(x)
+
+// grid: one workgroup of 256 threads per query block
+__global__ __launch_bounds__(256, 2) void attn_block16_kernel(BlockParams p) {
+  const int tid = threadIdx.x, wave = NS_U(tid >> 6), lane = tid & 63;
+  const int l32 = lane & 31, hh = lane >> 5;
+
+  // consecutive blocks (raster order within an image) go to the same XCD: workgroups are dealt
+  // round-robin to the 8 XCDs, and neighbouring query blocks share most of their key tiles
+  int bid = blockIdx.x;
+  if (p.blocks % 8 == 0) bid = (bid & 7) * (p.blocks / 8) + (bid >> 3);
+  const int per_image = p.nbh * p.nbw;
+  const int img = NS_U(bid / per_image), blk = bid - img * per_image;
+  const int R = NS_U(blk / p.nbw), C = blk - R * p.nbw;
+  const int b = NS_U(img / p.heads), h = img - b * p.heads;
+  const char *qb = reinterpret_cast<const char *>(p.q + b * p.qsb + h * p.qsh);
+  const char *kb = reinterpret_cast<const char *>(p.k + b * p.qsb + h * p.qsh);
+  const char *vb = reinterpret_cast<const char *>(p.v + b * p.qsb + h * p.qsh);
+  char *ob = reinterpret_cast<char *>(p.out + b * p.osb + h * p.osh);
+
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const uint32_t lds_base = (uint32_t)(size_t)((__attribute__((address_space(3))) unsigned char *)smem);
+
+  const uint32_t rowB = (uint32_t)p.qst * 2u;
+  const uint32_t gridrowB = (uint32_t)p.grid_w * rowB;
+  // tile `sub` of block (Rb, Cb) is grid rows 16*Rb + 4*sub .. +3, columns 16*Cb .. +15; its row i
+  // is the token at grid row offset i/16, column offset i%16
+  auto tile_token = [&](int Rb, int Cb, int sub) { return 1 + (Rb * 16 + sub * 4) * p.grid_w + Cb * 16; };
+  auto tile_off = [&](int i) { return (uint32_t)((i >> 4) * p.grid_w + (i & 15)) * rowB; };
+
+  // ---- per-lane constants
+  // transfers: request `it` of a tile is its rows 8*it .. 8*it+7 (half a grid row); LDS slot `lane`
+  // holds row it*8 + lane/8, physical 16-byte chunk lane%8, which is logical chunk
+  // (lane%8) ^ ((row>>1)&7) for K and (lane%8) ^ 4*((row>>1)&1) for V.  This wave issues requests
+  // 2*wave and 2*wave+1 (grid row `wave` of the tile) of K and of V.
+  const int drow = lane >> 3;
+  const uint32_t dma_koff[2] = {drow * rowB + 16u * ((lane & 7) ^ ((drow >> 1) & 7)),
+                                drow * rowB + 16u * ((lane & 7) ^ ((4 + (drow >> 1)) & 7))};
+  const uint32_t dma_voff = drow * rowB + 16u * ((lane & 7) ^ (((drow >> 1) & 1) << 2));
+  uint32_t krd[4];
+#pragma unroll
+  for (int s = 0; s < 4; s++) krd[s] = l32 * 128 + 16 * ((4 * hh + s) ^ ((l32 >> 1) & 7));
+  uint32_t vrd[2][2];
+  {
+    const int g = lane >> 4, s = lane & 15;
+    const int dbyte = (16 * (g & 1) + 4 * (s & 3)) * 2;
+#pragma unroll
+    for (int half = 0; half < 2; half++) {
+      const int key = 8 * half + 4 * hh + (s >> 2);
+      const int off = key * 128 + (dbyte ^ (((key >> 1) & 1) << 6));
+      vrd[0][half] = kVOff + off;
+      vrd[1][half] = kVOff + (off ^ 64);
+    }
+  }
+  const uint32_t qoff0 = tile_off(l32) + 64u * hh;
+  const uint32_t qoff1 = tile_off(l32 + 32) + 64u * hh;
+
+  // ---- the key tiles of the (clipped) 3x3 block neighbourhood, block by block, four tiles each
+  const int R0 = max(R - 1, 0), R1 = min(R + 1, p.nbh - 1);
+  const int C0 = max(C - 1, 0), C1 = min(C + 1, p.nbw - 1);
+  const int ncb = C1 - C0 + 1, steps = (R1 - R0 + 1) * ncb * 4;
+  int ir = R0, ic = C0, isub = 0, islot = 0;   // the tile to request next and its ring slot
+  auto issue_next = [&]() {                    // this wave's share (4 requests); past the last tile it repeats that one
+    const uint32_t base = (uint32_t)tile_token(ir, ic, isub) * rowB + (uint32_t)wave * gridrowB;
+    const uint32_t dst = lds_base + (uint32_t)islot * kSlot + (uint32_t)wave * 2048u;
+#pragma unroll
+    for (int j = 0; j < 2; j++) bdma16(kb + base + (size_t)j * 8 * rowB, dma_koff[j], dst + j * 1024);
+#pragma unroll
+    for (int j = 0; j < 2; j++) bdma16(vb + base + (size_t)j * 8 * rowB, dma_voff, dst + kVOff + j * 1024);
+    islot = islot == kSlots - 1 ? 0 : islot + 1;
+    const bool last = ir == R1 && ic == C1 && isub == 3;
+    const bool next_block = isub == 3, next_row = next_block && ic == C1;
+    isub = last ? isub : (next_block ? 0 : isub + 1);
+    ic = last ? ic : (next_row ? C0 : (next_block ? ic + 1 : ic));
+    ir = last ? ir : (next_row ? ir + 1 : ir);
+  };
+
+  // ---- register state of this wave's query tile
+  bf16x8 qf[2][4];
+  f32x16 o[2][2];
+  float m[2], l[2], nm[2], la[2][2];
+
+  auto stage_a = [&](const bf16x8 (&kf)[4], int nt) {
+    f32x16 s = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < 4; ks++) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[nt][ks], s, 0, 0, 0);
+    return s;
+  };
+  auto stage_b = [&](const f32x16 &s, int nt, bf16x8 (&pf)[2]) {
+#pragma unroll
+    for (int i = 0; i < 16; i += 2) {
+      const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], p.c, nm[nt]));
+      const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i + 1], p.c, nm[nt]));
+      la[nt][0] += p0;
+      la[nt][1] += p1;
+      const bf16x2 pk = __builtin_bit_cast(bf16x2, pack_bf16(p0, p1));
+      pf[i >> 3][i & 7] = pk[0];
+      pf[i >> 3][(i & 7) + 1] = pk[1];
+    }
+  };
+  // O^T[:, nt] += V^T[:, keys 32*mt ..] P^T; slot: byte offset of the key tile's ring slot
+  auto stage_c = [&](int mt, int nt, const bf16x8 (&pf)[2], uint32_t slot) {
+#pragma unroll
+    for (int sp = 0; sp < 2; sp++)
+#pragma unroll
+      for (int dt = 0; dt < 2; dt++) {
+        const uint32_t off = slot + (2 * mt + sp) * 2048;
+        const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(smem + vrd[dt][0] + off));
+        const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(smem + vrd[dt][1] + off));
+        const bf16x4 a = __builtin_bit_cast(bf16x4, lo4), b2 = __builtin_bit_cast(bf16x4, hi4);
+        const bf16x8 vf = {a[0], a[1], a[2], a[3], b2[0], b2[1], b2[2], b2[3]};
+        o[dt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[sp], o[dt][nt], 0, 0, 0);
+      }
+  };
+  const char *qtile = qb + (uint32_t)tile_token(R, C, wave) * rowB;
+  auto load_tile = [&]() {
+#pragma unroll
+    for (int s = 0; s < 4; s++) {
+      qf[0][s] = *reinterpret_cast<const bf16x8 *>(qtile + qoff0 + 16 * s);
+      qf[1][s] = *reinterpret_cast<const bf16x8 *>(qtile + qoff1 + 16 * s);
+    }
+  };
+  // The state the global token gives a query tile: m = its logit (the fixed exponent reference),
+  // l = 1, O = v_0; k_0 and v_0 sit in LDS.  The k_0 fragment is that of a key tile whose rows
+  // are all k_0, so every register of its product with Q is q . k_0.
+  auto init_tile = [&]() {
+    bf16x8 k0[4];
+#pragma unroll
+    for (int s = 0; s < 4; s++) k0[s] = *(lds_bf16x8_ptr)(smem + kK0Row + 64 * hh + 16 * s);
+#pragma unroll
+    for (int nt = 0; nt < 2; nt++) {
+      const f32x16 s = stage_a(k0, nt);
+      m[nt] = s[0] * p.c;
+      nm[nt] = -m[nt];
+      l[nt] = hh == 0 ? 1.f : 0.f;
+      la[nt][0] = 0.f; la[nt][1] = 0.f;
+    }
+#pragma unroll
+    for (int dt = 0; dt < 2; dt++)
+#pragma unroll
+      for (int ig = 0; ig < 4; ig++) {
+        const u32x2 v2 = *(u32x2 __attribute__((address_space(3))) *)(smem + kV0Row + 64 * dt + 16 * ig + 8 * hh);
+        const bf16x4 v4 = __builtin_bit_cast(bf16x4, v2);
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+          o[dt][0][4 * ig + e] = (float)v4[e];
+          o[dt][1][4 * ig + e] = (float)v4[e];
+        }
+      }
+  };
+  // normalise and store; returns whether a weight overflowed the fixed reference (then some sum or
+  // output is not finite).  Lane (query, hh) owns channels 32*dt + 8*ig + 4*hh + 0..3.
+  auto finish_tile = [&]() {
+    l[0] += la[0][0] + la[0][1];
+    l[1] += la[1][0] + la[1][1];
+    float big = fmaxf(fabsf(l[0]), fabsf(l[1]));
+#pragma unroll
+    for (int i = 0; i < 16; i++)
+      big = fmaxf(fmaxf(big, fmaxf(fabsf(o[0][0][i]), fabsf(o[0][1][i]))),
+                  fmaxf(fabsf(o[1][0][i]), fabsf(o[1][1][i])));
+    const bool bad = __any(!(big < 1e30f));
+    char *t = ob + (size_t)tile_token(R, C, wave) * (size_t)(p.ost * 2);
+#pragma unroll
+    for (int nt = 0; nt < 2; nt++) {
+      const float inv = 1.f / bswap_sum(l[nt]);
+      const int i = l32 + 32 * nt;
+      char *row = t + (size_t)((i >> 4) * p.grid_w + (i & 15)) * (size_t)(p.ost * 2) + 8 * hh;
+#pragma unroll
+      for (int dt = 0; dt < 2; dt++)
+#pragma unroll
+        for (int ig = 0; ig < 4; ig++) {
+          const u32x2 u = {pack_bf16(o[dt][nt][4 * ig] * inv, o[dt][nt][4 * ig + 1] * inv),
+                           pack_bf16(o[dt][nt][4 * ig + 2] * inv, o[dt][nt][4 * ig + 3] * inv)};
+          *reinterpret_cast<u32x2 *>(row + 64 * dt + 16 * ig) = u;
+        }
+    }
+    return bad;
+  };
+
+  // ---- prologue: the first three key tiles are requested, the first has landed
+  if (wave == 0) {                   // the global token's rows, 8 lanes x 16 bytes each (the other lanes repeat them)
+    bdma16(kb, 16u * (lane & 7), lds_base + kK0Row);
+    bdma16(vb, 16u * (lane & 7), lds_base + kV0Row);
+  }
+  issue_next();
+  issue_next();
+  issue_next();
+  bwait_vm<8>();                     // k_0, v_0 and tile 0
+  __syncthreads();
+  load_tile();                       // consumed at once: no load is pending at the loop head
+  init_tile();
+
+  int cslot = 0;
+  for (int s = 0; s < steps; s++) {
+    const uint32_t slot = (uint32_t)cslot * kSlot;
+    {
+      bf16x8 kA[4], kB[4], p0[2], p1[2], p2[2], p3[2];
+#pragma unroll
+      for (int t = 0; t < 4; t++) {
+        kA[t] = *(lds_bf16x8_ptr)(smem + slot + krd[t]);
+        kB[t] = *(lds_bf16x8_ptr)(smem + slot + 4096 + krd[t]);
+      }
+      const f32x16 s00 = stage_a(kA, 0);
+      const f32x16 s01 = stage_a(kA, 1);
+      stage_b(s00, 0, p0);
+      const f32x16 s10 = stage_a(kB, 0);
+      stage_b(s01, 1, p1);
+      stage_c(0, 0, p0, slot);
+      const f32x16 s11 = stage_a(kB, 1);
+      stage_b(s10, 0, p2);
+      stage_c(0, 1, p1, slot);
+      stage_b(s11, 1, p3);
+      stage_c(1, 0, p2, slot);
+      stage_c(1, 1, p3, slot);
+    }
+    bwait_vm<4>();     // tile s+1: this wave's share has landed (its share of tile s+2 may still be in flight)
+    __syncthreads();   // ... and everybody's; and everybody is done with tile s, whose slot tile s+3 takes
+    issue_next();
+    cslot = cslot == kSlots - 1 ? 0 : cslot + 1;
+  }
+  bwait_vm<0>();
+  const bool bad = finish_tile();
+  __syncthreads();                   // the ring is free: each wave takes 16 KB of it below
+  if (!bad) return;
+
+  // ---- a weight overflowed in this wave's query tile (its stored rows are not finite): once
+  // more with a running maximum, fragments straight from global memory, V staged through LDS
+  const uint32_t mine = (uint32_t)wave * 16384u;
+  load_tile();
+  init_tile();
+  for (int rr = R0; rr <= R1; rr++)
+    for (int cc = C0; cc <= C1; cc++)
+      for (int sub = 0; sub < 4; sub++) {
+        const uint32_t base = (uint32_t)tile_token(rr, cc, sub) * rowB;
+        bf16x8 kt[2][4];
+#pragma unroll
+        for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+          for (int t = 0; t < 4; t++)
+            kt[mt][t] = *reinterpret_cast<const bf16x8 *>(kb + base + mt * 2 * gridrowB + qoff0 + 16 * t);
+#pragma unroll
+        for (int it = 0; it < 8; it++)
+          bdma16(vb + base + (size_t)(it >> 1) * gridrowB + (size_t)(it & 1) * 8 * rowB, dma_voff,
+                 lds_base + mine + kVOff + it * 1024);
+        bwait_vm<0>();               // also the K fragments above
+#pragma unroll
+        for (int nt = 0; nt < 2; nt++) {
+          const f32x16 s0 = stage_a(kt[0], nt), s1 = stage_a(kt[1], nt);
+          float mx0 = fmaxf(s0[0], s0[1]), mx1 = fmaxf(s1[0], s1[1]);
+#pragma unroll
+          for (int e = 2; e < 16; e += 2) {
+            mx0 = fmaxf(fmaxf(mx0, s0[e]), s0[e + 1]);
+            mx1 = fmaxf(fmaxf(mx1, s1[e]), s1[e + 1]);
+          }
+          const float m_new = fmaxf(m[nt], bswap_max(fmaxf(mx0, mx1)) * p.c);
+          const float alpha = __builtin_amdgcn_exp2f(m[nt] - m_new);
+          m[nt] = m_new;
+          const float nmm = -m_new;
+          float ls = 0.f;
+          bf16x8 pa[2], pb[2];
+#pragma unroll
+          for (int e = 0; e < 16; e += 2) {
+            const float a0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s0[e], p.c, nmm));
+            const float a1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s0[e + 1], p.c, nmm));
+            const float b0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[e], p.c, nmm));
+            const float b1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[e + 1], p.c, nmm));
+            ls += (a0 + a1) + (b0 + b1);
+            const bf16x2 ka = __builtin_bit_cast(bf16x2, pack_bf16(a0, a1));
+            const bf16x2 kb2 = __builtin_bit_cast(bf16x2, pack_bf16(b0, b1));
+            pa[e >> 3][e & 7] = ka[0]; pa[e >> 3][(e & 7) + 1] = ka[1];
+            pb[e >> 3][e & 7] = kb2[0]; pb[e >> 3][(e & 7) + 1] = kb2[1];
+          }
+          l[nt] = __builtin_fmaf(l[nt], alpha, ls);
+#pragma unroll
+          for (int e = 0; e < 16; e++) { o[0][nt][e] *= alpha; o[1][nt][e] *= alpha; }
+          stage_c(0, nt, pa, mine);
+          stage_c(1, nt, pb, mine);
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // V reads done before the next transfer into the slot
+      }
+  finish_tile();
+}
+
+}  // namespace
+
+bool block16_attn_supported(const ns_attn_desc &d) {
+  return mfma_attn_supported(d) && d.block == 16;
+}
+
+ns_status launch_attn_block16(const AttnArgs &a) {
+  const ns_attn_desc &d = a.d;
+  BlockParams p;
+  p.q = static_cast<const uint16_t *>(a.q);
+  p.k = static_cast<const uint16_t *>(a.k);
+  p.v = static_cast<const uint16_t *>(a.v);
+  p.out = static_cast<uint16_t *>(a.out);
+  p.qsb = d.q_stride_b; p.qsh = d.q_stride_h; p.qst = d.q_stride_t;
+  p.osb = d.out_stride_b; p.osh = d.out_stride_h; p.ost = d.out_stride_t;
+  p.c = d.scale * kLog2e;
+  p.grid_w = d.grid_w;
+  p.nbh = d.grid_h / 16;
+  p.nbw = d.grid_w / 16;
+  p.heads = d.heads;
+  const long long blocks = (long long)d.batch * d.heads * p.nbh * p.nbw;
+  if (blocks > 0x7fffffffLL) return fail(NS_ERR_UNSUPPORTED, "launch grid too large");
+  p.blocks = (int)blocks;
+  static bool attr_set = false;
+  const int lds = 4 * 16384;        // three ring slots and the global token's rows; the redo gives each wave a slot
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(attn_block16_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+      return fail(NS_ERR_HIP, "cannot reserve %d bytes of LDS", lds);
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(attn_block16_kernel, dim3((unsigned)blocks), dim3(256), lds, a.stream, p);
+  return check_launch("attn_block16_kernel");
+}
+
+}  // namespace ns

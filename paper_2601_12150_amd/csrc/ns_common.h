@@ -108,6 +108,8 @@ bool sweep_attn_supported(const ns_attn_desc &d);    // 8x8 blocks: key tiles sh
 // (sweep_cls_chunks of them per head-image) and, with cls_logits, its raw logits [B,H,T]
 ns_status launch_attn_sweep(const AttnArgs &a, float *cls_logits, float *cls_partials);
 inline int sweep_cls_chunks(const ns_attn_desc &d) { return 4 * (d.grid_h / 8); }
+bool block16_attn_supported(const ns_attn_desc &d);  // 16x16 blocks: key tiles shared by a block's four query tiles
+ns_status launch_attn_block16(const AttnArgs &a);
 bool ragged_attn_supported(const ns_attn_desc &d);   // pruned sequence, blocks of at most 8x8
 ns_status launch_attn_ragged(const AttnArgs &a);
 

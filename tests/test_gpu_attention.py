@@ -157,7 +157,7 @@ def test_invalid_call_launches_nothing(nb):
     assert bool((out == 7.0).all())
 
 
-@pytest.mark.parametrize("variant", ["mfma", "persist", "sweep"])
+@pytest.mark.parametrize("variant", ["mfma", "persist", "sweep", "block"])
 @pytest.mark.parametrize("gh,gw,block", [(24, 40, 8), (8, 8, 8), (32, 32, 16), (48, 48, 8), (64, 64, 8), (96, 64, 16), (16, 72, 8), (40, 8, 8)])
 def test_persistent_kernel_variant(nb, gh, gw, block, variant, monkeypatch):
     # the persistent-wave kernels compute the same function (grids too small for them fall back)
@@ -165,7 +165,7 @@ def test_persistent_kernel_variant(nb, gh, gw, block, variant, monkeypatch):
     run_case(nb, 303, 2, 5, gh, gw, block, "bf16")
 
 
-@pytest.mark.parametrize("variant", ["mfma", "persist", "sweep"])
+@pytest.mark.parametrize("variant", ["mfma", "persist", "sweep", "block"])
 def test_persistent_kernel_variant_overflow_fallback(nb, variant, monkeypatch):
     monkeypatch.setenv("NSATTN_KERNEL", variant)
     q, k, v = synth.small_case(7, 1, 2, 64, 16, 16, "bf16")
@@ -177,7 +177,7 @@ def test_persistent_kernel_variant_overflow_fallback(nb, variant, monkeypatch):
     assert_attn_close(to_np(out), ref, "bf16", "large logits, persistent kernel")
 
 
-@pytest.mark.parametrize("variant", ["mfma", "persist", "sweep"])
+@pytest.mark.parametrize("variant", ["mfma", "persist", "sweep", "block"])
 def test_persistent_kernel_partial_overflow(nb, variant, monkeypatch):
     """Only some query tiles overflow the fixed exponent reference: those are redone, the others not."""
     monkeypatch.setenv("NSATTN_KERNEL", variant)
