@@ -124,7 +124,8 @@ def test_kernel_choice_policy(nb, monkeypatch):
     name = lambda d: nb.lib.ns_attn_patch_kernel_name(ctypes.byref(d)).decode()
     assert name(desc(2, 16, 128, 8)) == "attn_sweep_kernel"            # 512 rows of blocks
     assert name(desc(1, 4, 24, 8)) == "attn_mfma_persist_kernel"        # too few rows of blocks for the sweep
-    assert name(desc(1, 16, 256, 16)) == "attn_mfma_persist_kernel"     # 16x16 blocks
+    assert name(desc(1, 16, 256, 16)) == "attn_block16_kernel"          # 16x16 blocks, 4096 of them
+    assert name(desc(1, 2, 32, 16)) == "attn_mfma_persist_kernel"       # 16x16 blocks, too few for a workgroup each
     assert name(desc(1, 2, 8, 8)) == "attn_mfma_kernel"                 # a single block
     assert name(desc(1, 2, 24, 8, dtype=nb.NS_F32)) == "attn_generic_kernel"
     assert name(desc(1, 2, 24, 4)) == "attn_generic_kernel"             # 4x4 blocks on the full grid
@@ -134,6 +135,9 @@ def test_kernel_choice_policy(nb, monkeypatch):
     assert name(desc(2, 16, 128, 8)) == "attn_mfma_kernel"
     monkeypatch.setenv("NSATTN_KERNEL", "persist")
     assert name(desc(2, 16, 128, 8)) == "attn_mfma_persist_kernel"
+    monkeypatch.setenv("NSATTN_KERNEL", "block")
+    assert name(desc(1, 2, 32, 16)) == "attn_block16_kernel"
+    assert name(desc(2, 16, 128, 8)) != "attn_block16_kernel"           # a forced kernel that cannot serve falls back
     bad = desc(2, 16, 128, 8)
     bad.heads = 0
     assert name(bad) == ""
