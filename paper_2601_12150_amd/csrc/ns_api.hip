@@ -82,6 +82,13 @@ struct AttnWorkspace {
   size_t partials_off, lists_off, counts_off, total;
 };
 
+// Per-block token lists are built for a pruned sequence and for a complete grid that the list
+// kernel serves (bf16, head_dim 64, and either a block side other than 8 and 16 or a grid that the
+// block side does not divide).
+bool wants_lists(const ns_attn_desc &d) {
+  return d.coords != nullptr || (!mfma_attn_supported(d) && ragged_attn_supported(d));
+}
+
 AttnWorkspace attn_workspace_layout(const ns_attn_desc &d) {
   AttnWorkspace w;
   size_t off = 0;
@@ -90,7 +97,7 @@ AttnWorkspace attn_workspace_layout(const ns_attn_desc &d) {
   const size_t nrec = std::max<size_t>(cls_num_chunks(d.tokens), d.block > 0 ? 4 * (size_t)((d.grid_h + d.block - 1) / d.block) : 0);
   off += align_up((size_t)d.batch * d.heads * nrec * kClsPartialFloats * 4, 256);
   w.lists_off = w.counts_off = off;
-  if (d.coords) {
+  if (wants_lists(d)) {
     const size_t nbh = (d.grid_h + d.block - 1) / d.block, nbw = (d.grid_w + d.block - 1) / d.block;
     off += align_up((size_t)d.batch * nbh * nbw * d.block * d.block * 4, 256);
     w.counts_off = off;
@@ -129,14 +136,16 @@ size_t ns_attn_workspace_bytes(const ns_attn_desc *desc) {
 // one row of blocks per CU),
 // the block kernel (16x16 blocks; key tiles shared by a block's four query tiles; wants two blocks
 // per CU), the persistent one-wave-per-SIMD kernel (needs two blocks per grid side), and the plain
-// one-wave-per-query-tile kernel.  A pruned sequence takes the MFMA kernel for block lists when
-// the blocks are at most 8x8, and everything else the fp32 FMA kernel.
+// one-wave-per-query-tile kernel.  Every other bf16 problem with head_dim 64 (a pruned sequence, a
+// grid that the block side does not divide, other block sides) takes the MFMA kernel that walks
+// per-block token lists, and the rest (fp32, other head sizes) the fp32 FMA kernel.
 // NSATTN_KERNEL = sweep | block | persist | mfma | generic forces one of them where it applies.
 enum PatchKernel { PK_SWEEP, PK_BLOCK16, PK_PERSIST, PK_MFMA, PK_RAGGED, PK_GENERIC };
 
-static PatchKernel choose_patch_kernel(const ns_attn_desc &d, bool have_lists) {
+static PatchKernel choose_patch_kernel(const ns_attn_desc &d) {
   const char *e = getenv("NSATTN_KERNEL");
   const char force = e ? e[0] : 0;
+  if (force == 'g') return PK_GENERIC;        // serves every problem
   if (mfma_attn_supported(d)) {
     static int num_cus = 0;
     if (num_cus == 0) {
@@ -158,12 +167,12 @@ static PatchKernel choose_patch_kernel(const ns_attn_desc &d, bool have_lists) {
     if (persist_ok) return PK_PERSIST;
     return PK_MFMA;
   }
-  if (ragged_attn_supported(d) && have_lists && force != 'g') return PK_RAGGED;
+  if (ragged_attn_supported(d)) return PK_RAGGED;   // its lists: wants_lists()
   return PK_GENERIC;
 }
 
 static ns_status launch_patch_attention(const AttnArgs &a) {
-  switch (choose_patch_kernel(a.d, a.geom.lists != nullptr)) {
+  switch (choose_patch_kernel(a.d)) {
     case PK_SWEEP: return launch_attn_sweep(a, nullptr, nullptr);
     case PK_BLOCK16: return launch_attn_block16(a);
     case PK_PERSIST: return launch_attn_persist(a);
@@ -197,11 +206,11 @@ static ns_status prepare_attn(const ns_attn_desc *desc, const void *q, const voi
   g.nbw = (d.grid_w + d.block - 1) / d.block;
   g.n_global = d.n_global; g.tokens = d.tokens; g.cap = d.block * d.block;
   g.lists = nullptr; g.counts = nullptr;
-  if (d.coords) {
+  if (wants_lists(d)) {
     int32_t *lists = reinterpret_cast<int32_t *>(ws + w.lists_off);
     int32_t *counts = reinterpret_cast<int32_t *>(ws + w.counts_off);
     if (!reuse_lists) {
-      st = launch_block_lists(d, lists, counts, s);
+      st = d.coords ? launch_block_lists(d, lists, counts, s) : launch_grid_lists(d, lists, counts, s);
       if (st != NS_OK) return st;
     }
     g.lists = lists; g.counts = counts;
@@ -227,7 +236,7 @@ ns_status ns::attn_forward_impl(const ns_attn_desc *desc, const void *q, const v
   ns_status st = prepare_attn(desc, q, k, v, out, workspace, workspace_bytes, stream, a, partials, reuse_lists);
   if (st != NS_OK) return st;
   const ns_attn_desc &d = a.d;
-  if (choose_patch_kernel(d, a.geom.lists != nullptr) == PK_SWEEP) {
+  if (choose_patch_kernel(d) == PK_SWEEP) {
     // this kernel computes the global query's partials and logits on the way
     st = launch_attn_sweep(a, cls_logits, partials);
     if (st != NS_OK) return st;
@@ -256,7 +265,7 @@ ns_status ns_attn_patch_kernel_time(const ns_attn_desc *desc, const void *q, con
   if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
     return fail(NS_ERR_HIP, "hipEventCreate failed");
   hipError_t e = hipEventRecord(e0, a.stream);
-  const bool sweep = choose_patch_kernel(a.d, a.geom.lists != nullptr) == PK_SWEEP;
+  const bool sweep = choose_patch_kernel(a.d) == PK_SWEEP;
   for (int i = 0; i < reps && st == NS_OK; i++)
     st = sweep ? launch_attn_sweep(a, nullptr, partials) : launch_patch_attention(a);
   if (e == hipSuccess) e = hipEventRecord(e1, a.stream);
@@ -273,7 +282,7 @@ ns_status ns_attn_patch_kernel_time(const ns_attn_desc *desc, const void *q, con
 
 const char *ns_attn_patch_kernel_name(const ns_attn_desc *desc) {
   if (validate_desc(desc, true) != NS_OK) return "";
-  switch (choose_patch_kernel(*desc, desc->coords != nullptr)) {
+  switch (choose_patch_kernel(*desc)) {
     case PK_SWEEP: return "attn_sweep_kernel";
     case PK_BLOCK16: return "attn_block16_kernel";
     case PK_PERSIST: return "attn_mfma_persist_kernel";

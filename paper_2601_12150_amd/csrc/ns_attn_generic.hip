@@ -217,7 +217,30 @@ __global__ __launch_bounds__(256) void block_lists_kernel(const int32_t *coords,
   if (tid == 0) counts[(size_t)b * nblocks + blk] = min(running, cap);
 }
 
+// Complete grid: the same lists in closed form (raster order inside a block; the last block of a
+// row or column is short when the block side does not divide the grid).  grid (nblocks, B).
+__global__ __launch_bounds__(256) void grid_lists_kernel(int n_global, int grid_h, int grid_w, int block,
+                                                         int nbw, int nblocks, int cap, int32_t *lists,
+                                                         int32_t *counts) {
+  const int blk = blockIdx.x, b = blockIdx.y;
+  const int R = blk / nbw, C = blk % nbw;
+  const int bh = min(block, grid_h - R * block), bw = min(block, grid_w - C * block);
+  const int cnt = bh * bw;
+  int32_t *lb = lists + ((size_t)b * nblocks + blk) * cap;
+  for (int s = threadIdx.x; s < cnt; s += 256)
+    lb[s] = n_global + (R * block + s / bw) * grid_w + C * block + s % bw;
+  if (threadIdx.x == 0) counts[(size_t)b * nblocks + blk] = cnt;
+}
+
 }  // namespace
+
+ns_status launch_grid_lists(const ns_attn_desc &d, int32_t *lists, int32_t *counts, hipStream_t s) {
+  const int nbh = (d.grid_h + d.block - 1) / d.block, nbw = (d.grid_w + d.block - 1) / d.block;
+  dim3 grid(nbh * nbw, d.batch);
+  hipLaunchKernelGGL(grid_lists_kernel, grid, dim3(256), 0, s, d.n_global, d.grid_h, d.grid_w, d.block, nbw,
+                     nbh * nbw, d.block * d.block, lists, counts);
+  return check_launch("grid_lists_kernel");
+}
 
 ns_status launch_block_lists(const ns_attn_desc &d, int32_t *lists, int32_t *counts, hipStream_t s) {
   const int nbh = (d.grid_h + d.block - 1) / d.block, nbw = (d.grid_w + d.block - 1) / d.block;

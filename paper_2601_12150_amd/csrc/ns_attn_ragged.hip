@@ -1,11 +1,13 @@
-// bf16 MFMA neighbourhood attention for patch queries of a PRUNED sequence (gfx950), blocks of at
-// most 8x8 tokens.
+// bf16 MFMA neighbourhood attention for patch queries over per-block token lists (gfx950): pruned
+// sequences, grids that the block side does not divide, and block sides other than 8 and 16.
 //
 // After pruning (paper, "Time-Efficiency Optimization") the sequence is [CLS; surviving patches] and
 // the mask is still defined on the survivors' original grid positions (paper, "Memory-Efficiency
 // Optimization": adjacency "in the original pixel space").  block_lists_kernel has bucketed the
-// survivors by block; a block of side b <= 8 holds at most 64 of them, so every (query block, key
-// block) pair is one MFMA tile with the rows beyond the block's fill masked.
+// survivors by block (grid_lists_kernel does the same for a complete grid whose last blocks may be
+// short).  A block's list is cut into runs of 64 entries: a wave owns one run as its query tile
+// and walks the runs of the up to nine neighbouring blocks as key tiles, the rows beyond a run's
+// fill masked.
 //
 // Same register formulation as ns_attn_mfma.hip: S^T = K Q^T and O^T += V^T P^T with
 // v_mfma_f32_32x32x16_bf16, P kept in registers, K fragments gathered straight from global memory
@@ -25,6 +27,7 @@ struct RaggedParams {
   int64_t qsb, qsh, qst, osb, osh, ost;
   float c;               // scale * log2(e)
   int nbh, nbw, cap;     // blocks per side, slots per block in `lists`
+  int tpb;               // runs of 64 slots per block: ceil(cap / 64)
   int heads;
   const int32_t *lists;  // [B, nbh*nbw, cap] token indices
   const int32_t *counts; // [B, nbh*nbw]
@@ -45,17 +48,18 @@ __device__ __forceinline__ void rdma16(const char *base, uint32_t voff, uint32_t
                :: "s"(lds), "v"(voff), "s"(base) : "memory", "m0");
 }
 
-// grid (ceil(nblocks/4), H, B), 256 threads: one wave per query block.
+// grid (ceil(nblocks*tpb/4), H, B), 256 threads: one wave per query tile (tpb = runs per block).
 __global__ __launch_bounds__(256, 2) void attn_mfma_ragged_kernel(RaggedParams p) {
   const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int l32 = lane & 31, hh = lane >> 5;
   const int nblocks = p.nbh * p.nbw;
-  const int blk = blockIdx.x * 4 + wave, h = blockIdx.y, b = blockIdx.z;
+  const int qtile = blockIdx.x * 4 + wave, h = blockIdx.y, b = blockIdx.z;
+  const int blk = qtile / p.tpb, qbase = (qtile - blk * p.tpb) * 64;
   if (blk >= nblocks) return;                 // no workgroup barriers below
   const int32_t *cnts = p.counts + (size_t)b * nblocks;
   const int32_t *lst = p.lists + (size_t)b * nblocks * p.cap;
-  const int qcnt = __builtin_amdgcn_readfirstlane(cnts[blk]);
-  if (qcnt == 0) return;
+  const int qcnt = __builtin_amdgcn_readfirstlane(min(cnts[blk] - qbase, 64));   // fill of the query tile
+  if (qcnt <= 0) return;
   const int R = blk / p.nbw, C = blk % p.nbw;
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -67,12 +71,15 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_ragged_kernel(RaggedParams p
   const char *vb = reinterpret_cast<const char *>(p.v + b * p.qsb + h * p.qsh);
   const uint32_t rowB = (uint32_t)p.qst * 2u;
 
-  // token of slot `lane` of a block; slots beyond the fill repeat slot 0 (a valid row: its logits
-  // are masked, its weights are zero, its output is not stored)
-  auto slot_token = [&](int blk2, int cnt) { return lst[(size_t)blk2 * p.cap + (lane < cnt ? lane : 0)]; };
+  // token of slot `lane` of the run that starts at `base` in a block's list; slots beyond the
+  // run's fill repeat its first slot (a valid row: its logits are masked, its weights are zero,
+  // its output is not stored)
+  auto slot_token = [&](int blk2, int base, int cnt) {
+    return lst[(size_t)blk2 * p.cap + base + (lane < cnt ? lane : 0)];
+  };
 
   // ---- Q as B operand: lane (query l32 + 32*nt, half hh) holds channels 32*hh + 8*s + j
-  const int qtok = slot_token(blk, qcnt);
+  const int qtok = slot_token(blk, qbase, qcnt);
   bf16x8 qf[2][4];
   int qrow[2];
 #pragma unroll
@@ -137,11 +144,21 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_ragged_kernel(RaggedParams p
   }
   nbmask = __builtin_amdgcn_readfirstlane(nbmask);   // the query block itself is non-empty: mask != 0
 
-  // requests of one key tile: K fragments into registers, V into an LDS buffer
-  auto request = [&](int nb, bf16x8 (&kf)[2][4], int buf, int &cnt) {
-    const int blk2 = (R + nb / 3 - 1) * p.nbw + (C + nb % 3 - 1);
-    cnt = __builtin_amdgcn_readfirstlane(cnts[blk2]);
-    const int tok = slot_token(blk2, cnt);
+  // The key tiles in order: neighbour blocks by position, the runs of a block in list order.
+  int kblk = 0, kfill = 0, kbase = 0;         // current block, its fill, start of the current run
+  auto have_next = [&]() { return kbase + 64 < kfill || nbmask != 0; };
+  auto advance = [&]() {                       // only when have_next()
+    if (kbase + 64 < kfill) { kbase += 64; return; }
+    const int nb = __builtin_ctz(nbmask);
+    nbmask &= nbmask - 1;
+    kblk = (R + nb / 3 - 1) * p.nbw + (C + nb % 3 - 1);
+    kfill = __builtin_amdgcn_readfirstlane(cnts[kblk]);
+    kbase = 0;
+  };
+  // requests of the current key tile: K fragments into registers, V into an LDS buffer
+  auto request = [&](bf16x8 (&kf)[2][4], int buf, int &cnt) {
+    cnt = min(kfill - kbase, 64);
+    const int tok = slot_token(kblk, kbase, cnt);
 #pragma unroll
     for (int it = 0; it < 8; it++) {
       const uint32_t vt = (uint32_t)__shfl(tok, it * 8 + (lane >> 3));
@@ -223,13 +240,12 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_ragged_kernel(RaggedParams p
 
   bf16x8 kfa[2][4], kfb[2][4];
   int cnta = 0, cntb = 0;
-  int nb = __builtin_ctz(nbmask);
-  nbmask &= nbmask - 1;
-  request(nb, kfa, 0, cnta);
+  advance();
+  request(kfa, 0, cnta);
   while (true) {
     // tile in (kfa, buffer 0); request the next one into (kfb, buffer 1) first
-    const bool more1 = nbmask != 0;
-    if (more1) { nb = __builtin_ctz(nbmask); nbmask &= nbmask - 1; request(nb, kfb, 1, cntb); }
+    const bool more1 = have_next();
+    if (more1) { advance(); request(kfb, 1, cntb); }
     // this tile's V transfers are older than everything requested just now: at most the 16 new
     // requests may still be in flight
     if (more1) asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -237,8 +253,8 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_ragged_kernel(RaggedParams p
     // the tile's LDS reads have returned before the next transfer into its buffer is requested
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     if (!more1) break;
-    const bool more2 = nbmask != 0;
-    if (more2) { nb = __builtin_ctz(nbmask); nbmask &= nbmask - 1; request(nb, kfa, 0, cnta); }
+    const bool more2 = have_next();
+    if (more2) { advance(); request(kfa, 0, cnta); }
     if (more2) asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     process(kfb, 1, cntb);
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -267,7 +283,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_ragged_kernel(RaggedParams p
 
 bool ragged_attn_supported(const ns_attn_desc &d) {
   return d.dtype == NS_BF16 && d.head_dim == 64 && d.radius == 1 && d.n_global == 1 &&
-         d.coords != nullptr && d.block <= 8 && d.scale > 0.f && d.heads <= 65535 && d.batch <= 65535 &&
+         d.scale > 0.f && d.heads <= 65535 && d.batch <= 65535 &&
          (long long)d.tokens * d.q_stride_t * 2 < 0x7fffffffLL &&
          (long long)d.tokens * d.out_stride_t * 2 < 0x7fffffffLL;
 }
@@ -283,9 +299,11 @@ ns_status launch_attn_ragged(const AttnArgs &a) {
   p.osb = d.out_stride_b; p.osh = d.out_stride_h; p.ost = d.out_stride_t;
   p.c = d.scale * kLog2e;
   p.nbh = a.geom.nbh; p.nbw = a.geom.nbw; p.cap = a.geom.cap;
+  p.tpb = (p.cap + 63) / 64;
   p.heads = d.heads;
   p.lists = a.geom.lists; p.counts = a.geom.counts;
-  const long long gx = ((long long)p.nbh * p.nbw + 3) / 4;
+  if (!p.lists || !p.counts) return fail(NS_ERR_INVALID_ARG, "the list kernel was launched without block lists");
+  const long long gx = ((long long)p.nbh * p.nbw * p.tpb + 3) / 4;
   if (gx > 0x7fffffffLL) return fail(NS_ERR_UNSUPPORTED, "launch grid too large");
   hipLaunchKernelGGL(attn_mfma_ragged_kernel, dim3((unsigned)gx, d.heads, d.batch), dim3(256), 4 * 16384,
                      a.stream, p);

@@ -98,6 +98,7 @@ ns_status attn_forward_impl(const ns_attn_desc *desc, const void *q, const void 
                             void *stream, bool reuse_lists);
 
 ns_status launch_block_lists(const ns_attn_desc &d, int32_t *lists, int32_t *counts, hipStream_t s);
+ns_status launch_grid_lists(const ns_attn_desc &d, int32_t *lists, int32_t *counts, hipStream_t s);
 ns_status launch_attn_generic(const AttnArgs &a);
 bool mfma_attn_supported(const ns_attn_desc &d);
 ns_status launch_attn_mfma(const AttnArgs &a);
@@ -110,7 +111,7 @@ ns_status launch_attn_sweep(const AttnArgs &a, float *cls_logits, float *cls_par
 inline int sweep_cls_chunks(const ns_attn_desc &d) { return 4 * (d.grid_h / 8); }
 bool block16_attn_supported(const ns_attn_desc &d);  // 16x16 blocks: key tiles shared by a block's four query tiles
 ns_status launch_attn_block16(const AttnArgs &a);
-bool ragged_attn_supported(const ns_attn_desc &d);   // pruned sequence, blocks of at most 8x8
+bool ragged_attn_supported(const ns_attn_desc &d);   // bf16, head_dim 64: anything given per-block token lists
 ns_status launch_attn_ragged(const AttnArgs &a);
 
 // global-query (CLS) row: per-chunk partials, then a combine.

@@ -421,7 +421,7 @@ ns_status vit_forward(const ns_vit_desc *desc, const ns_vit_block_weights *weigh
   const int N = full.tokens - full.n_global;
   const void *cur = x_in;
   int flip = 0;
-  bool lists_built = false;   // the pruned sequence's block lists stay valid from block to block
+  bool lists_built = false;   // block lists stay valid from block to block until the sequence changes
   for (int l = 0; l < desc->layers; l++) {
     const bool last = l + 1 == desc->layers, scoring = prune && l + 1 == desc->prune_after;
     // the last block writes x_out directly unless the pruning stage still follows it
@@ -429,7 +429,7 @@ ns_status vit_forward(const ns_vit_desc *desc, const ns_vit_block_weights *weigh
     st = block_forward_impl(&bd, &weights[l], cur, dst, scoring ? scores : nullptr, ws + L.block_ws, bw, s,
                             lists_built);
     if (st != NS_OK) return st;
-    lists_built = bd.attn.coords != nullptr;
+    lists_built = true;
     cur = dst;
     flip ^= 1;
     if (scoring) {
@@ -444,6 +444,7 @@ ns_status vit_forward(const ns_vit_desc *desc, const ns_vit_block_weights *weigh
       flip ^= 1;
       bd.attn.tokens = full.n_global + desc->keep_k;
       bd.attn.coords = cout;
+      lists_built = false;
     }
   }
   return NS_OK;

@@ -128,13 +128,19 @@ def test_kernel_choice_policy(nb, monkeypatch):
     assert name(desc(1, 2, 32, 16)) == "attn_mfma_persist_kernel"       # 16x16 blocks, too few for a workgroup each
     assert name(desc(1, 2, 8, 8)) == "attn_mfma_kernel"                 # a single block
     assert name(desc(1, 2, 24, 8, dtype=nb.NS_F32)) == "attn_generic_kernel"
-    assert name(desc(1, 2, 24, 4)) == "attn_generic_kernel"             # 4x4 blocks on the full grid
+    assert name(desc(1, 2, 24, 4)) == "attn_mfma_ragged_kernel"         # 4x4 blocks on the full grid
+    assert name(desc(1, 16, 100, 8)) == "attn_mfma_ragged_kernel"       # the block side does not divide the grid
+    assert name(desc(1, 16, 245, 16)) == "attn_mfma_ragged_kernel"
+    assert name(desc(1, 2, 100, 8, dtype=nb.NS_F32)) == "attn_generic_kernel"
     assert name(desc(1, 2, 24, 8, coords=True)) == "attn_mfma_ragged_kernel"
-    assert name(desc(1, 2, 32, 16, coords=True)) == "attn_generic_kernel"
+    assert name(desc(1, 2, 32, 16, coords=True)) == "attn_mfma_ragged_kernel"
     monkeypatch.setenv("NSATTN_KERNEL", "mfma")
     assert name(desc(2, 16, 128, 8)) == "attn_mfma_kernel"
     monkeypatch.setenv("NSATTN_KERNEL", "persist")
     assert name(desc(2, 16, 128, 8)) == "attn_mfma_persist_kernel"
+    monkeypatch.setenv("NSATTN_KERNEL", "generic")
+    assert name(desc(1, 16, 100, 8)) == "attn_generic_kernel"
+    assert name(desc(2, 16, 128, 8)) == "attn_generic_kernel"
     monkeypatch.setenv("NSATTN_KERNEL", "block")
     assert name(desc(1, 2, 32, 16)) == "attn_block16_kernel"
     assert name(desc(2, 16, 128, 8)) != "attn_block16_kernel"           # a forced kernel that cannot serve falls back

@@ -44,8 +44,26 @@ def run_case(nb, seed, B, H, gh, gw, block, dtype, scale=0.125, strided=False):
 @pytest.mark.parametrize("gh,gw,block,dtype", [
     (14, 14, 7, "f32"), (10, 9, 4, "f32"), (5, 5, 8, "f32"), (12, 20, 4, "bf16"), (9, 9, 3, "bf16"),
     (17, 13, 5, "bf16"), (24, 24, 12, "f32"), (16, 16, 8, "f32"), (3, 70, 2, "bf16")])
-def test_generic_kernel(nb, gh, gw, block, dtype):
+def test_generic_kernel(nb, monkeypatch, gh, gw, block, dtype):
+    monkeypatch.setenv("NSATTN_KERNEL", "generic")     # bf16 would otherwise go to the list kernel
     run_case(nb, 101, 2, 3, gh, gw, block, dtype)
+
+
+# MFMA kernel over per-block token lists on complete grids: block sides that do not divide the grid
+# (short last blocks), block sides other than 8 and 16 (several runs of 64 per block for the large
+# ones, nearly empty tiles for the small ones), a block that covers the whole grid
+@pytest.mark.parametrize("gh,gw,block", [
+    (20, 27, 8), (37, 21, 16), (12, 20, 4), (9, 9, 3), (17, 13, 5), (3, 70, 2), (30, 30, 2), (25, 25, 7),
+    (40, 40, 64), (70, 72, 64), (33, 50, 32), (26, 26, 12), (5, 5, 8), (1, 1, 8), (1, 130, 16)])
+def test_list_kernel_on_complete_grids(nb, gh, gw, block):
+    q, k, v = synth.small_case(303, 2, 2, 64, gh, gw, "bf16")
+    dq, dk, dv = (to_dev(a, "bf16") for a in (q, k, v))
+    assert nb.ns_attn_patch_kernel_name(dq, gh, gw, block) == "attn_mfma_ragged_kernel"
+    run_case(nb, 303, 2, 2, gh, gw, block, "bf16")
+
+
+def test_list_kernel_strided_views(nb):
+    run_case(nb, 304, 2, 4, 27, 22, 8, "bf16", scale=0.3, strided=True)
 
 
 # MFMA kernel: 8x8 blocks (one tile each) and 16x16 blocks (four tiles each)
@@ -96,11 +114,13 @@ def test_pruned_sequence(nb, dtype, block):
 
 
 @pytest.mark.parametrize("g,block,shuffle,gain", [(30, 8, False, 1.0), (30, 5, True, 1.0), (20, 3, False, 1.0),
-                                                  (32, 8, True, 12.0)])
+                                                  (32, 8, True, 12.0), (48, 16, True, 1.0), (40, 12, False, 1.0),
+                                                  (50, 32, True, 6.0)])
 def test_pruned_sequence_mfma_kernel(nb, monkeypatch, g, block, shuffle, gain):
-    """bf16, head_dim 64, blocks of at most 8x8: the MFMA kernel for pruned sequences.  Covers grids
-    the block does not divide, survivors in arbitrary sequence order, logits large enough to need
-    the running maximum, and agreement with the fp32 FMA kernel on the same inputs."""
+    """bf16, head_dim 64: the MFMA kernel for pruned sequences.  Covers grids the block does not
+    divide, blocks of more than 64 tokens (several runs per block, the last one partly filled),
+    survivors in arbitrary sequence order, logits large enough to need the running maximum, and
+    agreement with the fp32 FMA kernel on the same inputs."""
     rng = np.random.default_rng(g * 100 + block)
     N = g * g
     keep = rng.random(N) < 0.6
