@@ -25,11 +25,12 @@ PEAK_HBM = 8.0e12           # MI355X published HBM3E bandwidth, B/s
 
 
 def sparse_pairs(grid: int, block: int):
-    """Allowed (query, key) pairs per head-image: patch rows (a2) and the CLS row (a3)."""
-    nb = grid // block
+    """Allowed (query, key) pairs per head-image: patch rows (a2) and the CLS row (a3).
+    Blocks per side ceil(grid / block), the last one short when the side does not divide."""
+    sides = [min(block, grid - i) for i in range(0, grid, block)]
+    axis = sum(s * sum(sides[max(i - 1, 0):i + 2]) for i, s in enumerate(sides))
     n = grid * grid
-    span = 3 * nb - 2 if nb > 1 else 1
-    patch_rows = span * span * block ** 4 + n      # neighbourhood pairs + patch->CLS
+    patch_rows = axis * axis + n                   # neighbourhood pairs + patch->CLS
     cls_row = n + 1
     return patch_rows, cls_row
 
@@ -39,7 +40,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=3, help="workload: 2, 3 (headline) or 4")
+    ap.add_argument("--config", type=int, default=3,
+                    help="workload: 2, 3 (headline), 4, or 11-15 (grids of 100 and 245 patches, windows 2-64)")
     ap.add_argument("--sets", type=int, default=3,
                     help="input sets rotated between steps so that no step finds its inputs in the 256 MB "
                          "Infinity Cache (1 = warm-cache run)")

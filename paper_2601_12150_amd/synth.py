@@ -55,6 +55,14 @@ CONFIGS = {
     2: Config("cfg2_g64_b8_bf16", 4, 16, 64, 64, 8, "bf16", 60, "grf", seed=2),
     3: Config("cfg3_g128_b8_bf16", 2, 16, 64, 128, 8, "bf16", 60, "background", 0.40, seed=3),
     4: Config("cfg4_g256_b16_bf16", 1, 16, 64, 256, 16, "bf16", 40, "background", 0.55, seed=4),
+    # Grids the block side does not divide and other window sizes: the paper's 14-pixel patch grids
+    # of its 1400- and 3430-pixel inputs (100 and 245 patches per side; "Classification", Table 1),
+    # its window-size ablation w in {2, 8, 16, 64} (Tables "window size") on the larger one.
+    11: Config("g100_b8_bf16", 2, 16, 64, 100, 8, "bf16", 60, "background", 0.40, seed=11),
+    12: Config("g245_b8_bf16", 1, 16, 64, 245, 8, "bf16", 60, "background", 0.40, seed=12),
+    13: Config("g245_b16_bf16", 1, 16, 64, 245, 16, "bf16", 60, "background", 0.40, seed=12),
+    14: Config("g245_b64_bf16", 1, 16, 64, 245, 64, "bf16", 60, "background", 0.40, seed=12),
+    15: Config("g245_b2_bf16", 1, 16, 64, 245, 2, "bf16", 60, "background", 0.40, seed=12),
 }
 
 

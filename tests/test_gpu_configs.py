@@ -27,7 +27,8 @@ def sample_rows(cfg, n, seed):
     return np.unique(np.concatenate([fixed, rest])).astype(np.int32)
 
 
-@pytest.mark.parametrize("cfg_id,n_rows", [(1, 785), (2, 160), (3, 96), (4, 40)])
+@pytest.mark.parametrize("cfg_id,n_rows", [(1, 785), (2, 160), (3, 96), (4, 40),
+                                           (11, 96), (12, 48), (13, 40), (14, 24), (15, 64)])
 def test_config_pipeline(nb, cfg_id, n_rows):
     cfg = synth.CONFIGS[cfg_id]
     print("config", cfg.name, flush=True)
