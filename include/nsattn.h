@@ -69,7 +69,7 @@ typedef struct ns_attn_desc {
   int32_t grid_w;    /* patch grid columns                                               */
   int32_t block;     /* b >= 1: side of a token block                                    */
   int32_t radius;    /* neighbourhood radius in blocks; this build implements 1 (3x3)    */
-  int32_t n_global;  /* G >= 1 leading global tokens; this build implements 1 (CLS)      */
+  int32_t n_global;  /* G >= 1 leading global tokens (CLS, registers); G <= 256, H*G <= 1024 */
   int32_t dtype;     /* ns_dtype of q, k, v, out; accumulation is always fp32            */
   int32_t tokens;    /* T: tokens present per image                                      */
   float scale;       /* logit multiplier, normally 1/sqrt(D)                             */
@@ -85,10 +85,13 @@ size_t ns_attn_workspace_bytes(const ns_attn_desc *desc);
  * Masked softmax attention for all T query tokens.
  *   q, k, v   in   [B,H,T,D] by the descriptor's q strides, dtype desc->dtype
  *   out       out  [B,H,T,D] by the descriptor's out strides, same dtype
- *   cls_logits out, nullable  [B,H,T] fp32: scale * <q_0, k_j> (global query 0)
- *   cls_lse    out, nullable  [B,H]   fp32: log(sum_j exp(cls_logits[j])) (natural log)
- * cls_logits and cls_lse are by-products of the global query's row; passing them lets
+ *   cls_logits out, nullable  [B,H,G,T] fp32: scale * <q_g, k_j> for global query g
+ *   cls_lse    out, nullable  [B,H,G]   fp32: log(sum_j exp(cls_logits[g][j])) (natural log)
+ * cls_logits and cls_lse are by-products of the global queries' rows; passing them lets
  * cls_scores_from_logits produce the importance scores without reading K again.
+ * Several global tokens (paper, "Memory-Efficiency Optimization": a few designated global
+ * tokens attend to, and are attended by, every token): each of the G global queries sees
+ * all T keys, and every patch query sees the G global keys besides its neighbourhood.
  */
 ns_status ns_attn_forward(const ns_attn_desc *desc, const void *q, const void *k, const void *v,
                           void *out, float *cls_logits, float *cls_lse, void *workspace,
@@ -96,18 +99,19 @@ ns_status ns_attn_forward(const ns_attn_desc *desc, const void *q, const void *k
 
 /*
  * Importance scores (paper, "Time-Efficiency Optimization": a score per token derived from
- * the global attention weights).  scores[b, j] = mean over heads of the softmax weight
- * that global query 0 puts on patch key G + j, the softmax running over all T keys.
+ * the global attention weights).  scores[b, j] = mean over heads and over the G global
+ * queries of the softmax weight that the global query puts on patch key G + j, the softmax
+ * running over all T keys.
  * Only batch, heads, head_dim, n_global, tokens, dtype, scale and the q strides of the
  * descriptor are used.
- *   q, k    in   as in ns_attn_forward (only token 0 of q is read)
+ *   q, k    in   as in ns_attn_forward (only tokens 0..G-1 of q are read)
  *   scores  out  [B, T-G] fp32
  */
 size_t cls_scores_workspace_bytes(const ns_attn_desc *desc);
 ns_status cls_scores(const ns_attn_desc *desc, const void *q, const void *k, float *scores,
                      void *workspace, size_t workspace_bytes, void *stream);
 
-/* The same scores from ns_attn_forward's by-products: logits [B,H,T], lse [B,H]. */
+/* The same scores from ns_attn_forward's by-products: logits [B,H,G,T], lse [B,H,G]. */
 ns_status cls_scores_from_logits(int32_t batch, int32_t heads, int32_t tokens, int32_t n_global,
                                  const float *cls_logits, const float *cls_lse, float *scores,
                                  void *stream);
@@ -130,6 +134,12 @@ ns_status topk_filter(int32_t batch, int32_t n, int32_t k, const float *scores, 
                       int32_t channels, int32_t x_dtype, const int32_t *coords_in,
                       int32_t *kept_idx, void *y, int32_t *coords_out, void *workspace,
                       size_t workspace_bytes, void *stream);
+/* The same with n_global leading global rows instead of one: x [B, G+N, C], y [B, G+k, C],
+ * rows 0..G-1 copied, row G+t = x row G+kept_idx[t]. */
+ns_status topk_filter_global(int32_t batch, int32_t n, int32_t k, int32_t n_global, const float *scores,
+                             const void *x, int32_t channels, int32_t x_dtype, const int32_t *coords_in,
+                             int32_t *kept_idx, void *y, int32_t *coords_out, void *workspace,
+                             size_t workspace_bytes, void *stream);
 
 /*
  * One pre-LayerNorm transformer block around the sparse attention:

@@ -29,7 +29,8 @@ def gelu(x):
     return 0.5 * x * (1.0 + _erf(x / math.sqrt(2.0)))
 
 
-def vit_block(x, w, grid_h, grid_w, block, heads, ln_eps=1e-6, scale=None, coords=None, want_scores=False):
+def vit_block(x, w, grid_h, grid_w, block, heads, ln_eps=1e-6, scale=None, coords=None, want_scores=False,
+              n_global=1):
     """x [B,T,dim]; w: dict of numpy arrays named as in the C ABI's ns_vit_block_weights."""
     x = np.asarray(x, dtype=np.float64)
     B, T, dim = x.shape
@@ -39,11 +40,11 @@ def vit_block(x, w, grid_h, grid_w, block, heads, ln_eps=1e-6, scale=None, coord
     a = layer_norm(x, f["ln1_g"], f["ln1_b"], ln_eps)
     qkv = a @ f["w_qkv"].T + f["b_qkv"]                       # [B,T,3*dim], rows q | k | v
     q, k, v = (qkv[..., i * dim:(i + 1) * dim].reshape(B, T, heads, D).transpose(0, 2, 1, 3) for i in range(3))
-    att = ns_attn(q, k, v, grid_h, grid_w, block, scale, coords=coords)       # [B,H,T,D]
+    att = ns_attn(q, k, v, grid_h, grid_w, block, scale, coords=coords, n_global=n_global)   # [B,H,T,D]
     att = att.transpose(0, 2, 1, 3).reshape(B, T, dim)
     h = x + att @ f["w_proj"].T + f["b_proj"]
     m = gelu(layer_norm(h, f["ln2_g"], f["ln2_b"], ln_eps) @ f["w_fc1"].T + f["b_fc1"])
     y = h + m @ f["w_fc2"].T + f["b_fc2"]
     if want_scores:
-        return y, cls_scores(q, k, scale)
+        return y, cls_scores(q, k, scale, n_global=n_global)
     return y

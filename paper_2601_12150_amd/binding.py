@@ -20,7 +20,7 @@ NS_OK, NS_ERR_INVALID_ARG, NS_ERR_UNSUPPORTED, NS_ERR_WORKSPACE, NS_ERR_HIP = ra
 NS_F32, NS_BF16 = 0, 1
 
 EXPORTS = ["ns_attn_workspace_bytes", "ns_attn_forward", "cls_scores_workspace_bytes", "cls_scores",
-           "cls_scores_from_logits", "topk_filter_workspace_bytes", "topk_filter",
+           "cls_scores_from_logits", "topk_filter_workspace_bytes", "topk_filter", "topk_filter_global",
            "vit_block_workspace_bytes", "vit_block_forward", "linear_forward", "vit_workspace_bytes", "vit_forward",
            "ns_attn_patch_kernel_time", "ns_attn_patch_kernel_name", "ns_last_error",
            "ns_version"]
@@ -86,6 +86,8 @@ def _load() -> ctypes.CDLL:
     lib.topk_filter_workspace_bytes.argtypes = [i32, i32, i32]
     lib.topk_filter.restype = ctypes.c_int
     lib.topk_filter.argtypes = [i32, i32, i32, vp, vp, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.topk_filter_global.restype = ctypes.c_int
+    lib.topk_filter_global.argtypes = [i32, i32, i32, i32, vp, vp, i32, i32, vp, vp, vp, vp, vp, sz, vp]
     lib.vit_block_workspace_bytes.restype = sz
     lib.vit_block_workspace_bytes.argtypes = [ctypes.POINTER(ns_vit_block_desc)]
     lib.vit_block_forward.restype = ctypes.c_int
@@ -161,7 +163,8 @@ def ns_attn_forward(q, k, v, grid_h, grid_w, block, scale=None, coords=None, out
     """Neighbourhood-sparse attention.  q, k, v: [B,H,T,D] device tensors with equal strides.
 
     Returns out [B,H,T,D] (allocated contiguous unless given) and, with want_cls, also the
-    global query's logits [B,H,T] and log-sum-exp [B,H] (both fp32)."""
+    global query's logits [B,H,T] and log-sum-exp [B,H] (both fp32; [B,H,G,T] and [B,H,G] when
+    n_global = G > 1)."""
     if not (q.shape == k.shape == v.shape and q.stride() == k.stride() == v.stride()):
         raise ValueError("q, k, v must have the same shape and strides")
     if not (q.dtype == k.dtype == v.dtype):
@@ -174,8 +177,9 @@ def ns_attn_forward(q, k, v, grid_h, grid_w, block, scale=None, coords=None, out
     desc = make_desc(q, grid_h, grid_w, block, scale, out, coords, radius, n_global)
     logits = lse = None
     if want_cls:
-        logits = torch.empty((B, H, T), dtype=torch.float32, device=q.device)
-        lse = torch.empty((B, H), dtype=torch.float32, device=q.device)
+        G = int(n_global)
+        logits = torch.empty((B, H, T) if G == 1 else (B, H, G, T), dtype=torch.float32, device=q.device)
+        lse = torch.empty((B, H) if G == 1 else (B, H, G), dtype=torch.float32, device=q.device)
     nbytes = lib.ns_attn_workspace_bytes(ctypes.byref(desc))
     ws = _workspace(nbytes, q.device, workspace)
     _check(lib.ns_attn_forward(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(logits),
@@ -200,10 +204,10 @@ def ns_attn_patch_kernel_time(q, k, v, grid_h, grid_w, block, scale=None, coords
     return float(ms.value)
 
 
-def ns_attn_patch_kernel_name(q, grid_h, grid_w, block, scale=None, coords=None) -> str:
+def ns_attn_patch_kernel_name(q, grid_h, grid_w, block, scale=None, coords=None, n_global=1) -> str:
     """Name of the kernel ns_attn_forward launches for the patch queries of this problem."""
     B, H, T, D = q.shape
-    desc = make_desc(q, grid_h, grid_w, block, scale, None, coords)
+    desc = make_desc(q, grid_h, grid_w, block, scale, None, coords, 1, n_global)
     desc.out_stride_b, desc.out_stride_h, desc.out_stride_t = desc.q_stride_b, desc.q_stride_h, desc.q_stride_t
     return lib.ns_attn_patch_kernel_name(ctypes.byref(desc)).decode()
 
@@ -226,7 +230,9 @@ def cls_scores(q, k, scale=None, n_global=1, scores=None, workspace=None, stream
 
 def cls_scores_from_logits(cls_logits, cls_lse, n_global=1, scores=None, stream=None):
     """The same scores from ns_attn_forward's by-products (no second pass over K)."""
-    B, H, T = cls_logits.shape
+    B, H, T = cls_logits.shape[0], cls_logits.shape[1], cls_logits.shape[-1]
+    if cls_logits.dim() == 4 and cls_logits.shape[2] != n_global:
+        raise ValueError("cls_logits must be [B,H,G,T] with G = n_global")
     if not (cls_logits.is_contiguous() and cls_lse.is_contiguous()):
         raise ValueError("cls_logits and cls_lse must be contiguous")
     if scores is None:
@@ -237,11 +243,13 @@ def cls_scores_from_logits(cls_logits, cls_lse, n_global=1, scores=None, stream=
 
 
 def topk_filter(scores, k, x=None, coords=None, kept_idx=None, y=None, coords_out=None,
-                workspace=None, stream=None):
+                workspace=None, stream=None, n_global=1):
     """Keep the k best-scoring patches per image.
 
-    scores [B,N] fp32; x optional [B,1+N,C]; coords optional [B,N] int32.
-    Returns (kept_idx [B,k] int32 ascending, y [B,1+k,C] or None, coords_out [B,k] or None)."""
+    scores [B,N] fp32; x optional [B,G+N,C] (G = n_global leading rows are kept); coords optional
+    [B,N] int32.
+    Returns (kept_idx [B,k] int32 ascending, y [B,G+k,C] or None, coords_out [B,k] or None)."""
+    G = int(n_global)
     if scores.dtype != torch.float32 or not scores.is_contiguous():
         raise ValueError("scores must be a contiguous float32 tensor")
     B, N = scores.shape
@@ -251,11 +259,11 @@ def topk_filter(scores, k, x=None, coords=None, kept_idx=None, y=None, coords_ou
         kept_idx = torch.empty((B, kk), dtype=torch.int32, device=dev)
     C, xdt = 0, NS_BF16
     if x is not None:
-        if not x.is_contiguous() or x.shape[0] != B or x.shape[1] != 1 + N:
-            raise ValueError("x must be contiguous [B, 1+N, C]")
+        if not x.is_contiguous() or x.shape[0] != B or x.shape[1] != G + N:
+            raise ValueError("x must be contiguous [B, n_global+N, C]")
         C, xdt = x.shape[2], _dtype_code(x)
         if y is None:
-            y = torch.empty((B, 1 + kk, C), dtype=x.dtype, device=dev)
+            y = torch.empty((B, G + kk, C), dtype=x.dtype, device=dev)
     if coords is not None:
         if coords.dtype != torch.int32 or not coords.is_contiguous():
             raise ValueError("coords must be contiguous int32 [B,N]")
@@ -263,9 +271,14 @@ def topk_filter(scores, k, x=None, coords=None, kept_idx=None, y=None, coords_ou
             coords_out = torch.empty((B, kk), dtype=torch.int32, device=dev)
     nbytes = lib.topk_filter_workspace_bytes(B, N, int(k))
     ws = _workspace(nbytes, dev, workspace)
-    _check(lib.topk_filter(B, N, int(k), _ptr(scores), _ptr(x), C, xdt, _ptr(coords), _ptr(kept_idx),
-                           _ptr(y), _ptr(coords_out), _ptr(ws), 0 if ws is None else ws.numel(),
-                           _stream(stream)))
+    if G == 1:
+        _check(lib.topk_filter(B, N, int(k), _ptr(scores), _ptr(x), C, xdt, _ptr(coords), _ptr(kept_idx),
+                               _ptr(y), _ptr(coords_out), _ptr(ws), 0 if ws is None else ws.numel(),
+                               _stream(stream)))
+    else:
+        _check(lib.topk_filter_global(B, N, int(k), G, _ptr(scores), _ptr(x), C, xdt, _ptr(coords),
+                                      _ptr(kept_idx), _ptr(y), _ptr(coords_out), _ptr(ws),
+                                      0 if ws is None else ws.numel(), _stream(stream)))
     return kept_idx, y, coords_out
 
 
@@ -274,11 +287,11 @@ WEIGHT_NAMES = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_proj", "b_proj", "ln2_g",
 
 
 def vit_block_forward(x, weights, grid_h, grid_w, block, heads, ln_eps=1e-6, scale=None, coords=None,
-                      want_scores=False, out=None, workspace=None, stream=None):
+                      want_scores=False, out=None, workspace=None, stream=None, n_global=1):
     """One pre-LayerNorm transformer block around the sparse attention.
 
     x [B,T,dim] bf16 contiguous; weights: dict of device tensors (matrices bf16 [out,in], vectors
-    fp32).  Returns x_out [B,T,dim] (and the importance scores [B,T-1] with want_scores)."""
+    fp32).  Returns x_out [B,T,dim] (and the importance scores [B,T-n_global] with want_scores)."""
     if x.dtype != torch.bfloat16 or not x.is_contiguous():
         raise ValueError("x must be a contiguous bfloat16 tensor [B,T,dim]")
     B, T, dim = x.shape
@@ -291,7 +304,7 @@ def vit_block_forward(x, weights, grid_h, grid_w, block, heads, ln_eps=1e-6, sca
     d = ns_vit_block_desc()
     a = d.attn
     a.batch, a.heads, a.head_dim = B, heads, dim // heads
-    a.grid_h, a.grid_w, a.block, a.radius, a.n_global = grid_h, grid_w, block, 1, 1
+    a.grid_h, a.grid_w, a.block, a.radius, a.n_global = grid_h, grid_w, block, 1, int(n_global)
     a.dtype, a.tokens = NS_BF16, T
     a.scale = float(dim // heads) ** -0.5 if scale is None else float(scale)
     if coords is not None:
@@ -304,7 +317,7 @@ def vit_block_forward(x, weights, grid_h, grid_w, block, heads, ln_eps=1e-6, sca
         setattr(w, n, weights[n].data_ptr())
     if out is None:
         out = torch.empty_like(x)
-    scores = torch.empty((B, T - 1), dtype=torch.float32, device=x.device) if want_scores else None
+    scores = torch.empty((B, T - int(n_global)), dtype=torch.float32, device=x.device) if want_scores else None
     nbytes = lib.vit_block_workspace_bytes(ctypes.byref(d))
     ws = _workspace(max(nbytes, 1), x.device, workspace)
     _check(lib.vit_block_forward(ctypes.byref(d), ctypes.byref(w), _ptr(x), _ptr(out), _ptr(scores), _ptr(ws),
@@ -332,18 +345,18 @@ def linear_forward(x, w, bias, residual=None, gelu=False, out=None, stream=None)
 
 
 def vit_forward(x, layer_weights, grid_h, grid_w, block, heads, prune_after=0, keep_k=0, ln_eps=1e-6,
-                scale=None, out=None, workspace=None, stream=None):
+                scale=None, out=None, workspace=None, stream=None, n_global=1):
     """A stack of blocks with one pruning stage after block `prune_after` (keep_k patches kept).
 
     x [B,T,dim] bf16; layer_weights: list of weight dicts (see vit_block_forward).
-    Returns (x_out [B, 1+keep_k or T, dim], kept_idx [B,keep_k] or None)."""
+    Returns (x_out [B, n_global+keep_k or T, dim], kept_idx [B,keep_k] or None)."""
     if x.dtype != torch.bfloat16 or not x.is_contiguous():
         raise ValueError("x must be a contiguous bfloat16 tensor [B,T,dim]")
     B, T, dim = x.shape
     d = ns_vit_desc()
     a = d.block.attn
     a.batch, a.heads, a.head_dim = B, heads, dim // heads
-    a.grid_h, a.grid_w, a.block, a.radius, a.n_global = grid_h, grid_w, block, 1, 1
+    a.grid_h, a.grid_w, a.block, a.radius, a.n_global = grid_h, grid_w, block, 1, int(n_global)
     a.dtype, a.tokens = NS_BF16, T
     a.scale = float(dim // heads) ** -0.5 if scale is None else float(scale)
     d.block.dim, d.block.mlp_dim, d.block.ln_eps = dim, layer_weights[0]["w_fc1"].shape[0], float(ln_eps)
@@ -358,7 +371,7 @@ def vit_forward(x, layer_weights, grid_h, grid_w, block, heads, prune_after=0, k
             setattr(warr[i], n, t.data_ptr())
     pruning = prune_after > 0 and keep_k > 0
     if out is None:
-        out = torch.empty((B, 1 + keep_k if pruning else T, dim), dtype=x.dtype, device=x.device)
+        out = torch.empty((B, int(n_global) + keep_k if pruning else T, dim), dtype=x.dtype, device=x.device)
     kept = torch.empty((B, keep_k), dtype=torch.int32, device=x.device) if pruning else None
     nbytes = lib.vit_workspace_bytes(ctypes.byref(d))
     ws = _workspace(max(nbytes, 1), x.device, workspace)

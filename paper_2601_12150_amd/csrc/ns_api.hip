@@ -64,8 +64,9 @@ ns_status validate_desc(const ns_attn_desc *d, bool need_out_strides, bool need_
   if (d->head_dim != 64) return fail(NS_ERR_UNSUPPORTED, "head_dim %d: only 64 is implemented", d->head_dim);
   if (need_grid && d->radius != 1)
     return fail(NS_ERR_UNSUPPORTED, "radius %d: only 1 (3x3 blocks) is implemented", d->radius);
-  if (d->n_global != 1) return fail(NS_ERR_UNSUPPORTED, "n_global %d: only 1 is implemented", d->n_global);
-  if (d->heads > 1024) return fail(NS_ERR_UNSUPPORTED, "more than 1024 heads");
+  if (d->n_global > 256) return fail(NS_ERR_UNSUPPORTED, "more than 256 global tokens");
+  if ((long long)d->heads * d->n_global > 1024)
+    return fail(NS_ERR_UNSUPPORTED, "heads x n_global above 1024");
   if (need_grid && d->block > 256) return fail(NS_ERR_UNSUPPORTED, "block side above 256");
   const size_t es = elt_size(d->dtype);
   if (d->q_stride_t < d->head_dim || (d->q_stride_b * es) % 16 || (d->q_stride_h * es) % 16 ||
@@ -95,7 +96,7 @@ AttnWorkspace attn_workspace_layout(const ns_attn_desc &d) {
   w.partials_off = off;
   // (the sweep kernel leaves 4 records per row of blocks instead of one per 512 keys)
   const size_t nrec = std::max<size_t>(cls_num_chunks(d.tokens), d.block > 0 ? 4 * (size_t)((d.grid_h + d.block - 1) / d.block) : 0);
-  off += align_up((size_t)d.batch * d.heads * nrec * kClsPartialFloats * 4, 256);
+  off += align_up((size_t)d.batch * d.heads * d.n_global * nrec * kClsPartialFloats * 4, 256);
   w.lists_off = w.counts_off = off;
   if (wants_lists(d)) {
     const size_t nbh = (d.grid_h + d.block - 1) / d.block, nbw = (d.grid_w + d.block - 1) / d.block;
@@ -295,8 +296,8 @@ const char *ns_attn_patch_kernel_name(const ns_attn_desc *desc) {
 size_t cls_scores_workspace_bytes(const ns_attn_desc *desc) {
   if (validate_desc(desc, false, false) != NS_OK) return 0;
   const ns_attn_desc &d = *desc;
-  return align_up((size_t)d.batch * d.heads * d.tokens * 4, 256) +
-         align_up((size_t)d.batch * d.heads * cls_num_chunks(d.tokens) * kClsPartialFloats * 4, 256);
+  return align_up((size_t)d.batch * d.heads * d.n_global * d.tokens * 4, 256) +
+         align_up((size_t)d.batch * d.heads * d.n_global * cls_num_chunks(d.tokens) * kClsPartialFloats * 4, 256);
 }
 
 ns_status cls_scores(const ns_attn_desc *desc, const void *q, const void *k, float *scores,
@@ -312,7 +313,7 @@ ns_status cls_scores(const ns_attn_desc *desc, const void *q, const void *k, flo
   hipStream_t s = static_cast<hipStream_t>(stream);
   float *logits = static_cast<float *>(workspace);
   float *partials = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) +
-                                              align_up((size_t)d.batch * d.heads * d.tokens * 4, 256));
+                                              align_up((size_t)d.batch * d.heads * d.n_global * d.tokens * 4, 256));
   st = launch_cls_row(d, q, k, nullptr, logits, partials, false, s);
   if (st != NS_OK) return st;
   return launch_cls_scores(d.batch, d.heads, d.tokens, d.n_global, logits, nullptr, partials,
@@ -324,7 +325,7 @@ ns_status cls_scores_from_logits(int32_t batch, int32_t heads, int32_t tokens, i
                                  void *stream) {
   if (batch < 1 || heads < 1 || n_global < 1 || tokens <= n_global)
     return fail(NS_ERR_INVALID_ARG, "batch, heads, n_global must be positive and tokens > n_global");
-  if (heads > 1024) return fail(NS_ERR_UNSUPPORTED, "more than 1024 heads");
+  if ((long long)heads * n_global > 1024) return fail(NS_ERR_UNSUPPORTED, "heads x n_global above 1024");
   if (batch > 65535) return fail(NS_ERR_UNSUPPORTED, "batch above 65535");
   if (!cls_logits || !cls_lse || !scores) return fail(NS_ERR_INVALID_ARG, "NULL pointer");
   if (!aligned(cls_logits, 4) || !aligned(cls_lse, 4) || !aligned(scores, 4))
@@ -342,8 +343,17 @@ ns_status topk_filter(int32_t batch, int32_t n, int32_t k, const float *scores, 
                       int32_t channels, int32_t x_dtype, const int32_t *coords_in,
                       int32_t *kept_idx, void *y, int32_t *coords_out, void *workspace,
                       size_t workspace_bytes, void *stream) {
+  return topk_filter_global(batch, n, k, 1, scores, x, channels, x_dtype, coords_in, kept_idx, y, coords_out,
+                            workspace, workspace_bytes, stream);
+}
+
+ns_status topk_filter_global(int32_t batch, int32_t n, int32_t k, int32_t n_global, const float *scores,
+                             const void *x, int32_t channels, int32_t x_dtype, const int32_t *coords_in,
+                             int32_t *kept_idx, void *y, int32_t *coords_out, void *workspace,
+                             size_t workspace_bytes, void *stream) {
   (void)workspace; (void)workspace_bytes;
   if (batch < 1 || n < 1) return fail(NS_ERR_INVALID_ARG, "batch and n must be positive");
+  if (n_global < 1) return fail(NS_ERR_INVALID_ARG, "n_global must be >= 1");
   if (k < 1 || k > n) return fail(NS_ERR_INVALID_ARG, "k = %d must be in [1, n = %d]", k, n);
   if (batch > 65535) return fail(NS_ERR_UNSUPPORTED, "batch above 65535");
   if (!scores || !kept_idx) return fail(NS_ERR_INVALID_ARG, "scores and kept_idx must not be NULL");
@@ -364,7 +374,7 @@ ns_status topk_filter(int32_t batch, int32_t n, int32_t k, const float *scores, 
   hipStream_t s = static_cast<hipStream_t>(stream);
   ns_status st = launch_topk_select(batch, n, k, scores, coords_in, kept_idx, coords_out, s);
   if (st != NS_OK) return st;
-  if (x) return launch_gather_rows(batch, n, k, row_bytes, x, kept_idx, y, s);
+  if (x) return launch_gather_rows(batch, n, k, n_global, row_bytes, x, kept_idx, y, s);
   return NS_OK;
 }
 

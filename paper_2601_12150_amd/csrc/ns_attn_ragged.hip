@@ -28,6 +28,7 @@ struct RaggedParams {
   float c;               // scale * log2(e)
   int nbh, nbw, cap;     // blocks per side, slots per block in `lists`
   int tpb;               // runs of 64 slots per block: ceil(cap / 64)
+  int n_global;          // leading global tokens (keys of every query)
   int heads;
   const int32_t *lists;  // [B, nbh*nbw, cap] token indices
   const int32_t *counts; // [B, nbh*nbw]
@@ -74,8 +75,10 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_ragged_kernel(RaggedParams p
   // token of slot `lane` of the run that starts at `base` in a block's list; slots beyond the
   // run's fill repeat its first slot (a valid row: its logits are masked, its weights are zero,
   // its output is not stored)
+  // blk2 < 0: the global tokens after the first, tokens 1 .. n_global-1, as a list of their own
   auto slot_token = [&](int blk2, int base, int cnt) {
-    return lst[(size_t)blk2 * p.cap + base + (lane < cnt ? lane : 0)];
+    const int slot = base + (lane < cnt ? lane : 0);
+    return blk2 < 0 ? 1 + slot : lst[(size_t)blk2 * p.cap + slot];
   };
 
   // ---- Q as B operand: lane (query l32 + 32*nt, half hh) holds channels 32*hh + 8*s + j
@@ -146,9 +149,15 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_ragged_kernel(RaggedParams p
 
   // The key tiles in order: neighbour blocks by position, the runs of a block in list order.
   int kblk = 0, kfill = 0, kbase = 0;         // current block, its fill, start of the current run
-  auto have_next = [&]() { return kbase + 64 < kfill || nbmask != 0; };
+  bool globals_pending = p.n_global > 1;      // they come first
+  auto have_next = [&]() { return kbase + 64 < kfill || globals_pending || nbmask != 0; };
   auto advance = [&]() {                       // only when have_next()
     if (kbase + 64 < kfill) { kbase += 64; return; }
+    if (globals_pending) {
+      globals_pending = false;
+      kblk = -1; kfill = p.n_global - 1; kbase = 0;
+      return;
+    }
     const int nb = __builtin_ctz(nbmask);
     nbmask &= nbmask - 1;
     kblk = (R + nb / 3 - 1) * p.nbw + (C + nb % 3 - 1);
@@ -282,7 +291,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_ragged_kernel(RaggedParams p
 }  // namespace
 
 bool ragged_attn_supported(const ns_attn_desc &d) {
-  return d.dtype == NS_BF16 && d.head_dim == 64 && d.radius == 1 && d.n_global == 1 &&
+  return d.dtype == NS_BF16 && d.head_dim == 64 && d.radius == 1 && d.n_global >= 1 &&
          d.scale > 0.f && d.heads <= 65535 && d.batch <= 65535 &&
          (long long)d.tokens * d.q_stride_t * 2 < 0x7fffffffLL &&
          (long long)d.tokens * d.out_stride_t * 2 < 0x7fffffffLL;
@@ -300,6 +309,7 @@ ns_status launch_attn_ragged(const AttnArgs &a) {
   p.c = d.scale * kLog2e;
   p.nbh = a.geom.nbh; p.nbw = a.geom.nbw; p.cap = a.geom.cap;
   p.tpb = (p.cap + 63) / 64;
+  p.n_global = d.n_global;
   p.heads = d.heads;
   p.lists = a.geom.lists; p.counts = a.geom.counts;
   if (!p.lists || !p.counts) return fail(NS_ERR_INVALID_ARG, "the list kernel was launched without block lists");

@@ -33,16 +33,19 @@ template <> struct Row8<uint16_t> {
 
 constexpr int kSteps = kClsChunk / (4 * 8);   // 4 waves x 8 keys per wave-step
 
-// grid (chunks, H, B), 256 threads.  Lane = (key slot, 8-channel slice): 8 lanes per key row.
+// grid (chunks, H*G, B), 256 threads.  Lane = (key slot, 8-channel slice): 8 lanes per key row.
+// With G global tokens the rows of one head are G consecutive "rows" hg = h*G + g; logits are
+// [B, H*G, T] and the partial records [B, H*G, chunks].
 template <typename T, bool WITH_V>
 __global__ __launch_bounds__(256) void cls_row_kernel(const T *q, const T *k, const T *v,
                                                       int64_t sb, int64_t sh, int64_t st, int T_,
-                                                      int H, float scale, float *logits,
+                                                      int H, int G, float scale, float *logits,
                                                       float *partials, int nchunks) {
-  const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int chunk = blockIdx.x, hg = blockIdx.y, b = blockIdx.z;
+  const int h = hg / G, gq = hg - h * G;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int slot = lane >> 3, sub = lane & 7;
-  const T *qb = q + b * sb + h * sh;          // token 0
+  const T *qb = q + b * sb + h * sh + gq * st;   // global token gq
   const T *kb = k + b * sb + h * sh;
   const T *vb = WITH_V ? v + b * sb + h * sh : nullptr;
   __shared__ float red[4];
@@ -73,7 +76,7 @@ __global__ __launch_bounds__(256) void cls_row_kernel(const T *q, const T *k, co
     acc += __shfl_xor(acc, 4);
     s[i] = acc;
     mx = fmaxf(mx, acc);
-    if (sub == 0 && key < T_ && logits) logits[((size_t)b * H + h) * T_ + key] = acc;
+    if (sub == 0 && key < T_ && logits) logits[((size_t)b * H * G + hg) * T_ + key] = acc;
   }
   mx = fmaxf(mx, __shfl_xor(mx, 8));
   mx = fmaxf(mx, __shfl_xor(mx, 16));
@@ -114,7 +117,7 @@ __global__ __launch_bounds__(256) void cls_row_kernel(const T *q, const T *k, co
     for (int e = 0; e < 8; e++) osum[wave][sub * 8 + e] = o8[e];
   }
   __syncthreads();
-  float *rec = partials + (((size_t)b * H + h) * nchunks + chunk) * kClsPartialFloats;
+  float *rec = partials + (((size_t)b * H * G + hg) * nchunks + chunk) * kClsPartialFloats;
   if (tid == 0) {
     rec[0] = M;
     rec[1] = (red[0] + red[1]) + (red[2] + red[3]);
@@ -125,15 +128,16 @@ __global__ __launch_bounds__(256) void cls_row_kernel(const T *q, const T *k, co
 __device__ __forceinline__ void store_out(float *p, float x) { *p = x; }
 __device__ __forceinline__ void store_out(uint16_t *p, float x) { *p = (uint16_t)(pack_bf16(x, 0.f) & 0xffffu); }
 
-// grid (H, B), 256 threads: thread (group g = tid/64, channel d = tid%64).  Group g merges the
+// grid (H*G, B), 256 threads: thread (group g = tid/64, channel d = tid%64).  Group g merges the
 // chunk partials g, g+4, g+8, ... with a running maximum; the four groups are then merged in
 // group order.  The order of operations is fixed, so the result is deterministic.
 template <typename T, bool WITH_V>
-__global__ __launch_bounds__(256) void cls_combine_kernel(const float *partials, int nchunks, int H,
-                                                          T *out, int64_t osb, int64_t osh,
+__global__ __launch_bounds__(256) void cls_combine_kernel(const float *partials, int nchunks, int H, int G,
+                                                          T *out, int64_t osb, int64_t osh, int64_t ost,
                                                           float *lse) {
-  const int h = blockIdx.x, b = blockIdx.y, g = threadIdx.x >> 6, d = threadIdx.x & 63;
-  const float *rec = partials + ((size_t)b * H + h) * nchunks * kClsPartialFloats;
+  const int hg = blockIdx.x, b = blockIdx.y, g = threadIdx.x >> 6, d = threadIdx.x & 63;
+  const int h = hg / G, gq = hg - h * G;
+  const float *rec = partials + ((size_t)b * H * G + hg) * nchunks * kClsPartialFloats;
   __shared__ float sm[4], sl[4], so[4][64];
   float M = -INFINITY, L = 0.f, O = 0.f;
 #pragma unroll 4
@@ -158,12 +162,13 @@ __global__ __launch_bounds__(256) void cls_combine_kernel(const float *partials,
     Lt = __builtin_fmaf(sl[i], w, Lt);
     Ot = __builtin_fmaf(so[i][d], w, Ot);
   }
-  if (WITH_V) store_out(out + b * osb + h * osh + d, Ot / Lt);
-  if (lse && d == 0) lse[(size_t)b * H + h] = Mt + __builtin_amdgcn_logf(Lt) * kLn2;
+  if (WITH_V) store_out(out + b * osb + h * osh + gq * ost + d, Ot / Lt);
+  if (lse && d == 0) lse[(size_t)b * H * G + hg] = Mt + __builtin_amdgcn_logf(Lt) * kLn2;
 }
 
-// grid (ceil(N/256), B), 256 threads (thread = patch).  lse given directly, or recomputed per
-// head from the row kernel's (max, sum) partials.
+// grid (ceil(N/256), B), 256 threads (thread = patch).  H counts the global rows of an image
+// (heads x global tokens): the score is the mean over all of them.  lse given directly, or
+// recomputed per row from the row kernel's (max, sum) partials.
 __global__ __launch_bounds__(256) void cls_scores_kernel(const float *logits, const float *lse,
                                                          const float *partials, int nchunks, int H,
                                                          int T_, int G, float *scores) {
@@ -216,11 +221,12 @@ __global__ __launch_bounds__(256) void cls_scores_kernel(const float *logits, co
 ns_status launch_cls_row(const ns_attn_desc &d, const void *q, const void *k, const void *v,
                          float *logits, float *partials, bool with_v, hipStream_t s) {
   const int nch = cls_num_chunks(d.tokens);
-  dim3 grid(nch, d.heads, d.batch), blk(256);
+  dim3 grid(nch, d.heads * d.n_global, d.batch), blk(256);
 #define NS_ROW(T, WV)                                                                          \
   hipLaunchKernelGGL((cls_row_kernel<T, WV>), grid, blk, 0, s, static_cast<const T *>(q),      \
                      static_cast<const T *>(k), static_cast<const T *>(v), d.q_stride_b,       \
-                     d.q_stride_h, d.q_stride_t, d.tokens, d.heads, d.scale, logits, partials, nch)
+                     d.q_stride_h, d.q_stride_t, d.tokens, d.heads, d.n_global, d.scale, logits, \
+                     partials, nch)
   if (d.dtype == NS_F32) { if (with_v) NS_ROW(float, true); else NS_ROW(float, false); }
   else { if (with_v) NS_ROW(uint16_t, true); else NS_ROW(uint16_t, false); }
 #undef NS_ROW
@@ -230,21 +236,23 @@ ns_status launch_cls_row(const ns_attn_desc &d, const void *q, const void *k, co
 ns_status launch_cls_combine(const ns_attn_desc &d, const float *partials, void *out, float *lse,
                              bool with_v, hipStream_t s, int nchunks) {
   const int nch = nchunks > 0 ? nchunks : cls_num_chunks(d.tokens);
-  dim3 grid(d.heads, d.batch), blk(256);
+  dim3 grid(d.heads * d.n_global, d.batch), blk(256);
   if (d.dtype == NS_F32) {
     if (with_v)
       hipLaunchKernelGGL((cls_combine_kernel<float, true>), grid, blk, 0, s, partials, nch, d.heads,
-                         static_cast<float *>(out), d.out_stride_b, d.out_stride_h, lse);
+                         d.n_global, static_cast<float *>(out), d.out_stride_b, d.out_stride_h, d.out_stride_t, lse);
     else
       hipLaunchKernelGGL((cls_combine_kernel<float, false>), grid, blk, 0, s, partials, nch, d.heads,
-                         static_cast<float *>(out), d.out_stride_b, d.out_stride_h, lse);
+                         d.n_global, static_cast<float *>(out), d.out_stride_b, d.out_stride_h, d.out_stride_t, lse);
   } else {
     if (with_v)
       hipLaunchKernelGGL((cls_combine_kernel<uint16_t, true>), grid, blk, 0, s, partials, nch,
-                         d.heads, static_cast<uint16_t *>(out), d.out_stride_b, d.out_stride_h, lse);
+                         d.heads, d.n_global, static_cast<uint16_t *>(out), d.out_stride_b, d.out_stride_h,
+                         d.out_stride_t, lse);
     else
       hipLaunchKernelGGL((cls_combine_kernel<uint16_t, false>), grid, blk, 0, s, partials, nch,
-                         d.heads, static_cast<uint16_t *>(out), d.out_stride_b, d.out_stride_h, lse);
+                         d.heads, d.n_global, static_cast<uint16_t *>(out), d.out_stride_b, d.out_stride_h,
+                         d.out_stride_t, lse);
   }
   return check_launch("cls_combine_kernel");
 }
@@ -253,7 +261,7 @@ ns_status launch_cls_scores(int B, int H, int T, int G, const float *logits, con
                             const float *partials, int nchunks, float *scores, hipStream_t s) {
   const int N = T - G;
   dim3 grid((N + 255) / 256, B), blk(256);
-  hipLaunchKernelGGL(cls_scores_kernel, grid, blk, 0, s, logits, lse, partials, nchunks, H, T, G,
+  hipLaunchKernelGGL(cls_scores_kernel, grid, blk, 0, s, logits, lse, partials, nchunks, H * G, T, G,
                      scores);
   return check_launch("cls_scores_kernel");
 }

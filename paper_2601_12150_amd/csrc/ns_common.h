@@ -134,7 +134,7 @@ ns_status launch_gemm256(const uint16_t *a, const uint16_t *w, const float *bias
 
 ns_status launch_topk_select(int B, int N, int k, const float *scores, const int32_t *coords_in,
                              int32_t *kept, int32_t *coords_out, hipStream_t s);
-ns_status launch_gather_rows(int B, int N, int k, size_t row_bytes, const void *x,
+ns_status launch_gather_rows(int B, int N, int k, int G, size_t row_bytes, const void *x,
                              const int32_t *kept, void *y, hipStream_t s);
 
 }  // namespace ns

@@ -235,15 +235,15 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_reg_kernel(const floa
   }
 }
 
-// grid (ceil((1+k)/4), B), 256 threads: one wave per output row.
+// grid (ceil((G+k)/4), B), 256 threads: one wave per output row; the G global rows come first.
 __global__ __launch_bounds__(256) void gather_rows_kernel(const uint4 *x, const int32_t *kept,
-                                                          uint4 *y, int N, int k, int vec_per_row) {
+                                                          uint4 *y, int N, int k, int G, int vec_per_row) {
   const int b = blockIdx.y;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
-  if (row > k) return;
-  const int src = row == 0 ? 0 : 1 + kept[(size_t)b * k + row - 1];
-  const uint4 *xs = x + ((size_t)b * (1 + N) + src) * vec_per_row;
-  uint4 *yd = y + ((size_t)b * (1 + k) + row) * vec_per_row;
+  if (row >= G + k) return;
+  const int src = row < G ? row : G + kept[(size_t)b * k + row - G];
+  const uint4 *xs = x + ((size_t)b * (G + N) + src) * vec_per_row;
+  uint4 *yd = y + ((size_t)b * (G + k) + row) * vec_per_row;
   for (int i = lane; i < vec_per_row; i += 64) yd[i] = xs[i];
 }
 
@@ -263,11 +263,11 @@ ns_status launch_topk_select(int B, int N, int k, const float *scores, const int
   return check_launch("topk_select_kernel");
 }
 
-ns_status launch_gather_rows(int B, int N, int k, size_t row_bytes, const void *x,
+ns_status launch_gather_rows(int B, int N, int k, int G, size_t row_bytes, const void *x,
                              const int32_t *kept, void *y, hipStream_t s) {
-  dim3 grid((1 + k + 3) / 4, B);
+  dim3 grid((G + k + 3) / 4, B);
   hipLaunchKernelGGL(gather_rows_kernel, grid, dim3(256), 0, s, static_cast<const uint4 *>(x), kept,
-                     static_cast<uint4 *>(y), N, k, (int)(row_bytes / 16));
+                     static_cast<uint4 *>(y), N, k, G, (int)(row_bytes / 16));
   return check_launch("gather_rows_kernel");
 }
 

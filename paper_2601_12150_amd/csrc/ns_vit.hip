@@ -231,8 +231,8 @@ VitWorkspace vit_layout(const ns_vit_block_desc &d, const ns_attn_desc &ad) {
   w.attn = take(M * d.dim * 2);
   w.h = take(M * d.dim * 2);
   w.hidden = take(M * d.mlp_dim * 2);
-  w.logits = take((size_t)ad.batch * ad.heads * ad.tokens * 4);
-  w.lse = take((size_t)ad.batch * ad.heads * 4);
+  w.logits = take((size_t)ad.batch * ad.heads * ad.n_global * ad.tokens * 4);
+  w.lse = take((size_t)ad.batch * ad.heads * ad.n_global * 4);
   w.attn_ws = off;
   off += align_up(ns_attn_workspace_bytes(&ad), 256);
   w.total = off;
@@ -438,7 +438,8 @@ ns_status vit_forward(const ns_vit_desc *desc, const ns_vit_block_weights *weigh
       st = check_launch("raster_coords_kernel");
       if (st != NS_OK) return st;
       void *y = last ? x_out : buf[flip];
-      st = topk_filter(full.batch, N, desc->keep_k, scores, cur, bd.dim, NS_BF16, cin, kept, y, cout, nullptr, 0, s);
+      st = topk_filter_global(full.batch, N, desc->keep_k, full.n_global, scores, cur, bd.dim, NS_BF16, cin, kept,
+                              y, cout, nullptr, 0, s);
       if (st != NS_OK) return st;
       cur = y;
       flip ^= 1;

@@ -59,12 +59,12 @@ def test_descriptor_validation(nb):
              ("q_stride_t", 63, nb.NS_ERR_INVALID_ARG), ("q_stride_h", 65 * 64 + 1, nb.NS_ERR_INVALID_ARG),
              ("out_stride_t", 8, nb.NS_ERR_INVALID_ARG),
              ("head_dim", 128, nb.NS_ERR_UNSUPPORTED), ("radius", 2, nb.NS_ERR_UNSUPPORTED),
-             ("n_global", 2, nb.NS_ERR_UNSUPPORTED)]
+             ("n_global", 300, nb.NS_ERR_UNSUPPORTED), ("n_global", 0, nb.NS_ERR_INVALID_ARG)]
     for field, value, code in cases:
         d = good_desc(nb)
         setattr(d, field, value)
         if field == "n_global":
-            d.tokens = 66
+            d.tokens = 64 + value
         assert attn_call(nb, d) == code, field
         assert nb.lib.ns_last_error()
         assert nb.lib.ns_attn_workspace_bytes(ctypes.byref(d)) == 0
