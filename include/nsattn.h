@@ -218,6 +218,21 @@ ns_status vit_forward(const ns_vit_desc *desc, const ns_vit_block_weights *weigh
                       void *stream);
 
 /*
+ * The same stack, also handing out the patch tokens after chosen blocks as spatial feature maps
+ * (paper, "Segmentation": the segmentation head needs feature maps that preserve the image's
+ * spatial structure, so the sparse attention runs in every layer and nothing is pruned before a
+ * map is taken).  Tokens are never permuted inside the library, so a map is simply the patch rows
+ * in raster order.
+ *   n_taps      number of feature maps (0: identical to vit_forward)
+ *   tap_layers  HOST array [n_taps], ascending, 1-based: map i is taken after block tap_layers[i];
+ *               with a pruning stage every tap must lie at or before prune_after
+ *   tap_out     HOST array [n_taps] of device pointers, each [B, grid_h*grid_w, dim] bf16
+ */
+ns_status vit_forward_features(const ns_vit_desc *desc, const ns_vit_block_weights *weights, const void *x_in,
+                               void *x_out, int32_t *kept_idx, int32_t n_taps, const int32_t *tap_layers,
+                               void *const *tap_out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Measurement aid for benchmarks (not part of the method): enqueues `reps` launches of the
  * patch-query attention kernel alone (the dominant kernel of ns_attn_forward; no CLS row)
  * on `stream`, bracketed by HIP events recorded on that stream, WAITS for them, and stores

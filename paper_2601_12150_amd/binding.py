@@ -20,7 +20,7 @@ NS_OK, NS_ERR_INVALID_ARG, NS_ERR_UNSUPPORTED, NS_ERR_WORKSPACE, NS_ERR_HIP = ra
 NS_F32, NS_BF16 = 0, 1
 
 EXPORTS = ["ns_attn_workspace_bytes", "ns_attn_forward", "cls_scores_workspace_bytes", "cls_scores",
-           "cls_scores_from_logits", "topk_filter_workspace_bytes", "topk_filter", "topk_filter_global",
+           "cls_scores_from_logits", "topk_filter_workspace_bytes", "topk_filter", "topk_filter_global", "vit_forward_features",
            "vit_block_workspace_bytes", "vit_block_forward", "linear_forward", "vit_workspace_bytes", "vit_forward",
            "ns_attn_patch_kernel_time", "ns_attn_patch_kernel_name", "ns_last_error",
            "ns_version"]
@@ -100,6 +100,9 @@ def _load() -> ctypes.CDLL:
     lib.vit_forward.restype = ctypes.c_int
     lib.vit_forward.argtypes = [ctypes.POINTER(ns_vit_desc), ctypes.POINTER(ns_vit_block_weights), vp, vp, vp, vp,
                                 sz, vp]
+    lib.vit_forward_features.restype = ctypes.c_int
+    lib.vit_forward_features.argtypes = [ctypes.POINTER(ns_vit_desc), ctypes.POINTER(ns_vit_block_weights), vp, vp,
+                                         vp, i32, ctypes.POINTER(i32), ctypes.POINTER(vp), vp, sz, vp]
     lib.ns_last_error.restype = ctypes.c_char_p
     lib.ns_version.restype = ctypes.c_char_p
     return lib
@@ -345,11 +348,13 @@ def linear_forward(x, w, bias, residual=None, gelu=False, out=None, stream=None)
 
 
 def vit_forward(x, layer_weights, grid_h, grid_w, block, heads, prune_after=0, keep_k=0, ln_eps=1e-6,
-                scale=None, out=None, workspace=None, stream=None, n_global=1):
+                scale=None, out=None, workspace=None, stream=None, n_global=1, tap_layers=None):
     """A stack of blocks with one pruning stage after block `prune_after` (keep_k patches kept).
 
     x [B,T,dim] bf16; layer_weights: list of weight dicts (see vit_block_forward).
-    Returns (x_out [B, n_global+keep_k or T, dim], kept_idx [B,keep_k] or None)."""
+    Returns (x_out [B, n_global+keep_k or T, dim], kept_idx [B,keep_k] or None); with tap_layers
+    (ascending 1-based block numbers) also a list of feature maps [B, grid_h*grid_w, dim], the patch
+    tokens after those blocks in raster order."""
     if x.dtype != torch.bfloat16 or not x.is_contiguous():
         raise ValueError("x must be a contiguous bfloat16 tensor [B,T,dim]")
     B, T, dim = x.shape
@@ -375,6 +380,13 @@ def vit_forward(x, layer_weights, grid_h, grid_w, block, heads, prune_after=0, k
     kept = torch.empty((B, keep_k), dtype=torch.int32, device=x.device) if pruning else None
     nbytes = lib.vit_workspace_bytes(ctypes.byref(d))
     ws = _workspace(max(nbytes, 1), x.device, workspace)
-    _check(lib.vit_forward(ctypes.byref(d), warr, _ptr(x), _ptr(out), _ptr(kept), _ptr(ws), ws.numel(),
-                           _stream(stream)))
-    return out, kept
+    if tap_layers is None:
+        _check(lib.vit_forward(ctypes.byref(d), warr, _ptr(x), _ptr(out), _ptr(kept), _ptr(ws), ws.numel(),
+                               _stream(stream)))
+        return out, kept
+    taps = [torch.empty((B, grid_h * grid_w, dim), dtype=x.dtype, device=x.device) for _ in tap_layers]
+    tl = (ctypes.c_int32 * len(taps))(*[int(t) for t in tap_layers])
+    tp = (ctypes.c_void_p * len(taps))(*[t.data_ptr() for t in taps])
+    _check(lib.vit_forward_features(ctypes.byref(d), warr, _ptr(x), _ptr(out), _ptr(kept), len(taps), tl, tp,
+                                    _ptr(ws), ws.numel(), _stream(stream)))
+    return out, kept, taps

@@ -255,6 +255,15 @@ ns_status block_attn_desc(const ns_vit_block_desc *d, ns_attn_desc &ad) {
   return NS_OK;
 }
 
+// y[b][j][:] = x[b][G + j][:]: the patch rows of a sequence without its global rows, 16 bytes per
+// lane.  grid (ceil(N * vec_per_row / 256), B).
+__global__ __launch_bounds__(256) void patch_rows_kernel(const uint4 *x, uint4 *y, int N, int G, int vec_per_row) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x, n = (size_t)N * vec_per_row;
+  if (i >= n) return;
+  const size_t b = blockIdx.y;
+  y[b * n + i] = x[(b * (size_t)(N + G) + G) * vec_per_row + i];
+}
+
 // coords[b][j] = (r << 16 | c) of patch j of the full raster grid
 __global__ __launch_bounds__(256) void raster_coords_kernel(int32_t *coords, int n, int grid_w) {
   const int j = blockIdx.x * 256 + threadIdx.x;
@@ -399,9 +408,26 @@ ns_status linear_forward(int32_t M, int32_t N, int32_t K, const void *x, const v
 ns_status vit_forward(const ns_vit_desc *desc, const ns_vit_block_weights *weights, const void *x_in,
                       void *x_out, int32_t *kept_idx, void *workspace, size_t workspace_bytes,
                       void *stream) {
+  return vit_forward_features(desc, weights, x_in, x_out, kept_idx, 0, nullptr, nullptr, workspace,
+                              workspace_bytes, stream);
+}
+
+ns_status vit_forward_features(const ns_vit_desc *desc, const ns_vit_block_weights *weights, const void *x_in,
+                               void *x_out, int32_t *kept_idx, int32_t n_taps, const int32_t *tap_layers,
+                               void *const *tap_out, void *workspace, size_t workspace_bytes, void *stream) {
   bool prune;
   ns_status st = check_stack(desc, prune);
   if (st != NS_OK) return st;
+  if (n_taps < 0 || (n_taps > 0 && (!tap_layers || !tap_out)))
+    return fail(NS_ERR_INVALID_ARG, "n_taps must be >= 0 and the tap arrays given with it");
+  for (int i = 0; i < n_taps; i++) {
+    if (tap_layers[i] < 1 || tap_layers[i] > desc->layers || (i > 0 && tap_layers[i] <= tap_layers[i - 1]))
+      return fail(NS_ERR_INVALID_ARG, "tap_layers must be ascending in 1..layers");
+    if (prune && tap_layers[i] > desc->prune_after)
+      return fail(NS_ERR_INVALID_ARG, "a feature map after the pruning stage has no grid structure left");
+    if (!tap_out[i] || reinterpret_cast<uintptr_t>(tap_out[i]) % 16)
+      return fail(NS_ERR_INVALID_ARG, "tap_out[%d] is NULL or misaligned", i);
+  }
   const size_t bw = vit_block_workspace_bytes(&desc->block);
   if (bw == 0) return NS_ERR_INVALID_ARG;   // message set by the block validation
   if (!weights || !x_in || !x_out) return fail(NS_ERR_INVALID_ARG, "weights, x_in and x_out must not be NULL");
@@ -422,6 +448,7 @@ ns_status vit_forward(const ns_vit_desc *desc, const ns_vit_block_weights *weigh
   const void *cur = x_in;
   int flip = 0;
   bool lists_built = false;   // block lists stay valid from block to block until the sequence changes
+  int tap = 0;
   for (int l = 0; l < desc->layers; l++) {
     const bool last = l + 1 == desc->layers, scoring = prune && l + 1 == desc->prune_after;
     // the last block writes x_out directly unless the pruning stage still follows it
@@ -432,6 +459,15 @@ ns_status vit_forward(const ns_vit_desc *desc, const ns_vit_block_weights *weigh
     lists_built = true;
     cur = dst;
     flip ^= 1;
+    if (tap < n_taps && tap_layers[tap] == l + 1) {
+      const int vec = bd.dim * 2 / 16;
+      dim3 grid((unsigned)(((size_t)N * vec + 255) / 256), full.batch);
+      hipLaunchKernelGGL(patch_rows_kernel, grid, dim3(256), 0, s, static_cast<const uint4 *>(cur),
+                         static_cast<uint4 *>(tap_out[tap]), N, full.n_global, vec);
+      st = check_launch("patch_rows_kernel");
+      if (st != NS_OK) return st;
+      tap++;
+    }
     if (scoring) {
       dim3 grid((N + 255) / 256, full.batch);
       hipLaunchKernelGGL(raster_coords_kernel, grid, dim3(256), 0, s, cin, N, full.grid_w);

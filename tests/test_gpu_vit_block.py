@@ -67,13 +67,16 @@ def test_block_validation(nb):
     assert e.value.code == nb.NS_ERR_INVALID_ARG
 
 
-def test_stack_with_pruning_stage(nb):
-    """4 blocks, pruning after block 2.  The GPU's kept set must agree with the oracle's scores
-    outside the tie band; the oracle then continues on the GPU's kept set, so the final outputs
-    are comparable element by element."""
-    B, g, block, heads, dim, mlp, layers, after = 2, 16, 8, 8, 512, 640, 4, 2
+@pytest.mark.parametrize("layers,after,keep_pct,g,block", [(4, 2, 60, 16, 8), (5, 4, 40, 16, 8), (3, 1, 20, 20, 8),
+                                                           (3, 3, 50, 16, 8), (4, 2, 30, 32, 16)])
+def test_stack_with_pruning_stage(nb, layers, after, keep_pct, g, block):
+    """A stack with the pruning stage after block `after` (the paper's example: after the fourth
+    layer) and keep ratios 20-60 % (discarded proportion p = 0.4-0.8).  The GPU's kept set must
+    agree with the oracle's scores outside the tie band; the oracle then continues on the GPU's
+    kept set, so the final outputs are comparable element by element."""
+    B, heads, dim, mlp = 2, 8, 512, 640
     N, T = g * g, 1 + g * g
-    keep = (N * 60 + 99) // 100
+    keep = (N * keep_pct + 99) // 100
     rng = np.random.default_rng(21)
     x = synth.round_to_bf16(rng.standard_normal((B, T, dim)).astype(np.float32))
     ws = [synth.make_block_weights(dim, mlp, seed=30 + i, dtype="bf16", ln_random=True) for i in range(layers)]
@@ -110,6 +113,33 @@ def test_stack_without_pruning_equals_repeated_blocks(nb):
         h = nb.vit_block_forward(h, w, g, g, block, heads)
     torch.cuda.synchronize()
     assert kept is None and torch.equal(out, h)
+
+
+def test_stack_feature_maps(nb):
+    """Segmentation mode: sparse attention in every layer, no pruning, patch tokens after chosen
+    blocks handed out in raster order.  Each map equals the patch rows of the block-by-block run
+    (which the block tests pin to the oracle), bit for bit."""
+    B, g, block, heads, dim, mlp = 2, 20, 8, 8, 512, 512       # 20 is not a multiple of 8
+    rng = np.random.default_rng(23)
+    x = torch.from_numpy(synth.round_to_bf16(rng.standard_normal((B, 1 + g * g, dim)).astype(np.float32))).to(torch.bfloat16).cuda()
+    ws = [dev_weights(synth.make_block_weights(dim, mlp, seed=50 + i)) for i in range(4)]
+    out, kept, taps = nb.vit_forward(x, ws, g, g, block, heads, tap_layers=[1, 3, 4])
+    h, hs = x, []
+    for w in ws:
+        h = nb.vit_block_forward(h, w, g, g, block, heads)
+        hs.append(h)
+    torch.cuda.synchronize()
+    assert kept is None and torch.equal(out, h)
+    for t, l in zip(taps, (1, 3, 4)):
+        assert t.shape == (B, g * g, dim) and torch.equal(t, hs[l - 1][:, 1:])
+    # with a pruning stage, a map may be taken up to the pruning point and not after it
+    keep = 150
+    out2, kept2, taps2 = nb.vit_forward(x, ws, g, g, block, heads, prune_after=2, keep_k=keep, tap_layers=[2])
+    torch.cuda.synchronize()
+    assert torch.equal(taps2[0], hs[1][:, 1:]) and out2.shape == (B, 1 + keep, dim)
+    with pytest.raises(nb.NsError) as e:
+        nb.vit_forward(x, ws, g, g, block, heads, prune_after=2, keep_k=keep, tap_layers=[3])
+    assert e.value.code == nb.NS_ERR_INVALID_ARG
 
 
 @pytest.mark.parametrize("M,N,K,gelu,res", [
