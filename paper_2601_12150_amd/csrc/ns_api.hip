@@ -132,42 +132,48 @@ size_t ns_attn_workspace_bytes(const ns_attn_desc *desc) {
 }
 
 // Kernel choice for the patch queries.  On the full grid with bf16, head_dim 64 and 8x8 or 16x16
-// blocks there are three MFMA kernels that compute the same function: the sweep (8x8 blocks; key
-// tiles shared along a row of blocks, the global query's row computed on the way; wants at least
-// one row of blocks per CU),
+// blocks there are three MFMA kernels that compute the same function: the sweep (8x8 blocks, also
+// on grids that 8 does not divide; key tiles shared along a row of blocks, the global query's row
+// computed on the way; wants at least one row of blocks per CU),
 // the block kernel (16x16 blocks; key tiles shared by a block's four query tiles; wants two blocks
 // per CU), the persistent one-wave-per-SIMD kernel (needs two blocks per grid side), and the plain
 // one-wave-per-query-tile kernel.  Every other bf16 problem with head_dim 64 (a pruned sequence, a
 // grid that the block side does not divide, other block sides) takes the MFMA kernel that walks
 // per-block token lists, and the rest (fp32, other head sizes) the fp32 FMA kernel.
-// NSATTN_KERNEL = sweep | block | persist | mfma | generic forces one of them where it applies.
+// NSATTN_KERNEL = sweep | block | persist | mfma | lists | generic forces one of them where it applies.
 enum PatchKernel { PK_SWEEP, PK_BLOCK16, PK_PERSIST, PK_MFMA, PK_RAGGED, PK_GENERIC };
+
+static int device_cus() {
+  static int num_cus = 0;
+  if (num_cus == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    num_cus = (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+                  ? prop.multiProcessorCount : 256;
+  }
+  return num_cus;
+}
 
 static PatchKernel choose_patch_kernel(const ns_attn_desc &d) {
   const char *e = getenv("NSATTN_KERNEL");
   const char force = e ? e[0] : 0;
   if (force == 'g') return PK_GENERIC;        // serves every problem
-  if (mfma_attn_supported(d)) {
-    static int num_cus = 0;
-    if (num_cus == 0) {
-      int dev = 0;
-      hipDeviceProp_t prop;
-      num_cus = (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-                    ? prop.multiProcessorCount : 256;
-    }
-    const long long strips = (long long)d.batch * d.heads * (d.grid_h / d.block);
-    const bool sweep_ok = sweep_attn_supported(d), persist_ok = persist_attn_supported(d);
+  const bool tiled_ok = mfma_attn_supported(d);               // block side 8 or 16 dividing the grid
+  const bool sweep_ok = sweep_attn_supported(d);              // block side 8, any grid
+  const long long strips = (long long)d.batch * d.heads * ((d.grid_h + d.block - 1) / d.block);
+  if (force == 's' && sweep_ok) return PK_SWEEP;
+  if (tiled_ok) {
+    const bool persist_ok = persist_attn_supported(d), block16_ok = block16_attn_supported(d);
     const long long blocks = strips * (d.grid_w / d.block);
-    const bool block16_ok = block16_attn_supported(d);
-    if (force == 's' && sweep_ok) return PK_SWEEP;
     if (force == 'b' && block16_ok) return PK_BLOCK16;
     if (force == 'p' && persist_ok) return PK_PERSIST;
     if (force == 'm') return PK_MFMA;
-    if (sweep_ok && strips >= num_cus) return PK_SWEEP;
-    if (block16_ok && blocks >= 2LL * num_cus) return PK_BLOCK16;
+    if (sweep_ok && strips >= device_cus()) return PK_SWEEP;
+    if (block16_ok && blocks >= 2LL * device_cus()) return PK_BLOCK16;
     if (persist_ok) return PK_PERSIST;
     return PK_MFMA;
   }
+  if (sweep_ok && force != 'l' && strips >= device_cus()) return PK_SWEEP;   // short edge blocks
   if (ragged_attn_supported(d)) return PK_RAGGED;   // its lists: wants_lists()
   return PK_GENERIC;
 }
@@ -207,7 +213,9 @@ static ns_status prepare_attn(const ns_attn_desc *desc, const void *q, const voi
   g.nbw = (d.grid_w + d.block - 1) / d.block;
   g.n_global = d.n_global; g.tokens = d.tokens; g.cap = d.block * d.block;
   g.lists = nullptr; g.counts = nullptr;
-  if (wants_lists(d)) {
+  // (the workspace has room for lists whenever wants_lists(); a complete grid that the sweep serves
+  // does without them)
+  if (wants_lists(d) && (d.coords || choose_patch_kernel(d) == PK_RAGGED)) {
     int32_t *lists = reinterpret_cast<int32_t *>(ws + w.lists_off);
     int32_t *counts = reinterpret_cast<int32_t *>(ws + w.counts_off);
     if (!reuse_lists) {

@@ -42,7 +42,7 @@ struct SweepParams {
   uint16_t *out;
   int64_t qsb, qsh, qst, osb, osh, ost;
   float c;              // scale * log2(e)
-  int grid_w, nbh, nbw;
+  int grid_h, grid_w, nbh, nbw;   // blocks per side: ceil(grid / 8)
   int heads;
   int strips;           // batch * heads * nbh
   int num_cus;
@@ -65,6 +65,7 @@ constexpr uint32_t kQ0Row = 3 * 16384 + 2048;  // q_0 likewise
 constexpr uint32_t kClsState = 3 * 16384 + 3072;   // per wave 512 B: o[64], m, l of the global query's partial
 constexpr uint32_t kClsLogit = 3 * 16384 + 3072 + 4 * 512;   // per wave 256 B: a tile's 64 logits
 constexpr float kEmptyMax = -1e30f;
+constexpr float kMasked = -1e30f;     // logit of a key that does not exist (edge blocks of a grid 8 does not divide)
 
 __device__ __forceinline__ float sswap_max(float x) {
   auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
@@ -94,7 +95,9 @@ __device__ __forceinline__ void swait_vm() {
 
 #define NS_U(x) __builtin_amdgcn_readfirstlane(x)
 
-// grid: one workgroup of 256 threads per strip (row of blocks of one image)
+// grid: one workgroup of 256 threads per strip (row of blocks of one image).  EDGE: the grid has
+// short blocks at its right or bottom edge (a side that 8 does not divide).
+template <bool EDGE>
 __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
   const int tid = threadIdx.x, wave = NS_U(tid >> 6), lane = tid & 63;
   const int l32 = lane & 31, hh = lane >> 5;
@@ -118,7 +121,21 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
   // token (grid row 8*Rb + i/8, grid column 8*Cb + i%8) is row i of the tile of block (Rb, Cb)
   auto block_token = [&](int Rb, int Cb) { return 1 + Rb * 8 * p.grid_w + Cb * 8; };
   auto block_base = [&](int Rb, int Cb) { return (uint32_t)block_token(Rb, Cb) * rowB; };
-  auto tile_off = [&](int i) { return (uint32_t)((i >> 3) * p.grid_w + (i & 7)) * rowB; };
+  // Blocks at the right and bottom edge of a grid that 8 does not divide are short.  Their tiles
+  // are filled up with copies of existing rows (the row and column index within the block are
+  // clamped): a copied QUERY computes what its original computes and is stored to the same place
+  // (same bits), a copied KEY gets the logit kMasked, i.e. the weight 0.
+  const int hv_last = EDGE ? p.grid_h - 8 * (p.nbh - 1) : 8, wv_last = EDGE ? p.grid_w - 8 * (p.nbw - 1) : 8;   // 1 .. 8
+  const int hvq = EDGE && R == p.nbh - 1 ? hv_last : 8;       // rows of this strip's query blocks
+  auto tile_off = [&](int i, int hv, int wv) {
+    return (uint32_t)(min(i >> 3, hv - 1) * p.grid_w + min(i & 7, wv - 1)) * rowB;
+  };
+  // logits of keys that do not exist: accumulator register e (key half mt) is key row 4*mt + e/4
+  // and column 4*hh + e%4 of a block with hv rows and wv columns
+  auto mask_keys = [&](f32x16 &sv, int mt, int hv, int wv) {
+#pragma unroll
+    for (int e = 0; e < 16; e++) sv[e] = (4 * mt + (e >> 2) >= hv || 4 * hh + (e & 3) >= wv) ? kMasked : sv[e];
+  };
 
   // ---- per-lane constants
   // transfers: request `it` of a tile is its rows 8*it .. 8*it+7 (one grid row of the block);
@@ -146,8 +163,8 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
       vrd[1][half] = kVOff + (off ^ 64);
     }
   }
-  const uint32_t qoff0 = tile_off(l32) + 64u * hh;
-  const uint32_t qoff1 = tile_off(l32 + 32) + 64u * hh;
+  const uint32_t qoff0 = tile_off(l32, hvq, 8) + 64u * hh;
+  const uint32_t qoff1 = tile_off(l32 + 32, hvq, 8) + 64u * hh;
 
   // ---- the key tiles of this strip, column by column
   const int r0 = max(R - 1, 0), r1 = min(R + 1, p.nbh - 1);
@@ -158,15 +175,19 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
   auto issue_next = [&]() {
     const uint32_t base = block_base(r0 + ir, ic);
     const uint32_t dst = lds_base + (uint32_t)islot * kSlot + (uint32_t)wave * 2048u;
+    const int hvk = EDGE && r0 + ir == p.nbh - 1 ? hv_last : 8;
+    // a short block's missing columns: the lanes of those columns fetch its last column instead
+    uint32_t back = 0;
+    if (EDGE && ic == ncols - 1 && wv_last < 8) back = (uint32_t)max(drow - (wv_last - 1), 0) * rowB;
 #pragma unroll
     for (int j = 0; j < 2; j++) {
-      const char *src = kb + base + (size_t)(2 * wave + j) * gridrowB;
-      sdma16(src, dma_koff[j], dst + j * 1024);
+      const char *src = kb + base + (size_t)min(2 * wave + j, hvk - 1) * gridrowB;
+      sdma16(src, dma_koff[j] - back, dst + j * 1024);
     }
 #pragma unroll
     for (int j = 0; j < 2; j++) {
-      const char *src = vb + base + (size_t)(2 * wave + j) * gridrowB;
-      sdma16(src, dma_voff, dst + kVOff + j * 1024);
+      const char *src = vb + base + (size_t)min(2 * wave + j, hvk - 1) * gridrowB;
+      sdma16(src, dma_voff - back, dst + kVOff + j * 1024);
     }
     islot = islot == kSlots - 1 ? 0 : islot + 1;
     const bool last = ic == ncols - 1 && ir == nr - 1;
@@ -215,10 +236,12 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
   // Q fragments of query block qc by ordinary loads
   auto load_block = [&](int qc) {
     const char *t = qb + block_base(R, qc);
+    uint32_t back = 0;                 // (l32 and l32 + 32 are in the same column of the block)
+    if (EDGE && qc == ncols - 1 && wv_last < 8) back = (uint32_t)max((l32 & 7) - (wv_last - 1), 0) * rowB;
 #pragma unroll
     for (int s = 0; s < 4; s++) {
-      qf[0][s] = *reinterpret_cast<const bf16x8 *>(t + qoff0 + 16 * s);
-      qf[1][s] = *reinterpret_cast<const bf16x8 *>(t + qoff1 + 16 * s);
+      qf[0][s] = *reinterpret_cast<const bf16x8 *>(t + (qoff0 - back) + 16 * s);
+      qf[1][s] = *reinterpret_cast<const bf16x8 *>(t + (qoff1 - back) + 16 * s);
     }
   };
   // The state the global token gives a query block: m = its logit (the fixed exponent reference),
@@ -280,7 +303,8 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
 #pragma unroll
     for (int nt = 0; nt < 2; nt++) {
       const int i = l32 + 32 * nt;
-      char *row = t + (size_t)((i >> 3) * p.grid_w + (i & 7)) * (size_t)(p.ost * 2) + 8 * hh;
+      const int wvq = EDGE && qc == ncols - 1 ? wv_last : 8;
+      char *row = t + (size_t)(min(i >> 3, hvq - 1) * p.grid_w + min(i & 7, wvq - 1)) * (size_t)(p.ost * 2) + 8 * hh;
 #pragma unroll
       for (int dt = 0; dt < 2; dt++)
 #pragma unroll
@@ -294,6 +318,7 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
   float *const cls_logit = reinterpret_cast<float *>(smem + kClsLogit + wave * 256);
   float *const logit_row = p.cls_logits ? p.cls_logits + ((size_t)b * p.heads + h) * p.tokens : nullptr;
   auto cls_duty = [&](uint32_t slot, int col, bool with_global_key) {
+    const int wvc = EDGE && col == ncols - 1 ? wv_last : 8;    // the tile is block (R, col): hvq rows, wvc columns
     // q_0 as B operand, the same in all 32 columns: channels 32*hh + 8*s + j
     bf16x8 q0f[4], kA[4], kB[4];
 #pragma unroll
@@ -308,6 +333,10 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
       sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kA[ks], q0f[ks], sa, 0, 0, 0);
       sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kB[ks], q0f[ks], sb, 0, 0, 0);
     }
+    if (EDGE && (hvq < 8 || wvc < 8)) {
+      mask_keys(sa, 0, hvq, wvc);
+      mask_keys(sb, 1, hvq, wvc);
+    }
     // register e of sa is key 8*(e/4) + 4*hh + e%4 of the tile (sb: + 32), whatever the column
     if (logit_row) {
       if (l32 == 0) {
@@ -319,9 +348,11 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
           *reinterpret_cast<f32x4 *>(cls_logit + 32 + 8 * g + 4 * hh) = vb2;
         }
       }
-      // lane = key of the tile: token (grid row 8R + lane/8, grid column 8*col + lane%8)
-      const float x = cls_logit[lane];
-      sstore4(logit_row + block_token(R, col) + (lane >> 3) * p.grid_w + (lane & 7), x);
+      // lane = key of the tile: token (grid row 8R + lane/8, grid column 8*col + lane%8); the lane of
+      // a key that does not exist repeats the store of the key it copies
+      const int kr = min(lane >> 3, hvq - 1), kc = min(lane & 7, wvc - 1);
+      const float x = cls_logit[8 * kr + kc];
+      sstore4(logit_row + block_token(R, col) + kr * p.grid_w + kc, x);
     }
     float mx = fmaxf(sa[0], sb[0]);
 #pragma unroll
@@ -453,13 +484,20 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
         kA[t] = *(lds_bf16x8_ptr)(smem + slot + krd[t]);
         kB[t] = *(lds_bf16x8_ptr)(smem + slot + 4096 + krd[t]);
       }
-      const f32x16 s00 = stage_a(kA, 0);
-      const f32x16 s01 = stage_a(kA, 1);
+      // (a short key block: its missing keys get the logit kMasked)
+      const int hvk = EDGE && r0 + ri == p.nbh - 1 ? hv_last : 8, wvk = EDGE && c == ncols - 1 ? wv_last : 8;
+      const bool edge = EDGE && (hvk < 8 || wvk < 8);
+      f32x16 s00 = stage_a(kA, 0);
+      if (edge) mask_keys(s00, 0, hvk, wvk);
+      f32x16 s01 = stage_a(kA, 1);
+      if (edge) mask_keys(s01, 0, hvk, wvk);
       stage_b(s00, 0, p0);
-      const f32x16 s10 = stage_a(kB, 0);
+      f32x16 s10 = stage_a(kB, 0);
+      if (edge) mask_keys(s10, 1, hvk, wvk);
       stage_b(s01, 1, p1);
       stage_c(0, 0, p0, slot);
-      const f32x16 s11 = stage_a(kB, 1);
+      f32x16 s11 = stage_a(kB, 1);
+      if (edge) mask_keys(s11, 1, hvk, wvk);
       stage_b(s10, 0, p2);
       stage_c(0, 1, p1, slot);
       stage_b(s11, 1, p3);
@@ -533,19 +571,25 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
     for (int cc = max(qr - 1, 0); cc <= min(qr + 1, ncols - 1); cc++)
       for (int rr = r0; rr <= r1; rr++) {
         const uint32_t base = block_base(rr, cc);
+        const int hvk = EDGE && rr == p.nbh - 1 ? hv_last : 8, wvk = EDGE && cc == ncols - 1 ? wv_last : 8;
         bf16x8 kt[2][4];
 #pragma unroll
         for (int mt = 0; mt < 2; mt++)
 #pragma unroll
           for (int t = 0; t < 4; t++)
-            kt[mt][t] = *reinterpret_cast<const bf16x8 *>(kb + base + mt * 4 * gridrowB + qoff0 + 16 * t);
+            kt[mt][t] = *reinterpret_cast<const bf16x8 *>(kb + base + tile_off(l32 + 32 * mt, hvk, wvk) + 64 * hh + 16 * t);
+        const uint32_t back = (uint32_t)max(drow - (wvk - 1), 0) * rowB;
 #pragma unroll
         for (int it = 0; it < 8; it++)
-          sdma16(vb + base + (size_t)it * gridrowB, dma_voff, lds_base + mine + kVOff + it * 1024);
+          sdma16(vb + base + (size_t)min(it, hvk - 1) * gridrowB, dma_voff - back, lds_base + mine + kVOff + it * 1024);
         swait_vm<0>();               // also the K fragments above
 #pragma unroll
         for (int nt = 0; nt < 2; nt++) {
-          const f32x16 s0 = stage_a(kt[0], nt), s1 = stage_a(kt[1], nt);
+          f32x16 s0 = stage_a(kt[0], nt), s1 = stage_a(kt[1], nt);
+          if (EDGE && (hvk < 8 || wvk < 8)) {
+            mask_keys(s0, 0, hvk, wvk);
+            mask_keys(s1, 1, hvk, wvk);
+          }
           float mx0 = fmaxf(s0[0], s0[1]), mx1 = fmaxf(s1[0], s1[1]);
 #pragma unroll
           for (int e = 2; e < 16; e += 2) {
@@ -588,7 +632,11 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
 }  // namespace
 
 bool sweep_attn_supported(const ns_attn_desc &d) {
-  return mfma_attn_supported(d) && d.block == 8 && d.grid_w / 8 <= 128;
+  return d.dtype == NS_BF16 && d.head_dim == 64 && d.radius == 1 && d.n_global == 1 && d.coords == nullptr &&
+         d.block == 8 && (d.grid_w + 7) / 8 <= 128 && d.scale > 0.f &&
+         // tokens are addressed with 32-bit byte offsets from the (batch, head) base
+         (long long)d.tokens * d.q_stride_t * 2 < 0x7fffffffLL &&
+         (long long)d.tokens * d.out_stride_t * 2 < 0x7fffffffLL;
 }
 
 ns_status launch_attn_sweep(const AttnArgs &a, float *cls_logits, float *cls_partials) {
@@ -601,9 +649,10 @@ ns_status launch_attn_sweep(const AttnArgs &a, float *cls_logits, float *cls_par
   p.qsb = d.q_stride_b; p.qsh = d.q_stride_h; p.qst = d.q_stride_t;
   p.osb = d.out_stride_b; p.osh = d.out_stride_h; p.ost = d.out_stride_t;
   p.c = d.scale * kLog2e;
+  p.grid_h = d.grid_h;
   p.grid_w = d.grid_w;
-  p.nbh = d.grid_h / 8;
-  p.nbw = d.grid_w / 8;
+  p.nbh = (d.grid_h + 7) / 8;
+  p.nbw = (d.grid_w + 7) / 8;
   p.heads = d.heads;
   p.tokens = d.tokens;
   p.scale = d.scale;
@@ -627,12 +676,17 @@ ns_status launch_attn_sweep(const AttnArgs &a, float *cls_logits, float *cls_par
   static bool attr_set = false;
   const int lds = 4 * 16384;        // three ring slots and the global token's rows; the redo gives each wave a slot
   if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(attn_sweep_kernel),
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(attn_sweep_kernel<false>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess ||
+        hipFuncSetAttribute(reinterpret_cast<const void *>(attn_sweep_kernel<true>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
       return fail(NS_ERR_HIP, "cannot reserve %d bytes of LDS", lds);
     attr_set = true;
   }
-  hipLaunchKernelGGL(attn_sweep_kernel, dim3((unsigned)strips), dim3(256), lds, a.stream, p);
+  if (d.grid_h % 8 == 0 && d.grid_w % 8 == 0)
+    hipLaunchKernelGGL(attn_sweep_kernel<false>, dim3((unsigned)strips), dim3(256), lds, a.stream, p);
+  else
+    hipLaunchKernelGGL(attn_sweep_kernel<true>, dim3((unsigned)strips), dim3(256), lds, a.stream, p);
   return check_launch("attn_sweep_kernel");
 }
 

@@ -108,7 +108,7 @@ bool sweep_attn_supported(const ns_attn_desc &d);    // 8x8 blocks: key tiles sh
 // cls_partials != NULL: the kernel also computes the global query's row, [B,H,4*nbh,66] partial records
 // (sweep_cls_chunks of them per head-image) and, with cls_logits, its raw logits [B,H,T]
 ns_status launch_attn_sweep(const AttnArgs &a, float *cls_logits, float *cls_partials);
-inline int sweep_cls_chunks(const ns_attn_desc &d) { return 4 * (d.grid_h / 8); }
+inline int sweep_cls_chunks(const ns_attn_desc &d) { return 4 * ((d.grid_h + 7) / 8); }
 bool block16_attn_supported(const ns_attn_desc &d);  // 16x16 blocks: key tiles shared by a block's four query tiles
 ns_status launch_attn_block16(const AttnArgs &a);
 bool ragged_attn_supported(const ns_attn_desc &d);   // bf16, head_dim 64: anything given per-block token lists

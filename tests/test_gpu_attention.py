@@ -167,6 +167,29 @@ def test_cls_by_products_and_determinism(nb, monkeypatch, variant, gh, gw):
     np.testing.assert_allclose(to_np(lse), ref_lse, rtol=0, atol=2e-5)
 
 
+@pytest.mark.parametrize("gh,gw,gain", [(20, 27, 1.0), (9, 9, 1.0), (8, 100, 1.0), (17, 8, 1.0), (1, 1, 1.0), (5, 5, 1.0),
+                                        (43, 60, 1.0), (12, 30, 14.0), (63, 65, 1.0)])
+def test_sweep_on_grids_8_does_not_divide(nb, monkeypatch, gh, gw, gain):
+    """The sweep kernel with short blocks at the right and bottom edge: patch rows, the global
+    query's row and its by-products; gain 14 makes weights overflow the fixed exponent reference,
+    so edge blocks also go through the running-maximum path."""
+    monkeypatch.setenv("NSATTN_KERNEL", "sweep")
+    q, k, v = synth.small_case(66, 2, 3, 64, gh, gw, "bf16")
+    q = synth.round_to_bf16(q * gain)
+    dq, dk, dv = (to_dev(a, "bf16") for a in (q, k, v))
+    assert nb.ns_attn_patch_kernel_name(dq, gh, gw, 8) == "attn_sweep_kernel"
+    out, logits, lse = nb.ns_attn_forward(dq, dk, dv, gh, gw, 8, 0.125, want_cls=True)
+    out2 = nb.ns_attn_forward(dq, dk, dv, gh, gw, 8, 0.125)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+    assert np.isfinite(to_np(out)).all()
+    ref = oracle.ns_attn(q, k, v, gh, gw, 8, 0.125)
+    assert_attn_close(to_np(out), ref, "bf16", "sweep on %dx%d" % (gh, gw))
+    _, ref_logits, ref_lse = oracle.cls_scores(q, k, 0.125, want_logits=True)
+    np.testing.assert_allclose(to_np(logits), ref_logits, rtol=0, atol=2e-5 * gain)
+    np.testing.assert_allclose(to_np(lse), ref_lse, rtol=0, atol=2e-5 * gain)
+
+
 def test_invalid_call_launches_nothing(nb):
     q = torch.zeros((1, 1, 65, 64), dtype=torch.bfloat16, device="cuda")
     out = torch.full_like(q, 7.0)
