@@ -160,12 +160,13 @@ static PatchKernel choose_patch_kernel(const ns_attn_desc &d) {
   if (force == 'g') return PK_GENERIC;        // serves every problem
   const bool tiled_ok = mfma_attn_supported(d);               // block side 8 or 16 dividing the grid
   const bool sweep_ok = sweep_attn_supported(d);              // block side 8, any grid
+  const bool block16_ok = block16_attn_supported(d);          // block side 16, any grid
   const long long strips = (long long)d.batch * d.heads * ((d.grid_h + d.block - 1) / d.block);
+  const long long blocks = strips * ((d.grid_w + d.block - 1) / d.block);
   if (force == 's' && sweep_ok) return PK_SWEEP;
+  if (force == 'b' && block16_ok) return PK_BLOCK16;
   if (tiled_ok) {
-    const bool persist_ok = persist_attn_supported(d), block16_ok = block16_attn_supported(d);
-    const long long blocks = strips * (d.grid_w / d.block);
-    if (force == 'b' && block16_ok) return PK_BLOCK16;
+    const bool persist_ok = persist_attn_supported(d);
     if (force == 'p' && persist_ok) return PK_PERSIST;
     if (force == 'm') return PK_MFMA;
     if (sweep_ok && strips >= device_cus()) return PK_SWEEP;
@@ -173,7 +174,9 @@ static PatchKernel choose_patch_kernel(const ns_attn_desc &d) {
     if (persist_ok) return PK_PERSIST;
     return PK_MFMA;
   }
-  if (sweep_ok && force != 'l' && strips >= device_cus()) return PK_SWEEP;   // short edge blocks
+  // short edge blocks: the sweep and the block kernel take them, the other two do not
+  if (force != 'l' && sweep_ok && strips >= device_cus()) return PK_SWEEP;
+  if (force != 'l' && block16_ok && blocks >= 2LL * device_cus()) return PK_BLOCK16;
   if (ragged_attn_supported(d)) return PK_RAGGED;   // its lists: wants_lists()
   return PK_GENERIC;
 }

@@ -20,7 +20,7 @@ struct BlockParams {
   uint16_t *out;
   int64_t qsb, qsh, qst, osb, osh, ost;
   float c;              // scale * log2(e)
-  int grid_w, nbh, nbw;
+  int grid_h, grid_w, nbh, nbw;   // blocks per side: ceil(grid / 16)
   int heads;
   int blocks;           // batch * heads * nbh * nbw
 };
@@ -63,7 +63,11 @@ __device__ __forceinline__ void bwait_vm() {
 
 #define NS_U(x) __builtin_amdgcn_readfirstlane(x)
 
-// grid: one workgroup of 256 threads per query block
+constexpr float kMasked = -1e30f;     // logit of a key that does not exist (edge blocks of a grid 16 does not divide)
+
+// grid: one workgroup of 256 threads per query block.  EDGE: the grid has short blocks at its
+// right or bottom edge (a side that 16 does not divide).
+template <bool EDGE>
 __global__ __launch_bounds__(256, 2) void attn_block16_kernel(BlockParams p) {
   const int tid = threadIdx.x, wave = NS_U(tid >> 6), lane = tid & 63;
   const int l32 = lane & 31, hh = lane >> 5;
@@ -89,7 +93,24 @@ __global__ __launch_bounds__(256, 2) void attn_block16_kernel(BlockParams p) {
   // tile `sub` of block (Rb, Cb) is grid rows 16*Rb + 4*sub .. +3, columns 16*Cb .. +15; its row i
   // is the token at grid row offset i/16, column offset i%16
   auto tile_token = [&](int Rb, int Cb, int sub) { return 1 + (Rb * 16 + sub * 4) * p.grid_w + Cb * 16; };
-  auto tile_off = [&](int i) { return (uint32_t)((i >> 4) * p.grid_w + (i & 15)) * rowB; };
+  // Short edge blocks: a tile is filled up with copies of existing tokens (row and column index
+  // within the block are clamped).  A copied QUERY computes what its original computes and is
+  // stored to the same place (same bits); a copied KEY gets the logit kMasked, i.e. the weight 0.
+  const int hv_last = EDGE ? p.grid_h - 16 * (p.nbh - 1) : 16, wv_last = EDGE ? p.grid_w - 16 * (p.nbw - 1) : 16;
+  auto rows_of = [&](int Rb) { return EDGE && Rb == p.nbh - 1 ? hv_last : 16; };
+  auto cols_of = [&](int Cb) { return EDGE && Cb == p.nbw - 1 ? wv_last : 16; };
+  // offset of row i of tile `sub` of a block with hv rows and wv columns, from the tile's first token
+  auto tile_off = [&](int i, int sub, int hv, int wv) {
+    const int r = min(4 * sub + (i >> 4), hv - 1) - 4 * sub;      // may be negative: a tile without rows of its own
+    return (uint32_t)(r * p.grid_w + min(i & 15, wv - 1)) * rowB;
+  };
+  // logits of keys that do not exist: accumulator register e (key half mt) of tile `sub` is block
+  // row 4*sub + 2*mt + e/8 and column 8*((e/4)%2) + 4*hh + e%4
+  auto mask_keys = [&](f32x16 &sv, int mt, int sub, int hv, int wv) {
+#pragma unroll
+    for (int e = 0; e < 16; e++)
+      sv[e] = (4 * sub + 2 * mt + (e >> 3) >= hv || 8 * ((e >> 2) & 1) + 4 * hh + (e & 3) >= wv) ? kMasked : sv[e];
+  };
 
   // ---- per-lane constants
   // transfers: request `it` of a tile is its rows 8*it .. 8*it+7 (half a grid row); LDS slot `lane`
@@ -115,8 +136,8 @@ __global__ __launch_bounds__(256, 2) void attn_block16_kernel(BlockParams p) {
       vrd[1][half] = kVOff + (off ^ 64);
     }
   }
-  const uint32_t qoff0 = tile_off(l32) + 64u * hh;
-  const uint32_t qoff1 = tile_off(l32 + 32) + 64u * hh;
+  const uint32_t qoff0 = tile_off(l32, wave, rows_of(R), cols_of(C)) + 64u * hh;
+  const uint32_t qoff1 = tile_off(l32 + 32, wave, rows_of(R), cols_of(C)) + 64u * hh;
 
   // ---- the key tiles of the (clipped) 3x3 block neighbourhood, block by block, four tiles each
   const int R0 = max(R - 1, 0), R1 = min(R + 1, p.nbh - 1);
@@ -124,12 +145,25 @@ __global__ __launch_bounds__(256, 2) void attn_block16_kernel(BlockParams p) {
   const int ncb = C1 - C0 + 1, steps = (R1 - R0 + 1) * ncb * 4;
   int ir = R0, ic = C0, isub = 0, islot = 0;   // the tile to request next and its ring slot
   auto issue_next = [&]() {                    // this wave's share (4 requests); past the last tile it repeats that one
-    const uint32_t base = (uint32_t)tile_token(ir, ic, isub) * rowB + (uint32_t)wave * gridrowB;
+    // grid row `wave` of the tile (clamped to the block's last row), columns 8*j + lane/8 (clamped)
+    const int grow = EDGE ? min(4 * isub + wave, rows_of(ir) - 1) : 4 * isub + wave;
+    const uint32_t base = (uint32_t)tile_token(ir, ic, 0) * rowB + (uint32_t)grow * gridrowB;
     const uint32_t dst = lds_base + (uint32_t)islot * kSlot + (uint32_t)wave * 2048u;
+    if (EDGE && ic == p.nbw - 1 && wv_last < 16) {
+      // The lane offset of a transfer is unsigned, so the whole (clamped) column goes into it:
+      // column min(8*j + lane/8, wv_last - 1) instead of 8*j in the base and lane/8 in the offset.
 #pragma unroll
-    for (int j = 0; j < 2; j++) bdma16(kb + base + (size_t)j * 8 * rowB, dma_koff[j], dst + j * 1024);
+      for (int j = 0; j < 2; j++) {
+        const uint32_t shift = (uint32_t)(min(8 * j + drow, wv_last - 1) - drow) * rowB;   // sum below is >= 0
+        bdma16(kb + base, dma_koff[j] + shift, dst + j * 1024);
+        bdma16(vb + base, dma_voff + shift, dst + kVOff + j * 1024);
+      }
+    } else {
 #pragma unroll
-    for (int j = 0; j < 2; j++) bdma16(vb + base + (size_t)j * 8 * rowB, dma_voff, dst + kVOff + j * 1024);
+      for (int j = 0; j < 2; j++) bdma16(kb + base + (size_t)j * 8 * rowB, dma_koff[j], dst + j * 1024);
+#pragma unroll
+      for (int j = 0; j < 2; j++) bdma16(vb + base + (size_t)j * 8 * rowB, dma_voff, dst + kVOff + j * 1024);
+    }
     islot = islot == kSlots - 1 ? 0 : islot + 1;
     const bool last = ir == R1 && ic == C1 && isub == 3;
     const bool next_block = isub == 3, next_row = next_block && ic == C1;
@@ -179,8 +213,8 @@ __global__ __launch_bounds__(256, 2) void attn_block16_kernel(BlockParams p) {
   auto load_tile = [&]() {
 #pragma unroll
     for (int s = 0; s < 4; s++) {
-      qf[0][s] = *reinterpret_cast<const bf16x8 *>(qtile + qoff0 + 16 * s);
-      qf[1][s] = *reinterpret_cast<const bf16x8 *>(qtile + qoff1 + 16 * s);
+      qf[0][s] = *reinterpret_cast<const bf16x8 *>(qtile + (int32_t)qoff0 + 16 * s);
+      qf[1][s] = *reinterpret_cast<const bf16x8 *>(qtile + (int32_t)qoff1 + 16 * s);
     }
   };
   // The state the global token gives a query tile: m = its logit (the fixed exponent reference),
@@ -227,7 +261,8 @@ __global__ __launch_bounds__(256, 2) void attn_block16_kernel(BlockParams p) {
     for (int nt = 0; nt < 2; nt++) {
       const float inv = 1.f / bswap_sum(l[nt]);
       const int i = l32 + 32 * nt;
-      char *row = t + (size_t)((i >> 4) * p.grid_w + (i & 15)) * (size_t)(p.ost * 2) + 8 * hh;
+      const int r = min(4 * wave + (i >> 4), rows_of(R) - 1) - 4 * wave;   // as in tile_off
+      char *row = t + (ptrdiff_t)(r * p.grid_w + min(i & 15, cols_of(C) - 1)) * (ptrdiff_t)(p.ost * 2) + 8 * hh;
 #pragma unroll
       for (int dt = 0; dt < 2; dt++)
 #pragma unroll
@@ -254,8 +289,11 @@ __global__ __launch_bounds__(256, 2) void attn_block16_kernel(BlockParams p) {
   init_tile();
 
   int cslot = 0;
+  int cr = R0, cc = C0, csub = 0;      // the key tile in work
   for (int s = 0; s < steps; s++) {
     const uint32_t slot = (uint32_t)cslot * kSlot;
+    const int hvk = rows_of(cr), wvk = cols_of(cc);
+    const bool edge = EDGE && (hvk < 4 * csub + 4 || wvk < 16);
     {
       bf16x8 kA[4], kB[4], p0[2], p1[2], p2[2], p3[2];
 #pragma unroll
@@ -263,13 +301,17 @@ __global__ __launch_bounds__(256, 2) void attn_block16_kernel(BlockParams p) {
         kA[t] = *(lds_bf16x8_ptr)(smem + slot + krd[t]);
         kB[t] = *(lds_bf16x8_ptr)(smem + slot + 4096 + krd[t]);
       }
-      const f32x16 s00 = stage_a(kA, 0);
-      const f32x16 s01 = stage_a(kA, 1);
+      f32x16 s00 = stage_a(kA, 0);
+      if (edge) mask_keys(s00, 0, csub, hvk, wvk);
+      f32x16 s01 = stage_a(kA, 1);
+      if (edge) mask_keys(s01, 0, csub, hvk, wvk);
       stage_b(s00, 0, p0);
-      const f32x16 s10 = stage_a(kB, 0);
+      f32x16 s10 = stage_a(kB, 0);
+      if (edge) mask_keys(s10, 1, csub, hvk, wvk);
       stage_b(s01, 1, p1);
       stage_c(0, 0, p0, slot);
-      const f32x16 s11 = stage_a(kB, 1);
+      f32x16 s11 = stage_a(kB, 1);
+      if (edge) mask_keys(s11, 1, csub, hvk, wvk);
       stage_b(s10, 0, p2);
       stage_c(0, 1, p1, slot);
       stage_b(s11, 1, p3);
@@ -280,6 +322,12 @@ __global__ __launch_bounds__(256, 2) void attn_block16_kernel(BlockParams p) {
     __syncthreads();   // ... and everybody's; and everybody is done with tile s, whose slot tile s+3 takes
     issue_next();
     cslot = cslot == kSlots - 1 ? 0 : cslot + 1;
+    if (EDGE) {        // the same order as the requests
+      const bool nb2 = csub == 3, nr2 = nb2 && cc == C1;
+      csub = nb2 ? 0 : csub + 1;
+      cc = nr2 ? C0 : (nb2 ? cc + 1 : cc);
+      cr = nr2 ? cr + 1 : cr;
+    }
   }
   bwait_vm<0>();
   const bool bad = finish_tile();
@@ -292,23 +340,33 @@ __global__ __launch_bounds__(256, 2) void attn_block16_kernel(BlockParams p) {
   load_tile();
   init_tile();
   for (int rr = R0; rr <= R1; rr++)
-    for (int cc = C0; cc <= C1; cc++)
+    for (int cc2 = C0; cc2 <= C1; cc2++)
       for (int sub = 0; sub < 4; sub++) {
-        const uint32_t base = (uint32_t)tile_token(rr, cc, sub) * rowB;
+        const int cc = cc2;
+        const char *kbase = kb + (uint32_t)tile_token(rr, cc, sub) * rowB;
+        const uint32_t vblock = (uint32_t)tile_token(rr, cc, 0) * rowB;
+        const int hvk = rows_of(rr), wvk = cols_of(cc);
         bf16x8 kt[2][4];
 #pragma unroll
         for (int mt = 0; mt < 2; mt++)
 #pragma unroll
           for (int t = 0; t < 4; t++)
-            kt[mt][t] = *reinterpret_cast<const bf16x8 *>(kb + base + mt * 2 * gridrowB + qoff0 + 16 * t);
+            kt[mt][t] = *reinterpret_cast<const bf16x8 *>(kbase + (int32_t)tile_off(l32 + 32 * mt, sub, hvk, wvk) + 64 * hh + 16 * t);
 #pragma unroll
-        for (int it = 0; it < 8; it++)
-          bdma16(vb + base + (size_t)(it >> 1) * gridrowB + (size_t)(it & 1) * 8 * rowB, dma_voff,
-                 lds_base + mine + kVOff + it * 1024);
+        for (int it = 0; it < 8; it++) {
+          const int grow = min(4 * sub + (it >> 1), hvk - 1);
+          // (unsigned lane offset: the clamped column goes into it whole, see issue_next)
+          const uint32_t shift = (uint32_t)(min(8 * (it & 1) + drow, wvk - 1) - drow) * rowB;
+          bdma16(vb + vblock + (size_t)grow * gridrowB, dma_voff + shift, lds_base + mine + kVOff + it * 1024);
+        }
         bwait_vm<0>();               // also the K fragments above
 #pragma unroll
         for (int nt = 0; nt < 2; nt++) {
-          const f32x16 s0 = stage_a(kt[0], nt), s1 = stage_a(kt[1], nt);
+          f32x16 s0 = stage_a(kt[0], nt), s1 = stage_a(kt[1], nt);
+          if (EDGE && (hvk < 4 * sub + 4 || wvk < 16)) {
+            mask_keys(s0, 0, sub, hvk, wvk);
+            mask_keys(s1, 1, sub, hvk, wvk);
+          }
           float mx0 = fmaxf(s0[0], s0[1]), mx1 = fmaxf(s1[0], s1[1]);
 #pragma unroll
           for (int e = 2; e < 16; e += 2) {
@@ -347,7 +405,11 @@ __global__ __launch_bounds__(256, 2) void attn_block16_kernel(BlockParams p) {
 }  // namespace
 
 bool block16_attn_supported(const ns_attn_desc &d) {
-  return mfma_attn_supported(d) && d.block == 16;
+  return d.dtype == NS_BF16 && d.head_dim == 64 && d.radius == 1 && d.n_global == 1 && d.coords == nullptr &&
+         d.block == 16 && d.scale > 0.f &&
+         // tokens are addressed with 32-bit byte offsets from the (batch, head) base
+         (long long)d.tokens * d.q_stride_t * 2 < 0x7fffffffLL &&
+         (long long)d.tokens * d.out_stride_t * 2 < 0x7fffffffLL;
 }
 
 ns_status launch_attn_block16(const AttnArgs &a) {
@@ -360,9 +422,10 @@ ns_status launch_attn_block16(const AttnArgs &a) {
   p.qsb = d.q_stride_b; p.qsh = d.q_stride_h; p.qst = d.q_stride_t;
   p.osb = d.out_stride_b; p.osh = d.out_stride_h; p.ost = d.out_stride_t;
   p.c = d.scale * kLog2e;
+  p.grid_h = d.grid_h;
   p.grid_w = d.grid_w;
-  p.nbh = d.grid_h / 16;
-  p.nbw = d.grid_w / 16;
+  p.nbh = (d.grid_h + 15) / 16;
+  p.nbw = (d.grid_w + 15) / 16;
   p.heads = d.heads;
   const long long blocks = (long long)d.batch * d.heads * p.nbh * p.nbw;
   if (blocks > 0x7fffffffLL) return fail(NS_ERR_UNSUPPORTED, "launch grid too large");
@@ -370,12 +433,17 @@ ns_status launch_attn_block16(const AttnArgs &a) {
   static bool attr_set = false;
   const int lds = 4 * 16384;        // three ring slots and the global token's rows; the redo gives each wave a slot
   if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(attn_block16_kernel),
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(attn_block16_kernel<false>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess ||
+        hipFuncSetAttribute(reinterpret_cast<const void *>(attn_block16_kernel<true>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
       return fail(NS_ERR_HIP, "cannot reserve %d bytes of LDS", lds);
     attr_set = true;
   }
-  hipLaunchKernelGGL(attn_block16_kernel, dim3((unsigned)blocks), dim3(256), lds, a.stream, p);
+  if (d.grid_h % 16 == 0 && d.grid_w % 16 == 0)
+    hipLaunchKernelGGL(attn_block16_kernel<false>, dim3((unsigned)blocks), dim3(256), lds, a.stream, p);
+  else
+    hipLaunchKernelGGL(attn_block16_kernel<true>, dim3((unsigned)blocks), dim3(256), lds, a.stream, p);
   return check_launch("attn_block16_kernel");
 }
 

@@ -190,6 +190,26 @@ def test_sweep_on_grids_8_does_not_divide(nb, monkeypatch, gh, gw, gain):
     np.testing.assert_allclose(to_np(lse), ref_lse, rtol=0, atol=2e-5 * gain)
 
 
+@pytest.mark.parametrize("gh,gw,gain", [(20, 27, 1.0), (37, 21, 1.0), (16, 50, 1.0), (33, 16, 1.0), (1, 1, 1.0), (5, 70, 1.0),
+                                        (45, 60, 1.0), (19, 30, 14.0), (3, 3, 1.0)])
+def test_block_kernel_on_grids_16_does_not_divide(nb, monkeypatch, gh, gw, gain):
+    """The kernel for 16x16 blocks with short blocks at the right and bottom edge (query tiles
+    with few or no rows of their own, key tiles partly or wholly made of copies); gain 14 sends
+    edge tiles through the running-maximum path as well."""
+    monkeypatch.setenv("NSATTN_KERNEL", "block")
+    q, k, v = synth.small_case(67, 2, 3, 64, gh, gw, "bf16")
+    q = synth.round_to_bf16(q * gain)
+    dq, dk, dv = (to_dev(a, "bf16") for a in (q, k, v))
+    assert nb.ns_attn_patch_kernel_name(dq, gh, gw, 16) == "attn_block16_kernel"
+    out = nb.ns_attn_forward(dq, dk, dv, gh, gw, 16, 0.125)
+    out2 = nb.ns_attn_forward(dq, dk, dv, gh, gw, 16, 0.125)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+    assert np.isfinite(to_np(out)).all()
+    ref = oracle.ns_attn(q, k, v, gh, gw, 16, 0.125)
+    assert_attn_close(to_np(out), ref, "bf16", "block kernel on %dx%d" % (gh, gw))
+
+
 def test_invalid_call_launches_nothing(nb):
     q = torch.zeros((1, 1, 65, 64), dtype=torch.bfloat16, device="cuda")
     out = torch.full_like(q, 7.0)
