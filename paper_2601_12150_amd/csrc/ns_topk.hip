@@ -176,8 +176,19 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_reg_kernel(const floa
   for (int bit = 31; bit >= 0; bit--) {
     const uint32_t cand = tau | (1u << bit);
     uint32_t c = 0;   // wave-uniform: lives in a scalar register
+    if (KPT <= 16) {
 #pragma unroll
-    for (int i = 0; i < KPT; i++) c += (uint32_t)__popcll(__ballot(key[i] >= cand));   // padding keys are 0 < cand
+      for (int i = 0; i < KPT; i++) c += (uint32_t)__popcll(__ballot(key[i] >= cand));   // padding keys are 0 < cand
+    } else {
+      // many keys per lane: count per lane on the vector ALU (compare + add with carry), one
+      // reduction over the lanes per bit; the scalar unit, one per CU, is the bottleneck otherwise
+      uint32_t cl = 0;
+#pragma unroll
+      for (int i = 0; i < KPT; i++) cl += key[i] >= cand ? 1u : 0u;
+#pragma unroll
+      for (int sft = 1; sft < 64; sft <<= 1) cl += (uint32_t)__shfl_xor((int)cl, sft);
+      c = (uint32_t)__builtin_amdgcn_readfirstlane((int)cl);
+    }
     const uint32_t tot = block_total(c, slot);
     slot ^= 1;
     if (tot >= (uint32_t)k) tau = cand;
