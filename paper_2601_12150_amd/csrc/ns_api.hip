@@ -159,23 +159,24 @@ static PatchKernel choose_patch_kernel(const ns_attn_desc &d) {
   const char force = e ? e[0] : 0;
   if (force == 'g') return PK_GENERIC;        // serves every problem
   const bool tiled_ok = mfma_attn_supported(d);               // block side 8 or 16 dividing the grid
-  const bool sweep_ok = sweep_attn_supported(d);              // block side 8, any grid
+  const bool sweep_ok = sweep_attn_supported(d);              // block side 8, 4 or 2, any grid
   const bool block16_ok = block16_attn_supported(d);          // block side 16, any grid
   const long long strips = (long long)d.batch * d.heads * ((d.grid_h + d.block - 1) / d.block);
   const long long blocks = strips * ((d.grid_w + d.block - 1) / d.block);
+  const long long strips8 = (long long)d.batch * d.heads * ((d.grid_h + 7) / 8);   // the sweep's workgroups
   if (force == 's' && sweep_ok) return PK_SWEEP;
   if (force == 'b' && block16_ok) return PK_BLOCK16;
   if (tiled_ok) {
     const bool persist_ok = persist_attn_supported(d);
     if (force == 'p' && persist_ok) return PK_PERSIST;
     if (force == 'm') return PK_MFMA;
-    if (sweep_ok && strips >= device_cus()) return PK_SWEEP;
+    if (sweep_ok && strips8 >= device_cus()) return PK_SWEEP;
     if (block16_ok && blocks >= 2LL * device_cus()) return PK_BLOCK16;
     if (persist_ok) return PK_PERSIST;
     return PK_MFMA;
   }
-  // short edge blocks: the sweep and the block kernel take them, the other two do not
-  if (force != 'l' && sweep_ok && strips >= device_cus()) return PK_SWEEP;
+  // short edge blocks, 4x4 and 2x2 blocks: the sweep (and, for the former, the block kernel) takes them
+  if (force != 'l' && sweep_ok && strips8 >= device_cus()) return PK_SWEEP;
   if (force != 'l' && block16_ok && blocks >= 2LL * device_cus()) return PK_BLOCK16;
   if (ragged_attn_supported(d)) return PK_RAGGED;   // its lists: wants_lists()
   return PK_GENERIC;

@@ -1,5 +1,5 @@
-// bf16 MFMA neighbourhood attention for 8x8 blocks: a workgroup sweeps a row of query blocks and
-// shares every key tile among the query blocks that need it (gfx950).
+// bf16 MFMA neighbourhood attention for 8x8 blocks (and 4x4, 2x2 blocks on 8x8 tiles): a workgroup
+// sweeps a row of query blocks and shares every key tile among the query blocks that need it (gfx950).
 //
 // Why.  With one wave per query block and private key tiles, every K and V tile is fetched from
 // L2 nine times (once per query block of its neighbourhood); measured, that L2 -> LDS traffic
@@ -95,9 +95,13 @@ __device__ __forceinline__ void swait_vm() {
 
 #define NS_U(x) __builtin_amdgcn_readfirstlane(x)
 
-// grid: one workgroup of 256 threads per strip (row of blocks of one image).  EDGE: the grid has
-// short blocks at its right or bottom edge (a side that 8 does not divide).
-template <bool EDGE>
+// grid: one workgroup of 256 threads per strip (row of 8x8 tiles of one image).  EDGE: the grid
+// has short tiles at its right or bottom edge (a side that 8 does not divide).  W: side of the
+// token blocks that define the neighbourhood, a divisor of 8.  For W < 8 the 8x8 tiles stay the
+// unit of work (a query tile still meets the 3x3 tiles around it, which contain the 3x3 blocks
+// around each of its tokens), and every logit of a (query, key) pair whose blocks are not
+// neighbours is masked.
+template <bool EDGE, int W>
 __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
   const int tid = threadIdx.x, wave = NS_U(tid >> 6), lane = tid & 63;
   const int l32 = lane & 31, hh = lane >> 5;
@@ -135,6 +139,21 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
   auto mask_keys = [&](f32x16 &sv, int mt, int hv, int wv) {
 #pragma unroll
     for (int e = 0; e < 16; e++) sv[e] = (4 * mt + (e >> 2) >= hv || 4 * hh + (e & 3) >= wv) ? kMasked : sv[e];
+  };
+  // W < 8: logits of pairs whose WxW blocks are not neighbours.  The key tile lies (dr, dc) tiles
+  // from the query tile; lane = query (tile row l32/8 + 4*nt, column l32%8), register e = key (tile
+  // row 4*mt + e/4, column 4*hh + e%4); block indices relative to the query tile's first block.
+  // (a copied query of a short tile sits where its original sits: wvq = columns of the query tile)
+  auto mask_window = [&](f32x16 &sv, int mt, int nt, int dr, int dc, int wvq) {
+    constexpr int n = 8 / W;
+    const int rq = EDGE ? min((l32 >> 3) + 4 * nt, hvq - 1) : (l32 >> 3) + 4 * nt;
+    const int cq = EDGE ? min(l32 & 7, wvq - 1) : (l32 & 7);
+    const int ra = rq / W - n * dr + 1, ca = cq / W - n * dc + 1;
+#pragma unroll
+    for (int e = 0; e < 16; e++) {
+      const bool ok = (unsigned)(ra - (4 * mt + (e >> 2)) / W) <= 2u && (unsigned)(ca - (4 * hh + (e & 3)) / W) <= 2u;
+      sv[e] = ok ? sv[e] : kMasked;
+    }
   };
 
   // ---- per-lane constants
@@ -487,17 +506,23 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
       // (a short key block: its missing keys get the logit kMasked)
       const int hvk = EDGE && r0 + ri == p.nbh - 1 ? hv_last : 8, wvk = EDGE && c == ncols - 1 ? wv_last : 8;
       const bool edge = EDGE && (hvk < 8 || wvk < 8);
+      const int dr = r0 + ri - R, dc = c - qc;
+      const int wvq = EDGE && qc == ncols - 1 ? wv_last : 8;
       f32x16 s00 = stage_a(kA, 0);
       if (edge) mask_keys(s00, 0, hvk, wvk);
+      if (W < 8) mask_window(s00, 0, 0, dr, dc, wvq);
       f32x16 s01 = stage_a(kA, 1);
       if (edge) mask_keys(s01, 0, hvk, wvk);
+      if (W < 8) mask_window(s01, 0, 1, dr, dc, wvq);
       stage_b(s00, 0, p0);
       f32x16 s10 = stage_a(kB, 0);
       if (edge) mask_keys(s10, 1, hvk, wvk);
+      if (W < 8) mask_window(s10, 1, 0, dr, dc, wvq);
       stage_b(s01, 1, p1);
       stage_c(0, 0, p0, slot);
       f32x16 s11 = stage_a(kB, 1);
       if (edge) mask_keys(s11, 1, hvk, wvk);
+      if (W < 8) mask_window(s11, 1, 1, dr, dc, wvq);
       stage_b(s10, 0, p2);
       stage_c(0, 1, p1, slot);
       stage_b(s11, 1, p3);
@@ -590,6 +615,11 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
             mask_keys(s0, 0, hvk, wvk);
             mask_keys(s1, 1, hvk, wvk);
           }
+          if (W < 8) {
+            const int wvq = EDGE && qr == ncols - 1 ? wv_last : 8;
+            mask_window(s0, 0, nt, rr - R, cc - qr, wvq);
+            mask_window(s1, 1, nt, rr - R, cc - qr, wvq);
+          }
           float mx0 = fmaxf(s0[0], s0[1]), mx1 = fmaxf(s1[0], s1[1]);
 #pragma unroll
           for (int e = 2; e < 16; e += 2) {
@@ -633,7 +663,7 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
 
 bool sweep_attn_supported(const ns_attn_desc &d) {
   return d.dtype == NS_BF16 && d.head_dim == 64 && d.radius == 1 && d.n_global == 1 && d.coords == nullptr &&
-         d.block == 8 && (d.grid_w + 7) / 8 <= 128 && d.scale > 0.f &&
+         (d.block == 8 || d.block == 4 || d.block == 2) && (d.grid_w + 7) / 8 <= 128 && d.scale > 0.f &&
          // tokens are addressed with 32-bit byte offsets from the (batch, head) base
          (long long)d.tokens * d.q_stride_t * 2 < 0x7fffffffLL &&
          (long long)d.tokens * d.out_stride_t * 2 < 0x7fffffffLL;
@@ -673,20 +703,23 @@ ns_status launch_attn_sweep(const AttnArgs &a, float *cls_logits, float *cls_par
     }
     p.num_cus = num_cus;
   }
+  typedef void (*kern_t)(SweepParams);
+  static const kern_t kerns[3][2] = {{attn_sweep_kernel<false, 8>, attn_sweep_kernel<true, 8>},
+                                     {attn_sweep_kernel<false, 4>, attn_sweep_kernel<true, 4>},
+                                     {attn_sweep_kernel<false, 2>, attn_sweep_kernel<true, 2>}};
   static bool attr_set = false;
   const int lds = 4 * 16384;        // three ring slots and the global token's rows; the redo gives each wave a slot
   if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(attn_sweep_kernel<false>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess ||
-        hipFuncSetAttribute(reinterpret_cast<const void *>(attn_sweep_kernel<true>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
-      return fail(NS_ERR_HIP, "cannot reserve %d bytes of LDS", lds);
+    for (int i = 0; i < 3; i++)
+      for (int j = 0; j < 2; j++)
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kerns[i][j]), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                lds) != hipSuccess)
+          return fail(NS_ERR_HIP, "cannot reserve %d bytes of LDS", lds);
     attr_set = true;
   }
-  if (d.grid_h % 8 == 0 && d.grid_w % 8 == 0)
-    hipLaunchKernelGGL(attn_sweep_kernel<false>, dim3((unsigned)strips), dim3(256), lds, a.stream, p);
-  else
-    hipLaunchKernelGGL(attn_sweep_kernel<true>, dim3((unsigned)strips), dim3(256), lds, a.stream, p);
+  const int wi = d.block == 8 ? 0 : (d.block == 4 ? 1 : 2);
+  const int ei = (d.grid_h % 8 == 0 && d.grid_w % 8 == 0) ? 0 : 1;
+  hipLaunchKernelGGL(kerns[wi][ei], dim3((unsigned)strips), dim3(256), lds, a.stream, p);
   return check_launch("attn_sweep_kernel");
 }
 

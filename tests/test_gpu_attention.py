@@ -210,6 +210,28 @@ def test_block_kernel_on_grids_16_does_not_divide(nb, monkeypatch, gh, gw, gain)
     assert_attn_close(to_np(out), ref, "bf16", "block kernel on %dx%d" % (gh, gw))
 
 
+@pytest.mark.parametrize("gh,gw,block,gain", [(16, 16, 2, 1.0), (16, 24, 4, 1.0), (20, 27, 2, 1.0), (43, 30, 4, 1.0),
+                                              (64, 64, 2, 1.0), (9, 9, 4, 1.0), (1, 1, 2, 1.0), (24, 16, 4, 14.0),
+                                              (13, 40, 2, 14.0)])
+def test_sweep_with_4x4_and_2x2_blocks(nb, monkeypatch, gh, gw, block, gain):
+    """Blocks of side 4 and 2 on the sweep kernel's 8x8 tiles: pairs whose blocks are not neighbours
+    are masked inside the tiles.  Also on grids that 8 (and the block side) does not divide, and
+    through the running-maximum path (gain 14)."""
+    monkeypatch.setenv("NSATTN_KERNEL", "sweep")
+    q, k, v = synth.small_case(68, 2, 3, 64, gh, gw, "bf16")
+    q = synth.round_to_bf16(q * gain)
+    dq, dk, dv = (to_dev(a, "bf16") for a in (q, k, v))
+    assert nb.ns_attn_patch_kernel_name(dq, gh, gw, block) == "attn_sweep_kernel"
+    out, logits, lse = nb.ns_attn_forward(dq, dk, dv, gh, gw, block, 0.125, want_cls=True)
+    torch.cuda.synchronize()
+    assert np.isfinite(to_np(out)).all()
+    ref = oracle.ns_attn(q, k, v, gh, gw, block, 0.125)
+    assert_attn_close(to_np(out), ref, "bf16", "sweep, %dx%d blocks on %dx%d" % (block, block, gh, gw))
+    _, ref_logits, ref_lse = oracle.cls_scores(q, k, 0.125, want_logits=True)
+    np.testing.assert_allclose(to_np(logits), ref_logits, rtol=0, atol=2e-5 * gain)
+    np.testing.assert_allclose(to_np(lse), ref_lse, rtol=0, atol=2e-5 * gain)
+
+
 def test_invalid_call_launches_nothing(nb):
     q = torch.zeros((1, 1, 65, 64), dtype=torch.bfloat16, device="cuda")
     out = torch.full_like(q, 7.0)
