@@ -139,13 +139,19 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_ragged_kernel(RaggedParams p
   }
 
   // ---- non-empty neighbour blocks as a bit mask over the 3x3 positions
-  uint32_t nbmask = 0;
-  for (int nb = 0; nb < 9; nb++) {
-    const int R2 = R + nb / 3 - 1, C2 = C + nb % 3 - 1;
-    if (R2 < 0 || R2 >= p.nbh || C2 < 0 || C2 >= p.nbw) continue;
-    if (cnts[R2 * p.nbw + C2] > 0) nbmask |= 1u << nb;
+  // fills of the nine neighbour positions (0 where the grid ends): lane nb loads its own, the wave
+  // then keeps all nine as scalars, so that walking the tiles needs no further loads of them
+  int fill_lane = 0;
+  if (lane < 9) {
+    const int R2 = R + lane / 3 - 1, C2 = C + lane % 3 - 1;
+    if (R2 >= 0 && R2 < p.nbh && C2 >= 0 && C2 < p.nbw) fill_lane = cnts[R2 * p.nbw + C2];
   }
-  nbmask = __builtin_amdgcn_readfirstlane(nbmask);   // the query block itself is non-empty: mask != 0
+  int fill9[9];
+#pragma unroll
+  for (int i = 0; i < 9; i++) fill9[i] = __builtin_amdgcn_readlane(fill_lane, i);
+  uint32_t nbmask = 0;
+#pragma unroll
+  for (int i = 0; i < 9; i++) nbmask |= fill9[i] > 0 ? 1u << i : 0u;   // the query block itself is non-empty: mask != 0
 
   // The key tiles in order: neighbour blocks by position, the runs of a block in list order.
   int kblk = 0, kfill = 0, kbase = 0;         // current block, its fill, start of the current run
@@ -161,7 +167,9 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_ragged_kernel(RaggedParams p
     const int nb = __builtin_ctz(nbmask);
     nbmask &= nbmask - 1;
     kblk = (R + nb / 3 - 1) * p.nbw + (C + nb % 3 - 1);
-    kfill = __builtin_amdgcn_readfirstlane(cnts[kblk]);
+    kfill = fill9[0];
+#pragma unroll
+    for (int i = 1; i < 9; i++) kfill = nb == i ? fill9[i] : kfill;
     kbase = 0;
   };
   // requests of the current key tile: K fragments into registers, V into an LDS buffer
