@@ -274,3 +274,38 @@ def test_persistent_kernel_partial_overflow(nb, variant, monkeypatch):
     torch.cuda.synchronize()
     assert np.isfinite(to_np(out)).all()
     assert_attn_close(to_np(out), ref, "bf16", "partly large logits, persistent kernel")
+
+
+def _random_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        block = int(rng.choice([2, 4, 8, 8, 8, 16, 16, 3, 5, 7, 12]))
+        gh, gw = int(rng.integers(1, 72)), int(rng.integers(1, 72))
+        force = str(rng.choice(["auto", "sweep", "block", "lists", "generic"]))
+        cases.append((i, gh, gw, block, int(rng.integers(1, 3)), int(rng.integers(1, 4)), force,
+                      float(rng.choice([1.0, 1.0, 1.0, 10.0])), float(rng.choice([0.125, 0.3, 0.05]))))
+    return cases
+
+
+@pytest.mark.parametrize("i,gh,gw,block,B,H,force,gain,scale", _random_cases(48, 2024))
+def test_random_shapes_against_the_oracle(nb, monkeypatch, i, gh, gw, block, B, H, force, gain, scale):
+    """Seeded random grids, block sides, batch and head counts, with a kernel forced at random (a forced
+    kernel that does not take the problem falls back to the automatic choice): every output row,
+    the global query's logits and log-sum-exp against the oracle."""
+    if force != "auto":
+        monkeypatch.setenv("NSATTN_KERNEL", force)
+    q, k, v = synth.small_case(5000 + i, B, H, 64, gh, gw, "bf16")
+    q = synth.round_to_bf16(q * gain)
+    dq, dk, dv = (to_dev(a, "bf16") for a in (q, k, v))
+    print("case %d: grid %dx%d block %d B=%d H=%d force=%s gain=%g scale=%g -> %s" % (
+        i, gh, gw, block, B, H, force, gain, scale, nb.ns_attn_patch_kernel_name(dq, gh, gw, block, scale)), flush=True)
+    out, logits, lse = nb.ns_attn_forward(dq, dk, dv, gh, gw, block, scale, want_cls=True)
+    torch.cuda.synchronize()
+    assert np.isfinite(to_np(out)).all()
+    ref = oracle.ns_attn(q, k, v, gh, gw, block, scale)
+    assert_attn_close(to_np(out), ref, "bf16", "random case %d" % i)
+    _, ref_logits, ref_lse = oracle.cls_scores(q, k, scale, want_logits=True)
+    tol = 2e-5 * gain * max(1.0, scale / 0.125)
+    np.testing.assert_allclose(to_np(logits), ref_logits, rtol=0, atol=tol)
+    np.testing.assert_allclose(to_np(lse), ref_lse, rtol=0, atol=tol)
