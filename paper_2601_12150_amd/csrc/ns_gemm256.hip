@@ -7,9 +7,12 @@
 // per v_mfma_f32_32x32x16_bf16, which is exactly the LDS bandwidth of a CU at full MFMA rate; with
 // a 128 x 128 piece per wave (4 x 4 MFMA tiles, 256 accumulator registers) it is half of that.
 // So: 4 waves per workgroup, one per SIMD, each with up to 512 registers; 256 (n) x 256 (m) per
-// workgroup; k in slices of 32 through a 4-stage LDS ring filled by direct global -> LDS
-// transfers that run three slices ahead; fragments of the next 16-wide k-step are read from LDS
-// while the 16 MFMAs of the current one execute.  The product is formed transposed (W rows as
+// workgroup; k in slices of 64 through two LDS stages filled by direct global -> LDS transfers
+// (rows of 128 bytes: a transfer then uses whole cache lines, which moves the same bytes in 3/4 of
+// the time that 64-byte rows take); the transfer of a slice is requested as soon as every wave has
+// read the last fragments of the slice before the previous one, a whole slice of work ahead;
+// fragments of the next 16-wide k-step are read from LDS while the 16 MFMAs of the current one
+// execute.  The product is formed transposed (W rows as
 // the A operand) as in the smaller kernel; the epilogue transposes each 32-token slab through
 // LDS so that bias / GELU / residual / store work on 16-byte pieces of full output rows.
 //
@@ -35,10 +38,10 @@ struct Gemm256Params {
   int extended;      // the last row tile has 288 rows
 };
 
-constexpr int kStageW = 256 * 64;            // bytes: 256 weight rows x 32 k
-constexpr int kStageX = 288 * 64;            // 288 token rows x 32 k
+constexpr int kStageW = 256 * 128;           // bytes: 256 weight rows x 64 k
+constexpr int kStageX = 288 * 128;           // 288 token rows x 64 k
 constexpr int kStage = kStageW + kStageX;
-constexpr int kStages = 4;
+constexpr int kStages = 2;
 constexpr int kEpiRow = 528;                 // bytes per staged output row: 128 floats + 16 pad
 constexpr int kEpiWave = 32 * kEpiRow;
 
@@ -117,13 +120,13 @@ __device__ __forceinline__ void gemm256_emit(const Gemm256Params &p, unsigned ch
 
 // One wave's work on one workgroup tile.  NTJ: 32-row token slabs of its own 128 rows that this
 // wave computes (0..4).  EXT: the tile has a ninth token slab (rows 256..287); this wave then
-// also computes that slab against weight slabs 2*WM and 2*WM+1 of its n half, and the upper
-// waves (WM = 1) issue 5 instead of 4 token-row requests per k-slice.
+// also computes that slab against weight slabs 2*WM and 2*WM+1 of its n half, and every wave
+// issues 9 instead of 8 token-row requests per k-slice.
 template <int NTJ, bool EXT, int WM, bool GELU, bool RES>
 __device__ __forceinline__ void gemm256_wave(const Gemm256Params &p, unsigned char *smem, int m0, int n0,
                                              int wave, int lane) {
   constexpr int NT = NTJ > 0 ? NTJ : 1;
-  constexpr int XREQ = (EXT && WM == 1) ? 5 : 4;
+  constexpr int XREQ = EXT ? 9 : 8;
   const int l32 = lane & 31, hh = lane >> 5;
   const int wm = wave >> 1, wn = wave & 1;
   const uint32_t lds0 = (uint32_t)(size_t)((__attribute__((address_space(3))) unsigned char *)smem);
@@ -131,46 +134,47 @@ __device__ __forceinline__ void gemm256_wave(const Gemm256Params &p, unsigned ch
   const char *ab = reinterpret_cast<const char *>(p.a);
   const char *wb = reinterpret_cast<const char *>(p.w);
 
-  // ---- transfers.  A request moves 16 rows x 64 bytes: slot `lane` is row lane/4, physical
-  // 16-byte chunk lane%4, which holds logical chunk (lane%4) ^ ((row>>2)&3); the row's low bits
-  // come from the lane alone because requests start at multiples of 16 rows.
-  const int drow = lane >> 2;
-  const uint32_t dchunk = 16u * ((lane & 3) ^ ((drow >> 2) & 3));
-  const int wreq0 = wave * 4;                                        // weight requests 4 per wave
-  const int xreq0 = XREQ == 5 ? 8 + 5 * (wave - 2) : wave * 4;       // token requests
-  const uint32_t woff = (uint32_t)(n0 + wreq0 * 16 + drow) * rowB + dchunk;
+  // ---- transfers.  A request moves 8 rows x 128 bytes: slot `lane` is row lane/8, physical
+  // 16-byte chunk lane%8, which holds logical chunk (lane%8) ^ (row & 7); requests start at
+  // multiples of 8 rows, so row & 7 = lane/8.
+  const int drow = lane >> 3;
+  const uint32_t dchunk = 16u * ((lane & 7) ^ drow);
+  const int wreq0 = wave * 8;                                        // weight requests: 8 per wave
+  const int xreq0 = wave * XREQ;                                     // token requests
+  const uint32_t woff = (uint32_t)(n0 + wreq0 * 8 + drow) * rowB + dchunk;
   uint32_t xoff[XREQ];
 #pragma unroll
   for (int j = 0; j < XREQ; j++) {
-    const int m = min(m0 + (xreq0 + j) * 16 + drow, p.M - 1);        // rows past M repeat the last row
+    const int m = min(m0 + (xreq0 + j) * 8 + drow, p.M - 1);         // rows past M repeat the last row
     xoff[j] = (uint32_t)m * rowB + dchunk;
   }
   auto issue = [&](int kt, int stage) {
-    const char *ak = ab + (size_t)kt * 64, *wk = wb + (size_t)kt * 64;
+    const char *ak = ab + (size_t)kt * 128, *wk = wb + (size_t)kt * 128;
     const uint32_t base = lds0 + stage * kStage;
 #pragma unroll
-    for (int j = 0; j < 4; j++) gdma16(wk + (size_t)j * 16 * rowB, woff, base + (wreq0 + j) * 1024);
+    for (int j = 0; j < 8; j++) gdma16(wk + (size_t)j * 8 * rowB, woff, base + (wreq0 + j) * 1024);
 #pragma unroll
     for (int j = 0; j < XREQ; j++) gdma16(ak, xoff[j], base + kStageW + (xreq0 + j) * 1024);
   };
-  constexpr int PER_SLICE = 4 + XREQ;
+  constexpr int PER_SLICE = 8 + XREQ;
 
-  // ---- fragment reads: lane (row l32 of a 32-row slab, half hh) reads logical chunk 2*ks + hh
-  unsigned char *wrd[2], *xrd[2], *erd[2];
+  // ---- fragment reads: lane (row l32 of a 32-row slab, half hh) reads logical chunk 2*ks + hh of
+  // k-step ks = 0..3, i.e. physical chunk (2*ks + hh) ^ (l32 & 7)
+  unsigned char *wrd[4], *xrd[4], *erd[4];
 #pragma unroll
-  for (int ks = 0; ks < 2; ks++) {
-    const int ch = 16 * ((2 * ks + hh) ^ ((l32 >> 2) & 3));
-    wrd[ks] = smem + (wn * 128 + l32) * 64 + ch;
-    xrd[ks] = smem + kStageW + (wm * 128 + l32) * 64 + ch;
-    erd[ks] = smem + kStageW + (256 + l32) * 64 + ch;
+  for (int ks = 0; ks < 4; ks++) {
+    const int ch = 16 * ((2 * ks + hh) ^ (l32 & 7));
+    wrd[ks] = smem + (wn * 128 + l32) * 128 + ch;
+    xrd[ks] = smem + kStageW + (wm * 128 + l32) * 128 + ch;
+    erd[ks] = smem + kStageW + (256 + l32) * 128 + ch;
   }
   bf16x8 fw[2][4], fx[2][NT], fe[2];
   auto read_frags = [&](int buf, int stage, int ks) {
     const int so = stage * kStage;
 #pragma unroll
-    for (int ti = 0; ti < 4; ti++) fw[buf][ti] = *(lds_bf16x8_ptr)(wrd[ks] + so + ti * 2048);
+    for (int ti = 0; ti < 4; ti++) fw[buf][ti] = *(lds_bf16x8_ptr)(wrd[ks] + so + ti * 4096);
 #pragma unroll
-    for (int tj = 0; tj < NTJ; tj++) fx[buf][tj] = *(lds_bf16x8_ptr)(xrd[ks] + so + tj * 2048);
+    for (int tj = 0; tj < NTJ; tj++) fx[buf][tj] = *(lds_bf16x8_ptr)(xrd[ks] + so + tj * 4096);
     if (EXT) fe[buf] = *(lds_bf16x8_ptr)(erd[ks] + so);
   };
   f32x16 acc[4][NT];   // [weight slab][token slab]: register e = n 8*(e/4) + 4*hh + e%4, lane = token l32
@@ -211,30 +215,38 @@ __device__ __forceinline__ void gemm256_wave(const Gemm256Params &p, unsigned ch
     }
   };
 
-  // ---- main loop.  At the top of iteration kt: slices <= kt+1 have landed for every wave, slice
-  // kt+2 is in flight, fragment buffer 0 holds (slice kt, k-step 0).  Requests past the last
-  // slice repeat it (into ring stages nobody reads any more) so that the waits stay uniform.
-  const int nk = p.K / 32;
+  // ---- main loop over slices of 64.  At the top of iteration kt: slice kt has landed for every
+  // wave, slice kt+1 is in flight into the other stage, fragment buffer 0 holds (slice kt, k-step
+  // 0).  After the third k-step every wave has issued its last reads of slice kt; with the barrier
+  // there slice kt+1 is complete for all, and slice kt+2 can be requested into slice kt's stage.
+  // Requests past the last slice repeat it (into a stage nobody reads any more).
+  const int nk = p.K / 64;
   issue(0, 0);
   issue(min(1, nk - 1), 1);
-  issue(min(2, nk - 1), 2);
   gwait_vm<PER_SLICE>();
   __syncthreads();
   read_frags(0, 0, 0);
   for (int kt = 0; kt < nk; kt++) {
-    // the stage of slice kt-1: every wave passed the barrier below after its last read of it
-    issue(min(kt + 3, nk - 1), (kt + 3) & 3);
-    read_frags(1, kt & 3, 1);
+    const int cur = kt & 1;
+    read_frags(1, cur, 1);
     mma(0);
     interleave();
-    read_frags(0, (kt + 1) & 3, 0);
+    read_frags(0, cur, 2);
     mma(1);
     interleave();
-    gwait_vm<PER_SLICE>();     // all but the youngest slice: slice kt+2 has landed (this wave's share)
-    __syncthreads();           // ... and everybody's
+    read_frags(1, cur, 3);
+    mma(0);
+    interleave();
+    gwait_vm<0>();                                     // slice kt+1 (this wave's share)
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the fragments of slice kt are in registers
+    __syncthreads();
+    issue(min(kt + 2, nk - 1), cur);
+    read_frags(0, cur ^ 1, 0);
+    mma(1);
+    interleave();
   }
   gwait_vm<0>();               // the repeated requests of the last iterations
-  __syncthreads();             // every wave is done with the ring: it becomes the epilogue's staging area
+  __syncthreads();             // every wave is done with the stages: they become the epilogue's staging area
 
   // ---- epilogue, one 32-token slab at a time
   unsigned char *ebuf = smem + wave * kEpiWave;
@@ -282,7 +294,7 @@ __global__ __launch_bounds__(256) void gemm256_bf16_kernel(Gemm256Params p) {
 }  // namespace
 
 bool gemm256_supported(int M, int N, int K) {
-  return M >= 256 && N % 256 == 0 && K % 32 == 0 && K >= 32;
+  return M >= 256 && N % 256 == 0 && K % 64 == 0 && K >= 64;
 }
 
 ns_status launch_gemm256(const uint16_t *a, const uint16_t *w, const float *bias, const uint16_t *r,

@@ -145,7 +145,7 @@ def test_stack_feature_maps(nb):
 @pytest.mark.parametrize("M,N,K,gelu,res", [
     (1025, 1024, 1024, False, True),    # one extended row tile chain: 4 tiles, the last with a ninth slab
     (577, 512, 256, True, False),       # remainder 65: a partial tile of its own (3 slabs)
-    (256, 256, 32, False, False),       # a single tile, a single k-slice
+    (256, 256, 64, False, False),       # a single tile, a single k-slice
     (300, 768, 2048, True, True),       # remainder 44 -> partial tile with two slabs; long k
     (1154, 640, 512, False, True),      # N not a multiple of 256: the 128 x 128 kernel
     (37, 128, 64, True, True),          # fewer rows than any tile
