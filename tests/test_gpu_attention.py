@@ -201,13 +201,17 @@ def test_block_kernel_on_grids_16_does_not_divide(nb, monkeypatch, gh, gw, gain)
     q = synth.round_to_bf16(q * gain)
     dq, dk, dv = (to_dev(a, "bf16") for a in (q, k, v))
     assert nb.ns_attn_patch_kernel_name(dq, gh, gw, 16) == "attn_block16_kernel"
-    out = nb.ns_attn_forward(dq, dk, dv, gh, gw, 16, 0.125)
+    out, logits, lse = nb.ns_attn_forward(dq, dk, dv, gh, gw, 16, 0.125, want_cls=True)
     out2 = nb.ns_attn_forward(dq, dk, dv, gh, gw, 16, 0.125)
     torch.cuda.synchronize()
     assert torch.equal(out, out2)
     assert np.isfinite(to_np(out)).all()
     ref = oracle.ns_attn(q, k, v, gh, gw, 16, 0.125)
     assert_attn_close(to_np(out), ref, "bf16", "block kernel on %dx%d" % (gh, gw))
+    # the global query's row is computed on the way: its by-products
+    _, ref_logits, ref_lse = oracle.cls_scores(q, k, 0.125, want_logits=True)
+    np.testing.assert_allclose(to_np(logits), ref_logits, rtol=0, atol=2e-5 * gain)
+    np.testing.assert_allclose(to_np(lse), ref_lse, rtol=0, atol=2e-5 * gain)
 
 
 @pytest.mark.parametrize("gh,gw,block,gain", [(16, 16, 2, 1.0), (16, 24, 4, 1.0), (20, 27, 2, 1.0), (43, 30, 4, 1.0),
