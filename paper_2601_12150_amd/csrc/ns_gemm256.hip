@@ -21,7 +21,9 @@
 // instead of opening a nearly empty tile row, which would cost a whole extra round on a launch
 // that otherwise fills the chip exactly once; the slab's 8 MFMA tiles are shared out two per
 // wave.  Any other remainder gets a tile of its own whose waves only compute the slabs that
-// hold rows.
+// hold rows.  Where M / 256 row tiles leave many CUs without work in the last round (a pruned
+// sequence: 39 x 4 tiles on 256 CUs), tiles of 192 rows (three slabs per wave) are used instead
+// when that shortens the launch.
 #include "ns_common.h"
 
 namespace ns {
@@ -36,6 +38,7 @@ struct Gemm256Params {
   int gelu;
   int ntn, ntm;      // tiles along n and m
   int extended;      // the last row tile has 288 rows
+  int tm;            // token rows per tile: 256, or 192 (three slabs per wave) where that fills the chip better
 };
 
 constexpr int kStageW = 256 * 128;           // bytes: 256 weight rows x 64 k
@@ -122,11 +125,13 @@ __device__ __forceinline__ void gemm256_emit(const Gemm256Params &p, unsigned ch
 // wave computes (0..4).  EXT: the tile has a ninth token slab (rows 256..287); this wave then
 // also computes that slab against weight slabs 2*WM and 2*WM+1 of its n half, and every wave
 // issues 9 instead of 8 token-row requests per k-slice.
-template <int NTJ, bool EXT, int WM, bool GELU, bool RES>
+template <int NTJ, bool EXT, int WM, bool GELU, bool RES, int TM = 256>
 __device__ __forceinline__ void gemm256_wave(const Gemm256Params &p, unsigned char *smem, int m0, int n0,
                                              int wave, int lane) {
+  static_assert(TM == 256 || (TM == 192 && !EXT && NTJ <= 3), "192-row tiles: three slabs per wave, no ninth slab");
   constexpr int NT = NTJ > 0 ? NTJ : 1;
-  constexpr int XREQ = EXT ? 9 : 8;
+  constexpr int XREQ = EXT ? 9 : TM / 32;    // requests of 8 token rows per wave
+  constexpr int WROWS = TM / 2;              // token rows per pair of waves
   const int l32 = lane & 31, hh = lane >> 5;
   const int wm = wave >> 1, wn = wave & 1;
   const uint32_t lds0 = (uint32_t)(size_t)((__attribute__((address_space(3))) unsigned char *)smem);
@@ -165,7 +170,7 @@ __device__ __forceinline__ void gemm256_wave(const Gemm256Params &p, unsigned ch
   for (int ks = 0; ks < 4; ks++) {
     const int ch = 16 * ((2 * ks + hh) ^ (l32 & 7));
     wrd[ks] = smem + (wn * 128 + l32) * 128 + ch;
-    xrd[ks] = smem + kStageW + (wm * 128 + l32) * 128 + ch;
+    xrd[ks] = smem + kStageW + (wm * WROWS + l32) * 128 + ch;
     erd[ks] = smem + kStageW + (256 + l32) * 128 + ch;
   }
   bf16x8 fw[2][4], fx[2][NT], fe[2];
@@ -253,7 +258,7 @@ __device__ __forceinline__ void gemm256_wave(const Gemm256Params &p, unsigned ch
 #pragma unroll
   for (int tj = 0; tj < NTJ; tj++) {
     const f32x16 *const slab[4] = {&acc[0][tj], &acc[1][tj], &acc[2][tj], &acc[3][tj]};
-    gemm256_emit<4, GELU, RES>(p, ebuf, slab, m0 + wm * 128 + tj * 32, n0 + wn * 128, lane);
+    gemm256_emit<4, GELU, RES>(p, ebuf, slab, m0 + wm * WROWS + tj * 32, n0 + wn * 128, lane);
   }
   if (EXT) {
     const f32x16 *const slab[2] = {&acce[0], &acce[1]};
@@ -270,16 +275,26 @@ __global__ __launch_bounds__(256) void gemm256_bf16_kernel(Gemm256Params p) {
   int bid = blockIdx.x;
   if (total % 8 == 0) bid = (bid & 7) * (total / 8) + (bid >> 3);
   const int bm = bid / p.ntn, bn = bid - bm * p.ntn;
-  const int m0 = bm * 256, n0 = bn * 256;
+  const int m0 = bm * p.tm, n0 = bn * 256;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
   const bool ext = p.extended && bm == p.ntm - 1;
   const int wm = wave >> 1;
-  const int rows = min(p.M - (m0 + wm * 128), 128);   // may be <= 0
+  const int wrows = p.tm >> 1;
+  const int rows = min(p.M - (m0 + wm * wrows), wrows);   // may be <= 0
   const int ntj = __builtin_amdgcn_readfirstlane(rows <= 0 ? 0 : (rows + 31) / 32);
   if (ext) {   // the extended tile is full: 256 + (1..32) rows
     if (wm) gemm256_wave<4, true, 1, GELU, RES>(p, smem, m0, n0, wave, lane);
     else gemm256_wave<4, true, 0, GELU, RES>(p, smem, m0, n0, wave, lane);
+    return;
+  }
+  if (p.tm == 192) {
+    switch (ntj) {
+      case 3: gemm256_wave<3, false, 0, GELU, RES, 192>(p, smem, m0, n0, wave, lane); break;
+      case 2: gemm256_wave<2, false, 0, GELU, RES, 192>(p, smem, m0, n0, wave, lane); break;
+      case 1: gemm256_wave<1, false, 0, GELU, RES, 192>(p, smem, m0, n0, wave, lane); break;
+      default: gemm256_wave<0, false, 0, GELU, RES, 192>(p, smem, m0, n0, wave, lane); break;
+    }
     return;
   }
   switch (ntj) {
@@ -302,10 +317,25 @@ ns_status launch_gemm256(const uint16_t *a, const uint16_t *w, const float *bias
   if (!gemm256_supported(M, N, K)) return fail(NS_ERR_UNSUPPORTED, "GEMM shape M=%d N=%d K=%d", M, N, K);
   if ((long long)M * K * 2 >= 0x7fffffffLL || (long long)N * K * 2 >= 0x7fffffffLL)
     return fail(NS_ERR_UNSUPPORTED, "GEMM operand beyond 2 GiB");
-  Gemm256Params p{a, w, r, bias, c, M, N, K, gelu ? 1 : 0, N / 256, 0, 0};
+  Gemm256Params p{a, w, r, bias, c, M, N, K, gelu ? 1 : 0, N / 256, 0, 0, 256};
   const int q = M / 256, rem = M % 256;
   p.extended = (rem > 0 && rem <= 32) ? 1 : 0;
   p.ntm = (rem == 0 || p.extended) ? q : q + 1;
+  p.tm = 256;
+  {
+    // rounds of workgroups x rows per tile: 192-row tiles where they shorten the launch
+    static int cus = 0;
+    if (cus == 0) {
+      int dev = 0;
+      hipDeviceProp_t prop;
+      cus = (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+                ? prop.multiProcessorCount : 256;
+    }
+    const long long ntm192 = (M + 191) / 192;
+    const long long cost256 = ((long long)p.ntm * p.ntn + cus - 1) / cus * 256;
+    const long long cost192 = (ntm192 * p.ntn + cus - 1) / cus * 192;
+    if (cost192 < cost256) { p.tm = 192; p.ntm = (int)ntm192; p.extended = 0; }
+  }
   const long long wgs = (long long)p.ntm * p.ntn;
   if (wgs > 0x7fffffffLL) return fail(NS_ERR_UNSUPPORTED, "GEMM grid too large");
   typedef void (*kern_t)(Gemm256Params);
