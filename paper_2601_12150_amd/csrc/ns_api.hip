@@ -135,8 +135,8 @@ size_t ns_attn_workspace_bytes(const ns_attn_desc *desc) {
 // blocks there are three MFMA kernels that compute the same function: the sweep (8x8 blocks, also
 // on grids that 8 does not divide; key tiles shared along a row of blocks, the global query's row
 // computed on the way; wants at least one row of blocks per CU),
-// the block kernel (16x16 blocks; key tiles shared by a block's four query tiles; wants two blocks
-// per CU), the persistent one-wave-per-SIMD kernel (needs two blocks per grid side), and the plain
+// the block kernel (block sides that are multiples of 16; key tiles shared by the four query tiles of
+// a 16x16 square; wants two squares per CU), the persistent one-wave-per-SIMD kernel (needs two blocks per grid side), and the plain
 // one-wave-per-query-tile kernel.  Every other bf16 problem with head_dim 64 (a pruned sequence, a
 // grid that the block side does not divide, other block sides) takes the MFMA kernel that walks
 // per-block token lists, and the rest (fp32, other head sizes) the fp32 FMA kernel.
@@ -160,10 +160,9 @@ static PatchKernel choose_patch_kernel(const ns_attn_desc &d) {
   if (force == 'g') return PK_GENERIC;        // serves every problem
   const bool tiled_ok = mfma_attn_supported(d);               // block side 8 or 16 dividing the grid
   const bool sweep_ok = sweep_attn_supported(d);              // block side 8, 4 or 2, any grid
-  const bool block16_ok = block16_attn_supported(d);          // block side 16, any grid
-  const long long strips = (long long)d.batch * d.heads * ((d.grid_h + d.block - 1) / d.block);
-  const long long blocks = strips * ((d.grid_w + d.block - 1) / d.block);
+  const bool block16_ok = block16_attn_supported(d);          // block side a multiple of 16, any grid
   const long long strips8 = (long long)d.batch * d.heads * ((d.grid_h + 7) / 8);   // the sweep's workgroups
+  const long long squares16 = (long long)d.batch * d.heads * ((d.grid_h + 15) / 16) * ((d.grid_w + 15) / 16);   // the block kernel's
   if (force == 's' && sweep_ok) return PK_SWEEP;
   if (force == 'b' && block16_ok) return PK_BLOCK16;
   if (tiled_ok) {
@@ -171,13 +170,13 @@ static PatchKernel choose_patch_kernel(const ns_attn_desc &d) {
     if (force == 'p' && persist_ok) return PK_PERSIST;
     if (force == 'm') return PK_MFMA;
     if (sweep_ok && strips8 >= device_cus()) return PK_SWEEP;
-    if (block16_ok && blocks >= 2LL * device_cus()) return PK_BLOCK16;
+    if (block16_ok && squares16 >= 2LL * device_cus()) return PK_BLOCK16;
     if (persist_ok) return PK_PERSIST;
     return PK_MFMA;
   }
   // short edge blocks, 4x4 and 2x2 blocks: the sweep (and, for the former, the block kernel) takes them
   if (force != 'l' && sweep_ok && strips8 >= device_cus()) return PK_SWEEP;
-  if (force != 'l' && block16_ok && blocks >= 2LL * device_cus()) return PK_BLOCK16;
+  if (force != 'l' && block16_ok && squares16 >= 2LL * device_cus()) return PK_BLOCK16;
   if (ragged_attn_supported(d)) return PK_RAGGED;   // its lists: wants_lists()
   return PK_GENERIC;
 }

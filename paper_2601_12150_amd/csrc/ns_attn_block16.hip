@@ -1,9 +1,10 @@
-// bf16 MFMA neighbourhood attention for 16x16 blocks: the four 64-query tiles of a query block
-// share every key tile (gfx950).
+// bf16 MFMA neighbourhood attention for blocks whose side is a multiple of 16: the four 64-query
+// tiles of a 16x16 square share every key tile (gfx950).
 //
-// A 16x16 block is four tiles of 64 tokens (4 grid rows of 16), and all four have the same
-// neighbourhood: the up to 9 x 4 key tiles of the 3x3 blocks around it.  A workgroup of 4 waves
-// owns one query block, wave w its tile w; the key tiles pass through a 3-slot LDS ring (direct
+// A 16x16 square is four tiles of 64 tokens (4 grid rows of 16), and all four have the same
+// neighbourhood: the 16x16 squares of the (clipped) 3x3 blocks around the block the square lies
+// in - up to 9 x 4 key tiles for 16x16 blocks, 36 x 4 for 32x32, 144 x 4 for 64x64.  A workgroup
+// of 4 waves owns one square, wave w its tile w; the key tiles pass through a 3-slot LDS ring (direct
 // global -> LDS transfers, a quarter of each issued by every wave, XOR-swizzled) and every wave
 // uses every one of them: one fetch from L2 instead of four, and no wave ever idles.  One
 // s_barrier per key tile makes the tile visible to all and frees the slot that the next transfer
@@ -20,7 +21,8 @@ struct BlockParams {
   uint16_t *out;
   int64_t qsb, qsh, qst, osb, osh, ost;
   float c;              // scale * log2(e)
-  int grid_h, grid_w, nbh, nbw;   // blocks per side: ceil(grid / 16)
+  int grid_h, grid_w, nbh, nbw;   // 16x16 squares per side: ceil(grid / 16)
+  int bm;               // squares per block side: block / 16
   int heads;
   int blocks;           // batch * heads * nbh * nbw
 };
@@ -65,8 +67,8 @@ __device__ __forceinline__ void bwait_vm() {
 
 constexpr float kMasked = -1e30f;     // logit of a key that does not exist (edge blocks of a grid 16 does not divide)
 
-// grid: one workgroup of 256 threads per query block.  EDGE: the grid has short blocks at its
-// right or bottom edge (a side that 16 does not divide).
+// grid: one workgroup of 256 threads per 16x16 square of queries.  EDGE: the grid has short squares
+// at its right or bottom edge (a side that 16 does not divide).
 template <bool EDGE>
 __global__ __launch_bounds__(256, 2) void attn_block16_kernel(BlockParams p) {
   const int tid = threadIdx.x, wave = NS_U(tid >> 6), lane = tid & 63;
@@ -99,6 +101,9 @@ __global__ __launch_bounds__(256, 2) void attn_block16_kernel(BlockParams p) {
   const int hv_last = EDGE ? p.grid_h - 16 * (p.nbh - 1) : 16, wv_last = EDGE ? p.grid_w - 16 * (p.nbw - 1) : 16;
   auto rows_of = [&](int Rb) { return EDGE && Rb == p.nbh - 1 ? hv_last : 16; };
   auto cols_of = [&](int Cb) { return EDGE && Cb == p.nbw - 1 ? wv_last : 16; };
+  // key tiles of a square that hold rows of their own (the others would be copies only: left out)
+  const int subs_last = EDGE ? (hv_last + 3) >> 2 : 4;
+  auto subs_of = [&](int Rb) { return EDGE && Rb == p.nbh - 1 ? subs_last : 4; };
   // offset of row i of tile `sub` of a block with hv rows and wv columns, from the tile's first token
   auto tile_off = [&](int i, int sub, int hv, int wv) {
     const int r = min(4 * sub + (i >> 4), hv - 1) - 4 * sub;      // may be negative: a tile without rows of its own
@@ -139,10 +144,11 @@ __global__ __launch_bounds__(256, 2) void attn_block16_kernel(BlockParams p) {
   const uint32_t qoff0 = tile_off(l32, wave, rows_of(R), cols_of(C)) + 64u * hh;
   const uint32_t qoff1 = tile_off(l32 + 32, wave, rows_of(R), cols_of(C)) + 64u * hh;
 
-  // ---- the key tiles of the (clipped) 3x3 block neighbourhood, block by block, four tiles each
-  const int R0 = max(R - 1, 0), R1 = min(R + 1, p.nbh - 1);
-  const int C0 = max(C - 1, 0), C1 = min(C + 1, p.nbw - 1);
-  const int ncb = C1 - C0 + 1, steps = (R1 - R0 + 1) * ncb * 4;
+  // ---- the key tiles of the (clipped) 3x3 block neighbourhood, square by square, four tiles each
+  const int RB = NS_U(R / p.bm), CB = NS_U(C / p.bm);             // the block this square lies in
+  const int R0 = max(RB - 1, 0) * p.bm, R1 = min((RB + 2) * p.bm, p.nbh) - 1;
+  const int C0 = max(CB - 1, 0) * p.bm, C1 = min((CB + 2) * p.bm, p.nbw) - 1;
+  const int ncb = C1 - C0 + 1, steps = ((R1 - R0) * 4 + subs_of(R1)) * ncb;
   int ir = R0, ic = C0, isub = 0, islot = 0;   // the tile to request next and its ring slot
   auto issue_next = [&]() {                    // this wave's share (4 requests); past the last tile it repeats that one
     // grid row `wave` of the tile (clamped to the block's last row), columns 8*j + lane/8 (clamped)
@@ -165,8 +171,8 @@ __global__ __launch_bounds__(256, 2) void attn_block16_kernel(BlockParams p) {
       for (int j = 0; j < 2; j++) bdma16(vb + base + (size_t)j * 8 * rowB, dma_voff, dst + kVOff + j * 1024);
     }
     islot = islot == kSlots - 1 ? 0 : islot + 1;
-    const bool last = ir == R1 && ic == C1 && isub == 3;
-    const bool next_block = isub == 3, next_row = next_block && ic == C1;
+    const bool next_block = isub == subs_of(ir) - 1, next_row = next_block && ic == C1;
+    const bool last = ir == R1 && next_row;
     isub = last ? isub : (next_block ? 0 : isub + 1);
     ic = last ? ic : (next_row ? C0 : (next_block ? ic + 1 : ic));
     ir = last ? ir : (next_row ? ir + 1 : ir);
@@ -323,7 +329,7 @@ __global__ __launch_bounds__(256, 2) void attn_block16_kernel(BlockParams p) {
     issue_next();
     cslot = cslot == kSlots - 1 ? 0 : cslot + 1;
     if (EDGE) {        // the same order as the requests
-      const bool nb2 = csub == 3, nr2 = nb2 && cc == C1;
+      const bool nb2 = csub == subs_of(cr) - 1, nr2 = nb2 && cc == C1;
       csub = nb2 ? 0 : csub + 1;
       cc = nr2 ? C0 : (nb2 ? cc + 1 : cc);
       cr = nr2 ? cr + 1 : cr;
@@ -341,7 +347,7 @@ __global__ __launch_bounds__(256, 2) void attn_block16_kernel(BlockParams p) {
   init_tile();
   for (int rr = R0; rr <= R1; rr++)
     for (int cc2 = C0; cc2 <= C1; cc2++)
-      for (int sub = 0; sub < 4; sub++) {
+      for (int sub = 0; sub < subs_of(rr); sub++) {
         const int cc = cc2;
         const char *kbase = kb + (uint32_t)tile_token(rr, cc, sub) * rowB;
         const uint32_t vblock = (uint32_t)tile_token(rr, cc, 0) * rowB;
@@ -406,7 +412,7 @@ __global__ __launch_bounds__(256, 2) void attn_block16_kernel(BlockParams p) {
 
 bool block16_attn_supported(const ns_attn_desc &d) {
   return d.dtype == NS_BF16 && d.head_dim == 64 && d.radius == 1 && d.n_global == 1 && d.coords == nullptr &&
-         d.block == 16 && d.scale > 0.f &&
+         d.block >= 16 && d.block % 16 == 0 && d.scale > 0.f &&
          // tokens are addressed with 32-bit byte offsets from the (batch, head) base
          (long long)d.tokens * d.q_stride_t * 2 < 0x7fffffffLL &&
          (long long)d.tokens * d.out_stride_t * 2 < 0x7fffffffLL;
@@ -426,6 +432,7 @@ ns_status launch_attn_block16(const AttnArgs &a) {
   p.grid_w = d.grid_w;
   p.nbh = (d.grid_h + 15) / 16;
   p.nbw = (d.grid_w + 15) / 16;
+  p.bm = d.block / 16;
   p.heads = d.heads;
   const long long blocks = (long long)d.batch * d.heads * p.nbh * p.nbw;
   if (blocks > 0x7fffffffLL) return fail(NS_ERR_UNSUPPORTED, "launch grid too large");

@@ -134,7 +134,9 @@ def test_kernel_choice_policy(nb, monkeypatch):
     assert name(desc(1, 16, 245, 2)) == "attn_sweep_kernel"             # 2x2 blocks on the sweep's 8x8 tiles (496 rows of tiles)
     assert name(desc(1, 16, 245, 3)) == "attn_mfma_ragged_kernel"       # 3 does not divide 8
     assert name(desc(1, 16, 245, 16)) == "attn_block16_kernel"          # short edge blocks in the 16x16 kernel
-    assert name(desc(1, 16, 245, 64)) == "attn_mfma_ragged_kernel"
+    assert name(desc(1, 16, 245, 64)) == "attn_block16_kernel"           # blocks of 4x4 squares of 16x16
+    assert name(desc(1, 16, 245, 32)) == "attn_block16_kernel"
+    assert name(desc(1, 16, 245, 24)) == "attn_mfma_ragged_kernel"       # 24 is no multiple of 16 (nor does it divide 8)
     assert name(desc(1, 2, 100, 8, dtype=nb.NS_F32)) == "attn_generic_kernel"
     assert name(desc(1, 2, 24, 8, coords=True)) == "attn_mfma_ragged_kernel"
     assert name(desc(1, 2, 32, 16, coords=True)) == "attn_mfma_ragged_kernel"

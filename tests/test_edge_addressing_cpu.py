@@ -11,7 +11,7 @@ def s32(x):
     x %= M32
     return x - M32 if x >= (1 << 31) else x
 
-def check_block16(gh, gw):
+def check_block16(gh, gw, bm=1):
     rowB = 128; gridrowB = gw * rowB; T = 1 + gh * gw; size = T * rowB
     nbh, nbw = (gh + 15) // 16, (gw + 15) // 16
     hv_last, wv_last = gh - 16 * (nbh - 1), gw - 16 * (nbw - 1)
@@ -38,9 +38,13 @@ def check_block16(gh, gw):
                         if not (rowB <= a and a + 128 <= size): bad += 1
                     # transfers of every key tile of the neighbourhood
                     dma_koff = [drow * rowB + 16 * ((lane & 7) ^ ((drow >> 1) & 7)), drow * rowB + 16 * ((lane & 7) ^ ((4 + (drow >> 1)) & 7))]
-                    for ir in range(max(R - 1, 0), min(R + 1, nbh - 1) + 1):
-                        for ic in range(max(C - 1, 0), min(C + 1, nbw - 1) + 1):
-                            for isub in range(4):
+                    RB, CB = R // bm, C // bm          # the block (bm x bm squares) this square lies in
+                    R0, R1 = max(RB - 1, 0) * bm, min((RB + 2) * bm, nbh) - 1
+                    C0, C1 = max(CB - 1, 0) * bm, min((CB + 2) * bm, nbw) - 1
+                    if not (0 <= R0 <= R <= R1 < nbh and 0 <= C0 <= C <= C1 < nbw): bad += 1
+                    for ir in range(R0, R1 + 1):
+                        for ic in range(C0, C1 + 1):
+                            for isub in range((hv_last + 3) // 4 if ir == nbh - 1 else 4):   # tiles with rows of their own
                                 grow = min(4 * isub + wave, rows_of(ir) - 1)
                                 base = u32(tile_token(ir, ic, 0) * rowB + grow * gridrowB)
                                 for j in range(2):
@@ -98,6 +102,11 @@ def check_sweep(gh, gw):
 @pytest.mark.parametrize("gh,gw", [(20, 27), (37, 21), (16, 50), (33, 16), (1, 1), (5, 70), (19, 30), (3, 3), (17, 17)])
 def test_block16_kernel_addresses_stay_in_bounds(gh, gw):
     assert check_block16(gh, gw) == 0
+
+
+@pytest.mark.parametrize("gh,gw,bm", [(37, 21, 2), (50, 70, 2), (70, 53, 4), (33, 16, 3), (5, 5, 4)])
+def test_block16_kernel_addresses_with_larger_blocks(gh, gw, bm):
+    assert check_block16(gh, gw, bm) == 0
 
 
 @pytest.mark.parametrize("gh,gw", [(20, 27), (9, 9), (8, 100), (17, 8), (1, 1), (5, 5), (12, 30), (23, 33)])

@@ -214,6 +214,28 @@ def test_block_kernel_on_grids_16_does_not_divide(nb, monkeypatch, gh, gw, gain)
     np.testing.assert_allclose(to_np(lse), ref_lse, rtol=0, atol=2e-5 * gain)
 
 
+@pytest.mark.parametrize("gh,gw,block,gain", [(64, 64, 32, 1.0), (96, 128, 32, 1.0), (70, 53, 32, 1.0), (37, 21, 32, 1.0),
+                                              (128, 64, 64, 1.0), (100, 75, 64, 1.0), (150, 40, 48, 1.0), (5, 5, 64, 1.0),
+                                              (50, 70, 32, 14.0), (16, 16, 32, 1.0)])
+def test_block_kernel_with_blocks_of_several_squares(nb, monkeypatch, gh, gw, block, gain):
+    """Block sides 32, 48 and 64 on the block kernel: a 16x16 square of queries walks the squares of
+    the 3x3 blocks around its own block.  Divisible grids, grids neither 16 nor the block side
+    divides, a block larger than the grid (dense attention), and the running-maximum path (gain 14)."""
+    monkeypatch.setenv("NSATTN_KERNEL", "block")
+    q, k, v = synth.small_case(69, 1, 2, 64, gh, gw, "bf16")
+    q = synth.round_to_bf16(q * gain)
+    dq, dk, dv = (to_dev(a, "bf16") for a in (q, k, v))
+    assert nb.ns_attn_patch_kernel_name(dq, gh, gw, block) == "attn_block16_kernel"
+    out, logits, lse = nb.ns_attn_forward(dq, dk, dv, gh, gw, block, 0.125, want_cls=True)
+    torch.cuda.synchronize()
+    assert np.isfinite(to_np(out)).all()
+    ref = oracle.ns_attn(q, k, v, gh, gw, block, 0.125)
+    assert_attn_close(to_np(out), ref, "bf16", "block kernel, %dx%d blocks on %dx%d" % (block, block, gh, gw))
+    _, ref_logits, ref_lse = oracle.cls_scores(q, k, 0.125, want_logits=True)
+    np.testing.assert_allclose(to_np(logits), ref_logits, rtol=0, atol=2e-5 * gain)
+    np.testing.assert_allclose(to_np(lse), ref_lse, rtol=0, atol=2e-5 * gain)
+
+
 @pytest.mark.parametrize("gh,gw,block,gain", [(16, 16, 2, 1.0), (16, 24, 4, 1.0), (20, 27, 2, 1.0), (43, 30, 4, 1.0),
                                               (64, 64, 2, 1.0), (9, 9, 4, 1.0), (1, 1, 2, 1.0), (24, 16, 4, 14.0),
                                               (13, 40, 2, 14.0)])
