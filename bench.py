@@ -91,6 +91,7 @@ def main() -> int:
     import ctypes
     desc0 = nb.make_desc(sets[0]["q"], g, g, blk, cfg.scale, sets[0]["out"])
     ws = torch.empty(max(1, nb.lib.ns_attn_workspace_bytes(ctypes.byref(desc0))), dtype=torch.uint8, device="cuda")
+    ws_sel = torch.empty(max(16, nb.lib.topk_filter_workspace_bytes(B, T - 1, k)), dtype=torch.uint8, device="cuda")
     stream = torch.cuda.current_stream()
 
     def step(s):
@@ -105,7 +106,8 @@ def main() -> int:
                                              vp(s["scores"].data_ptr()), st))
         nb._check(lib.topk_filter(B, T - 1, k, vp(s["scores"].data_ptr()), vp(s["x"].data_ptr()), C,
                                   nb.NS_BF16 if cfg.dtype == "bf16" else nb.NS_F32, None,
-                                  vp(s["kept"].data_ptr()), vp(s["y"].data_ptr()), None, None, 0, st))
+                                  vp(s["kept"].data_ptr()), vp(s["y"].data_ptr()), None, vp(ws_sel.data_ptr()),
+                                  ws_sel.numel(), st))
 
     if args.calibration_copy:
         # plain copy of B*T*C elements: every patch kept, so gather_rows_kernel reads and writes each row once
@@ -203,11 +205,12 @@ def measure_stages(nb, torch, sets, cfg, g, blk, k, C, B, H, T, D, ws, desc0, fl
         return (time.perf_counter() - t) / n
 
     ws2 = torch.empty(nb.lib.cls_scores_workspace_bytes(ctypes.byref(desc0)), dtype=torch.uint8, device="cuda")
+    ws_sel = torch.empty(max(16, nb.lib.topk_filter_workspace_bytes(B, T - 1, k)), dtype=torch.uint8, device="cuda")
     elt = 2 if cfg.dtype == "bf16" else 4
     t_scores = time_call(lambda s: nb.cls_scores(s["q"], s["k"], cfg.scale, scores=s["scores"], workspace=ws2))
     t_fused = time_call(lambda s: nb.cls_scores_from_logits(s["logits"], s["lse"], scores=s["scores"]))
-    t_filter = time_call(lambda s: nb.topk_filter(s["scores"], k, x=s["x"], kept_idx=s["kept"], y=s["y"]))
-    t_select = time_call(lambda s: nb.topk_filter(s["scores"], k, kept_idx=s["kept"]))
+    t_filter = time_call(lambda s: nb.topk_filter(s["scores"], k, x=s["x"], kept_idx=s["kept"], y=s["y"], workspace=ws_sel))
+    t_select = time_call(lambda s: nb.topk_filter(s["scores"], k, kept_idx=s["kept"], workspace=ws_sel))
     t_attn = time_call(lambda s: nb.ns_attn_forward(s["q"], s["k"], s["v"], g, g, blk, cfg.scale, out=s["out"],
                                                     workspace=ws))
     bytes_scores = B * H * T * D * elt + B * H * T * 4 * 2 + B * (T - 1) * 4

@@ -346,8 +346,9 @@ ns_status cls_scores_from_logits(int32_t batch, int32_t heads, int32_t tokens, i
 }
 
 size_t topk_filter_workspace_bytes(int32_t batch, int32_t n, int32_t k) {
-  (void)batch; (void)n; (void)k;
-  return 0;   // the selection keeps its state in LDS
+  (void)k;
+  if (batch < 1 || n < 1) return 0;
+  return topk_select_workspace_bytes(batch, n);   // 0 for n <= 16384: the selection keeps its state in LDS
 }
 
 ns_status topk_filter(int32_t batch, int32_t n, int32_t k, const float *scores, const void *x,
@@ -362,7 +363,6 @@ ns_status topk_filter_global(int32_t batch, int32_t n, int32_t k, int32_t n_glob
                              const void *x, int32_t channels, int32_t x_dtype, const int32_t *coords_in,
                              int32_t *kept_idx, void *y, int32_t *coords_out, void *workspace,
                              size_t workspace_bytes, void *stream) {
-  (void)workspace; (void)workspace_bytes;
   if (batch < 1 || n < 1) return fail(NS_ERR_INVALID_ARG, "batch and n must be positive");
   if (n_global < 1) return fail(NS_ERR_INVALID_ARG, "n_global must be >= 1");
   if (k < 1 || k > n) return fail(NS_ERR_INVALID_ARG, "k = %d must be in [1, n = %d]", k, n);
@@ -382,8 +382,15 @@ ns_status topk_filter_global(int32_t batch, int32_t n, int32_t k, int32_t n_glob
     if (!aligned(x, 16) || !aligned(y, 16)) return fail(NS_ERR_INVALID_ARG, "x and y must be 16-byte aligned");
     if (x == y) return fail(NS_ERR_INVALID_ARG, "y must not alias x");
   }
+  const size_t need_ws = topk_select_workspace_bytes(batch, n);
+  if (need_ws) {
+    if (!workspace) return fail(NS_ERR_WORKSPACE, "workspace is NULL, %zu bytes needed", need_ws);
+    if (!aligned(workspace, 16)) return fail(NS_ERR_WORKSPACE, "workspace must be 16-byte aligned");
+    if (workspace_bytes < need_ws)
+      return fail(NS_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need_ws);
+  }
   hipStream_t s = static_cast<hipStream_t>(stream);
-  ns_status st = launch_topk_select(batch, n, k, scores, coords_in, kept_idx, coords_out, s);
+  ns_status st = launch_topk_select(batch, n, k, scores, coords_in, kept_idx, coords_out, workspace, s);
   if (st != NS_OK) return st;
   if (x) return launch_gather_rows(batch, n, k, n_global, row_bytes, x, kept_idx, y, s);
   return NS_OK;

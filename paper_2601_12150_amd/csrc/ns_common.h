@@ -132,8 +132,10 @@ bool gemm256_supported(int M, int N, int K);
 ns_status launch_gemm256(const uint16_t *a, const uint16_t *w, const float *bias, const uint16_t *r,
                          uint16_t *c, int M, int N, int K, bool gelu, hipStream_t s);
 
+// ws: topk_select_workspace_bytes(B, N) bytes, 16-byte aligned (nothing for short score rows)
+size_t topk_select_workspace_bytes(int B, int N);
 ns_status launch_topk_select(int B, int N, int k, const float *scores, const int32_t *coords_in,
-                             int32_t *kept, int32_t *coords_out, hipStream_t s);
+                             int32_t *kept, int32_t *coords_out, void *ws, hipStream_t s);
 ns_status launch_gather_rows(int B, int N, int k, int G, size_t row_bytes, const void *x,
                              const int32_t *kept, void *y, hipStream_t s);
 

@@ -1,12 +1,14 @@
 // Ranking and compaction (paper, "Time-Efficiency Optimization": rank the tokens by
 // importance, discard the lowest-scoring proportion, shorten the sequence).
 //
-// topk_select_kernel: exact k-th largest score by a 4-pass, 8-bit-digit radix select on an
-// order-preserving integer image of the floats, then an in-index-order compaction, so the
-// kept indices come out ascending and exact ties resolve to the lower index.  One workgroup
-// of 16 waves per image: a score row is at most a few hundred KB, so the step is bound by
-// latency, not by bandwidth.
-// gather_rows_kernel: copies the kept token rows (and the CLS row) with 16-byte accesses.
+// Exact k-th largest score on an order-preserving integer image of the floats, then an
+// in-index-order compaction, so the kept indices come out ascending and exact ties resolve to
+// the lower index.
+//   topk_select_reg_kernel: rows of up to 16384 scores, one workgroup of 16 waves per image, keys
+//     in registers, bisection on the key's bits: latency-bound, a score row is 64 KB.
+//   topk_digit_pass_kernel / topk_place_kernel: longer rows, several
+//     workgroups per image, four 8-bit digit passes (radix select), one launch each.
+// gather_rows_kernel: copies the kept token rows (and the global rows) with 16-byte accesses.
 #include "ns_common.h"
 
 namespace ns {
@@ -39,101 +41,8 @@ __device__ __forceinline__ void wave_histogram_add(uint32_t *h, bool cand, uint3
   if ((rem >> lane) & 1ull) atomicAdd(&h[digit], 1u);
 }
 
-__global__ __launch_bounds__(kSelThreads) void topk_select_kernel(const float *scores, int N, int k,
-                                                                  const int32_t *coords_in,
-                                                                  int32_t *kept,
-                                                                  int32_t *coords_out) {
-  const int b = blockIdx.x;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const float *sc = scores + (size_t)b * N;
-  __shared__ uint32_t hist[kSelWaves][256];
-  __shared__ uint32_t wtot[4];
-  __shared__ uint32_t s_prefix, s_need;
-  __shared__ uint32_t wgt[kSelWaves], weq[kSelWaves];
-
-  uint32_t prefix = 0, mask = 0, need = (uint32_t)k;
-  for (int shift = 24; shift >= 0; shift -= 8) {
-    for (int i = tid; i < kSelWaves * 256; i += kSelThreads) (&hist[0][0])[i] = 0;
-    __syncthreads();
-    for (int base = 0; base < N; base += kSelThreads) {
-      const int j = base + tid;
-      bool cand = false;
-      uint32_t digit = 0;
-      if (j < N) {
-        const uint32_t key = order_key(sc[j]);
-        cand = (key & mask) == prefix;
-        digit = (key >> shift) & 255u;
-      }
-      wave_histogram_add(hist[wave], cand, digit, lane);
-    }
-    __syncthreads();
-    // threads 0..255: bin totals, suffix sums (count of candidates with a larger digit)
-    uint32_t tot = 0, above = 0;
-    if (tid < 256) {
-#pragma unroll
-      for (int w = 0; w < kSelWaves; w++) tot += hist[w][tid];
-      uint32_t incl = tot;   // inclusive suffix sum inside the wave: lanes >= lane
-#pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t t = __shfl_down(incl, off);
-        if (lane + off < 64) incl += t;
-      }
-      if (lane == 0) wtot[wave] = incl;
-      above = incl - tot;
-    }
-    __syncthreads();
-    if (tid < 256) {
-      for (int w = wave + 1; w < 4; w++) above += wtot[w];
-      if (above < need && need <= above + tot) {   // exactly one bin satisfies this
-        s_prefix = prefix | ((uint32_t)tid << shift);
-        s_need = need - above;
-      }
-    }
-    __syncthreads();
-    prefix = s_prefix;
-    need = s_need;
-    mask |= 255u << shift;
-    __syncthreads();
-  }
-  // prefix = key of the k-th largest score; `need` of the scores equal to it are kept (the
-  // first ones in index order), all larger ones are kept.
-  const uint32_t tau = prefix;
-  const int per_wave = (N + kSelWaves - 1) / kSelWaves;
-  const int lo = min(N, wave * per_wave), hi = min(N, lo + per_wave);
-  uint32_t cgt = 0, ceq = 0;
-  for (int base = lo; base < hi; base += 64) {
-    const int j = base + lane;
-    const uint32_t key = j < hi ? order_key(sc[j]) : 0u;
-    cgt += (uint32_t)__popcll(__ballot(j < hi && key > tau));
-    ceq += (uint32_t)__popcll(__ballot(j < hi && key == tau));
-  }
-  if (lane == 0) { wgt[wave] = cgt; weq[wave] = ceq; }
-  __syncthreads();
-  uint32_t gt_before = 0, eq_before = 0;
-  for (int w = 0; w < wave; w++) { gt_before += wgt[w]; eq_before += weq[w]; }
-  int32_t *kb = kept + (size_t)b * k;
-  const unsigned long long lt = (1ull << lane) - 1ull;
-  for (int base = lo; base < hi; base += 64) {
-    const int j = base + lane;
-    const uint32_t key = j < hi ? order_key(sc[j]) : 0u;
-    const bool gt = j < hi && key > tau, eq = j < hi && key == tau;
-    const unsigned long long bgt = __ballot(gt), beq = __ballot(eq);
-    const uint32_t my_gt = gt_before + (uint32_t)__popcll(bgt & lt);
-    const uint32_t my_eq = eq_before + (uint32_t)__popcll(beq & lt);
-    const bool take = gt || (eq && my_eq < need);
-    if (take) {
-      const uint32_t pos = my_gt + min(my_eq, need);
-      kb[pos] = j;
-      if (coords_in) coords_out[(size_t)b * k + pos] = coords_in[(size_t)b * N + j];
-    }
-    gt_before += (uint32_t)__popcll(bgt);
-    eq_before += (uint32_t)__popcll(beq);
-  }
-}
-
-// Register-resident variant for N <= 1024 * KPT: every thread keeps its KPT keys in registers
-// (thread t holds indices i*1024 + t), so the selection and the compaction read global memory
-// exactly once and the step is a few microseconds of ALU work.
+// Rows of N <= 1024 * KPT scores: every thread keeps its KPT keys in registers (thread t holds
+// indices i*1024 + t), so the selection and the compaction read global memory exactly once.
 template <int KPT>
 __global__ __launch_bounds__(kSelThreads) void topk_select_reg_kernel(const float *scores, int N, int k,
                                                                       const int32_t *coords_in,
@@ -176,19 +85,8 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_reg_kernel(const floa
   for (int bit = 31; bit >= 0; bit--) {
     const uint32_t cand = tau | (1u << bit);
     uint32_t c = 0;   // wave-uniform: lives in a scalar register
-    if (KPT <= 16) {
 #pragma unroll
-      for (int i = 0; i < KPT; i++) c += (uint32_t)__popcll(__ballot(key[i] >= cand));   // padding keys are 0 < cand
-    } else {
-      // many keys per lane: count per lane on the vector ALU (compare + add with carry), one
-      // reduction over the lanes per bit; the scalar unit, one per CU, is the bottleneck otherwise
-      uint32_t cl = 0;
-#pragma unroll
-      for (int i = 0; i < KPT; i++) cl += key[i] >= cand ? 1u : 0u;
-#pragma unroll
-      for (int sft = 1; sft < 64; sft <<= 1) cl += (uint32_t)__shfl_xor((int)cl, sft);
-      c = (uint32_t)__builtin_amdgcn_readfirstlane((int)cl);
-    }
+    for (int i = 0; i < KPT; i++) c += (uint32_t)__popcll(__ballot(key[i] >= cand));   // padding keys are 0 < cand
     const uint32_t tot = block_total(c, slot);
     slot ^= 1;
     if (tot >= (uint32_t)k) tau = cand;
@@ -246,6 +144,186 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_reg_kernel(const floa
   }
 }
 
+// ---- several workgroups per image (score rows too long for one CU to select from quickly)
+//
+// Four digit passes of 8 bits over the order-preserving keys, most significant first, and a
+// placement pass, each one launch over (chunks, images).  A pass histograms the digit of the keys
+// that match the prefix chosen so far, per chunk, into `part`; the next launch begins by adding the
+// chunks' histograms (every workgroup does so for itself: a few hundred loads) and choosing the
+// digit that holds the k-th largest key.  No atomics on global memory, no waiting between
+// workgroups: the launches order the passes.
+struct SelState { uint32_t prefix, need; };
+
+// Threads 0..255 bring the number of candidates per digit; sel[0] = the digit that holds the
+// need-th largest candidate, sel[1] = how many keys of that digit are still needed.
+__device__ __forceinline__ void choose_digit(uint32_t tot, uint32_t need, int tid, int wave, int lane,
+                                             uint32_t *wtot, uint32_t *sel) {
+  uint32_t above = 0;
+  if (tid < 256) {
+    uint32_t incl = tot;   // inclusive suffix sum inside the wave: lanes >= lane
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const uint32_t t = __shfl_down(incl, off);
+      if (lane + off < 64) incl += t;
+    }
+    if (lane == 0) wtot[wave] = incl;
+    above = incl - tot;
+  }
+  __syncthreads();
+  if (tid < 256) {
+    for (int w = wave + 1; w < 4; w++) above += wtot[w];
+    if (above < need && need <= above + tot) {   // exactly one digit satisfies this
+      sel[0] = (uint32_t)tid;
+      sel[1] = need - above;
+    }
+  }
+  __syncthreads();
+}
+
+// The state after digit `upto` (0..3) has been chosen, from the state before and that digit's
+// histograms; workgroup 0 of the image records it for the next launch.  The histograms were
+// written by other workgroups (other L2s): every load is a long trip, so all threads take part
+// (thread t: digit t % 256, every fourth chunk) and keep eight loads in flight.
+// quarter[4..7], if asked for (before >= 0): the same sums over the chunks below `before` only.
+__device__ __forceinline__ SelState advance_state(int upto, int b, int B, int k, int nchunk, const uint32_t *part,
+                                                  SelState *state, bool record, int before, int tid, int wave,
+                                                  int lane, uint32_t *wtot, uint32_t *sel, uint32_t (*quarter)[256]) {
+  SelState st = {0u, (uint32_t)k};
+  if (upto > 0) st = state[(size_t)(upto - 1) * B + b];
+  {
+    const uint32_t *h = part + ((size_t)upto * B + b) * (size_t)nchunk * 256 + (tid & 255);
+    uint32_t acc = 0, acc_before = 0;
+#pragma unroll 8
+    for (int c = tid >> 8; c < nchunk; c += 4) {
+      const uint32_t n = h[(size_t)c * 256];
+      acc += n;
+      acc_before += c < before ? n : 0u;
+    }
+    quarter[tid >> 8][tid & 255] = acc;
+    if (before >= 0) quarter[4 + (tid >> 8)][tid & 255] = acc_before;
+  }
+  __syncthreads();
+  const uint32_t tot = tid < 256 ? quarter[0][tid] + quarter[1][tid] + quarter[2][tid] + quarter[3][tid] : 0u;
+  choose_digit(tot, st.need, tid, wave, lane, wtot, sel);
+  st.prefix |= sel[0] << (24 - 8 * upto);
+  st.need = sel[1];
+  if (record && tid == 0) state[(size_t)upto * B + b] = st;
+  return st;
+}
+
+// grid (nchunk, B): digit `pass` (0 = bits 31..24) of the keys of chunk blockIdx.x.  The last pass
+// also counts the chunk's keys above the 24-bit prefix (they are kept whatever the last digit is).
+__global__ __launch_bounds__(kSelThreads) void topk_digit_pass_kernel(const float *scores, int N, int k, int pass,
+                                                                     int kpt, uint32_t *part, SelState *state,
+                                                                     uint32_t *above) {
+  const int b = blockIdx.y, B = gridDim.y, c = blockIdx.x, nchunk = gridDim.x;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const float *sc = scores + (size_t)b * N;
+  __shared__ uint32_t hist[kSelWaves][256];
+  __shared__ uint32_t wtot[4], sel[2], wabove[kSelWaves];
+  SelState st = {0u, (uint32_t)k};
+  if (pass > 0)     // (the first rows of hist serve as its exchange buffer)
+    st = advance_state(pass - 1, b, B, k, nchunk, part, state, c == 0, -1, tid, wave, lane, wtot, sel, hist);
+  for (int i = tid; i < kSelWaves * 256; i += kSelThreads) (&hist[0][0])[i] = 0;
+  __syncthreads();
+  const uint32_t mask = pass ? 0xffffffffu << (32 - 8 * pass) : 0u;
+  const int shift = 24 - 8 * pass;
+  const int base = c * kpt * kSelThreads;
+  uint32_t nabove = 0;     // wave-uniform
+  for (int i = 0; i < kpt; i++) {
+    const int j = base + i * kSelThreads + tid;
+    bool cand = false, over = false;
+    uint32_t digit = 0;
+    if (j < N) {
+      const uint32_t key = order_key(sc[j]);
+      cand = (key & mask) == st.prefix;
+      over = (key & mask) > st.prefix;
+      digit = (key >> shift) & 255u;
+    }
+    wave_histogram_add(hist[wave], cand, digit, lane);
+    if (pass == 3) nabove += (uint32_t)__popcll(__ballot(over));
+  }
+  if (pass == 3 && lane == 0) wabove[wave] = nabove;
+  __syncthreads();
+  if (tid < 256) {
+    uint32_t tot = 0;
+#pragma unroll
+    for (int w = 0; w < kSelWaves; w++) tot += hist[w][tid];
+    part[(((size_t)pass * B + b) * nchunk + c) * 256 + tid] = tot;
+  }
+  if (pass == 3 && tid == 0) {
+    uint32_t t = 0;
+    for (int w = 0; w < kSelWaves; w++) t += wabove[w];
+    above[(size_t)b * nchunk + c] = t;
+  }
+}
+
+// grid (nchunk, B): the kept keys of chunk blockIdx.x go to their places (ascending index order;
+// of the keys equal to the k-th largest, the first `need` in index order are kept).  What the
+// chunks before this one keep comes from their histograms of the last digit and their counts of
+// keys above the prefix: no key of another chunk is read.
+__global__ __launch_bounds__(kSelThreads) void topk_place_kernel(const float *scores, int N, int k, int kpt,
+                                                                const uint32_t *part, SelState *state,
+                                                                const uint32_t *above, const int32_t *coords_in,
+                                                                int32_t *kept, int32_t *coords_out) {
+  const int b = blockIdx.y, B = gridDim.y, c = blockIdx.x, nchunk = gridDim.x;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const float *sc = scores + (size_t)b * N;
+  __shared__ uint32_t quarter[8][256];
+  __shared__ uint32_t wtot[4], sel[2];
+  __shared__ uint32_t wgt[kSelWaves], weq[kSelWaves];
+  const uint32_t above_mine = tid < c ? above[(size_t)b * nchunk + tid] : 0u;     // at most 128 chunks
+  const SelState st = advance_state(3, b, B, k, nchunk, part, state, false, c, tid, wave, lane, wtot, sel, quarter);
+  const uint32_t tau = st.prefix, need = st.need, digit = tau & 255u;
+  uint32_t cgt = above_mine, ceq = 0;
+  if (tid < 256) {
+    const uint32_t n = quarter[4][tid] + quarter[5][tid] + quarter[6][tid] + quarter[7][tid];
+    cgt += (uint32_t)tid > digit ? n : 0u;
+    ceq = (uint32_t)tid == digit ? n : 0u;
+  }
+  if (wave < 4) {
+#pragma unroll
+    for (int sft = 1; sft < 64; sft <<= 1) {
+      cgt += (uint32_t)__shfl_xor((int)cgt, sft);
+      ceq += (uint32_t)__shfl_xor((int)ceq, sft);
+    }
+    if (lane == 0) { wgt[wave] = cgt; weq[wave] = ceq; }
+  }
+  __syncthreads();
+  uint32_t gt_before = wgt[0] + wgt[1] + wgt[2] + wgt[3], eq_before = weq[0] + weq[1] + weq[2] + weq[3];
+  __syncthreads();
+  const int base = c * kpt * kSelThreads;
+  int32_t *kb = kept + (size_t)b * k;
+  const unsigned long long lt = (1ull << lane) - 1ull;
+  for (int i = 0; i < kpt; i++) {          // index order inside the chunk: (i, wave, lane)
+    const int j = base + i * kSelThreads + tid;
+    const uint32_t key = j < N ? order_key(sc[j]) : 0u;
+    const bool gt = j < N && key > tau, eq = j < N && key == tau;
+    const unsigned long long bgt = __ballot(gt), beq = __ballot(eq);
+    if (lane == 0) { wgt[wave] = (uint32_t)__popcll(bgt); weq[wave] = (uint32_t)__popcll(beq); }
+    __syncthreads();
+    uint32_t my_gt = gt_before + (uint32_t)__popcll(bgt & lt), my_eq = eq_before + (uint32_t)__popcll(beq & lt);
+    uint32_t all_gt = 0, all_eq = 0;
+#pragma unroll
+    for (int w = 0; w < kSelWaves; w++) {
+      my_gt += w < wave ? wgt[w] : 0u;
+      my_eq += w < wave ? weq[w] : 0u;
+      all_gt += wgt[w];
+      all_eq += weq[w];
+    }
+    if (gt || (eq && my_eq < need)) {
+      const uint32_t pos = my_gt + min(my_eq, need);
+      if (pos < (uint32_t)k) {   // always, when the scores hold no NaN
+        kb[pos] = j;
+        if (coords_in) coords_out[(size_t)b * k + pos] = coords_in[(size_t)b * N + j];
+      }
+    }
+    gt_before += all_gt;
+    eq_before += all_eq;
+    __syncthreads();
+  }
+}
+
 // grid (ceil((G+k)/4), B), 256 threads: one wave per output row; the G global rows come first.
 __global__ __launch_bounds__(256) void gather_rows_kernel(const uint4 *x, const int32_t *kept,
                                                           uint4 *y, int N, int k, int G, int vec_per_row) {
@@ -260,18 +338,33 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const uint4 *x, const 
 
 }  // namespace
 
+// Keys per thread of the several-workgroup selection: at most 128 chunks per image.
+static int multi_kpt(int N) { return (int)(((long long)N + 128LL * kSelThreads - 1) / (128LL * kSelThreads)); }
+static int multi_chunks(int N) { return (N + multi_kpt(N) * kSelThreads - 1) / (multi_kpt(N) * kSelThreads); }
+
+size_t topk_select_workspace_bytes(int B, int N) {
+  if (N <= 16 * kSelThreads) return 0;                    // one workgroup per image, state in registers and LDS
+  return (size_t)4 * B * multi_chunks(N) * 256 * sizeof(uint32_t) + (size_t)4 * B * sizeof(SelState) +
+         (size_t)B * multi_chunks(N) * sizeof(uint32_t);
+}
+
 ns_status launch_topk_select(int B, int N, int k, const float *scores, const int32_t *coords_in,
-                             int32_t *kept, int32_t *coords_out, hipStream_t s) {
-  if (N <= 16 * kSelThreads)
+                             int32_t *kept, int32_t *coords_out, void *ws, hipStream_t s) {
+  if (N <= 16 * kSelThreads) {
     hipLaunchKernelGGL(topk_select_reg_kernel<16>, dim3(B), dim3(kSelThreads), 0, s, scores, N, k,
                        coords_in, kept, coords_out);
-  else if (N <= 64 * kSelThreads)
-    hipLaunchKernelGGL(topk_select_reg_kernel<64>, dim3(B), dim3(kSelThreads), 0, s, scores, N, k,
-                       coords_in, kept, coords_out);
-  else
-    hipLaunchKernelGGL(topk_select_kernel, dim3(B), dim3(kSelThreads), 0, s, scores, N, k, coords_in,
-                       kept, coords_out);
-  return check_launch("topk_select_kernel");
+    return check_launch("topk_select_reg_kernel");
+  }
+  const int kpt = multi_kpt(N), nchunk = multi_chunks(N);
+  uint32_t *part = static_cast<uint32_t *>(ws);
+  SelState *state = reinterpret_cast<SelState *>(part + (size_t)4 * B * nchunk * 256);
+  uint32_t *above = reinterpret_cast<uint32_t *>(state + (size_t)4 * B);
+  for (int pass = 0; pass < 4; pass++)
+    hipLaunchKernelGGL(topk_digit_pass_kernel, dim3(nchunk, B), dim3(kSelThreads), 0, s, scores, N, k, pass, kpt,
+                       part, state, above);
+  hipLaunchKernelGGL(topk_place_kernel, dim3(nchunk, B), dim3(kSelThreads), 0, s, scores, N, k, kpt, part, state,
+                     above, coords_in, kept, coords_out);
+  return check_launch("topk_place_kernel");
 }
 
 ns_status launch_gather_rows(int B, int N, int k, int G, size_t row_bytes, const void *x,

@@ -475,7 +475,7 @@ ns_status vit_forward_features(const ns_vit_desc *desc, const ns_vit_block_weigh
       if (st != NS_OK) return st;
       void *y = last ? x_out : buf[flip];
       st = topk_filter_global(full.batch, N, desc->keep_k, full.n_global, scores, cur, bd.dim, NS_BF16, cin, kept,
-                              y, cout, nullptr, 0, s);
+                              y, cout, ws + L.block_ws, bw, s);   // the block's workspace is idle here
       if (st != NS_OK) return st;
       cur = y;
       flip ^= 1;

@@ -67,6 +67,33 @@ def test_topk_ties_signs_and_clusters(nb):
     topk_case(nb, c, 9831)
 
 
+@pytest.mark.parametrize("N", [16385, 17408, 60025, 131072, 131073, 300000])
+def test_topk_long_rows_several_workgroups(nb, N):
+    """Rows above 16384 scores are selected by several workgroups per image (digit histograms
+    exchanged between launches): random, tied, clustered and signed scores, k from 1 to N, the
+    coordinates compacted along."""
+    rng = np.random.default_rng(N)
+    topk_case(nb, rng.random((2, N)).astype(np.float32), (N * 6) // 10)
+    topk_case(nb, rng.integers(0, 4, size=(2, N)).astype(np.float32), N // 3)          # heavy ties across chunks
+    topk_case(nb, np.full((1, N), 0.5, np.float32), N // 2)                              # all equal
+    c = (1e-5 * (1.0 + 1e-3 * rng.standard_normal((2, N)))).astype(np.float32)          # clustered
+    c[:, : N // 3] = rng.random((2, N // 3)).astype(np.float32) * 2e-5
+    topk_case(nb, c, (N * 6) // 10)
+    s = rng.standard_normal((2, N)).astype(np.float32)
+    s[:, ::7] = 0.0
+    s[:, 3::7] = -0.0
+    s[0, 17] = np.inf
+    s[1, N - 1] = -np.inf
+    for k in (1, 2, N // 2, N - 1, N):
+        topk_case(nb, s, k)
+    coords = rng.integers(0, 2 ** 31 - 1, size=(2, N), dtype=np.int32)
+    kept, _, cout = nb.topk_filter(torch.from_numpy(c).cuda(), N // 5, coords=torch.from_numpy(coords).cuda())
+    torch.cuda.synchronize()
+    ref = oracle.topk(c, N // 5)
+    assert np.array_equal(kept.cpu().numpy(), ref)
+    assert np.array_equal(cout.cpu().numpy(), np.take_along_axis(coords, ref.astype(np.int64), axis=1))
+
+
 def test_gather_and_coords_compaction_bit_exact(nb):
     rng = np.random.default_rng(4)
     B, N, C, k = 2, 500, 1024, 301

@@ -102,6 +102,28 @@ def test_stack_with_pruning_stage(nb, layers, after, keep_pct, g, block):
     assert_attn_close(to_np(out), h, "bf16", "stack output")
 
 
+def test_stack_pruning_of_a_long_sequence(nb):
+    """More than 16384 patches: the stack's selection runs with several workgroups per image and
+    takes its scratch from the stack's workspace.  The stack must keep exactly what topk_filter
+    (checked against the oracle elsewhere) keeps from the same block's scores, and continue on it."""
+    B, g, block, heads, dim, mlp = 1, 132, 8, 8, 512, 512
+    N = g * g
+    keep = (N * 60 + 99) // 100
+    rng = np.random.default_rng(23)
+    x = torch.from_numpy(synth.round_to_bf16(rng.standard_normal((B, 1 + N, dim)).astype(np.float32))).to(torch.bfloat16).cuda()
+    ws = [dev_weights(synth.make_block_weights(dim, mlp, seed=50 + i)) for i in range(2)]
+    out, kept = nb.vit_forward(x, ws, g, g, block, heads, prune_after=1, keep_k=keep)
+    h, scores = nb.vit_block_forward(x, ws[0], g, g, block, heads, want_scores=True)
+    coords = torch.from_numpy(synth.raster_coords(g, g).astype(np.int32)).cuda().repeat(B, 1).contiguous()
+    kept2, y, cout = nb.topk_filter(scores, keep, x=h, coords=coords)
+    torch.cuda.synchronize()
+    assert np.array_equal(kept.cpu().numpy(), oracle.topk(scores.cpu().numpy(), keep))
+    assert torch.equal(kept, kept2)
+    out2 = nb.vit_block_forward(y, ws[1], g, g, block, heads, coords=cout)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+
+
 def test_stack_without_pruning_equals_repeated_blocks(nb):
     B, g, block, heads, dim, mlp = 1, 16, 8, 8, 512, 512
     rng = np.random.default_rng(22)
