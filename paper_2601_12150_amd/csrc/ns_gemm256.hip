@@ -140,35 +140,39 @@ __device__ __forceinline__ void gemm256_wave(const Gemm256Params &p, unsigned ch
   const char *wb = reinterpret_cast<const char *>(p.w);
 
   // ---- transfers.  A request moves 8 rows x 128 bytes: slot `lane` is row lane/8, physical
-  // 16-byte chunk lane%8, which holds logical chunk (lane%8) ^ (row & 7); requests start at
-  // multiples of 8 rows, so row & 7 = lane/8.
+  // 16-byte chunk lane%8, which holds logical chunk (lane%8) ^ ((row >> 1) & 7), row counted
+  // within the stage.  (The LDS has 64 banks and serves 16 lanes of a 16-byte read per clock: two
+  // rows of 128 bytes span the banks once, so rows 2j and 2j+1 share a swizzle and the 16 rows
+  // that 16 consecutive lanes read land on 16 different bank groups.)  Requests start at
+  // multiples of 8 rows, so (row >> 1) & 7 = 4 * (request & 1) + lane/16.
   const int drow = lane >> 3;
-  const uint32_t dchunk = 16u * ((lane & 7) ^ drow);
+  auto dchunk = [&](int req) { return 16u * ((lane & 7) ^ ((4 * (req & 1) + (drow >> 1)) & 7)); };
   const int wreq0 = wave * 8;                                        // weight requests: 8 per wave
   const int xreq0 = wave * XREQ;                                     // token requests
-  const uint32_t woff = (uint32_t)(n0 + wreq0 * 8 + drow) * rowB + dchunk;
+  const uint32_t woff[2] = {(uint32_t)(n0 + wreq0 * 8 + drow) * rowB + dchunk(0),
+                            (uint32_t)(n0 + wreq0 * 8 + drow) * rowB + dchunk(1)};
   uint32_t xoff[XREQ];
 #pragma unroll
   for (int j = 0; j < XREQ; j++) {
     const int m = min(m0 + (xreq0 + j) * 8 + drow, p.M - 1);         // rows past M repeat the last row
-    xoff[j] = (uint32_t)m * rowB + dchunk;
+    xoff[j] = (uint32_t)m * rowB + dchunk(xreq0 + j);
   }
   auto issue = [&](int kt, int stage) {
     const char *ak = ab + (size_t)kt * 128, *wk = wb + (size_t)kt * 128;
     const uint32_t base = lds0 + stage * kStage;
 #pragma unroll
-    for (int j = 0; j < 8; j++) gdma16(wk + (size_t)j * 8 * rowB, woff, base + (wreq0 + j) * 1024);
+    for (int j = 0; j < 8; j++) gdma16(wk + (size_t)j * 8 * rowB, woff[j & 1], base + (wreq0 + j) * 1024);
 #pragma unroll
     for (int j = 0; j < XREQ; j++) gdma16(ak, xoff[j], base + kStageW + (xreq0 + j) * 1024);
   };
   constexpr int PER_SLICE = 8 + XREQ;
 
   // ---- fragment reads: lane (row l32 of a 32-row slab, half hh) reads logical chunk 2*ks + hh of
-  // k-step ks = 0..3, i.e. physical chunk (2*ks + hh) ^ (l32 & 7)
+  // k-step ks = 0..3, i.e. physical chunk (2*ks + hh) ^ ((l32 >> 1) & 7) (slabs start at multiples of 32 rows)
   unsigned char *wrd[4], *xrd[4], *erd[4];
 #pragma unroll
   for (int ks = 0; ks < 4; ks++) {
-    const int ch = 16 * ((2 * ks + hh) ^ (l32 & 7));
+    const int ch = 16 * ((2 * ks + hh) ^ ((l32 >> 1) & 7));
     wrd[ks] = smem + (wn * 128 + l32) * 128 + ch;
     xrd[ks] = smem + kStageW + (wm * WROWS + l32) * 128 + ch;
     erd[ks] = smem + kStageW + (256 + l32) * 128 + ch;
