@@ -128,42 +128,49 @@ __global__ __launch_bounds__(256) void cls_row_kernel(const T *q, const T *k, co
 __device__ __forceinline__ void store_out(float *p, float x) { *p = x; }
 __device__ __forceinline__ void store_out(uint16_t *p, float x) { *p = (uint16_t)(pack_bf16(x, 0.f) & 0xffffu); }
 
-// grid (H*G, B), 256 threads: thread (group g = tid/64, channel d = tid%64).  Group g merges the
-// chunk partials g, g+4, g+8, ... with a running maximum; the four groups are then merged in
-// group order.  The order of operations is fixed, so the result is deterministic.
+// grid (H*G, B), 1024 threads: thread (group g = tid/64, channel d = tid%64).  First the maximum
+// over all records, then group g sums the records g, g+16, g+32, ... weighted against that maximum
+// (no running maximum: the loads do not depend on each other and eight are kept in flight - the
+// records were written by other workgroups, so every load is a long trip), and the sixteen groups
+// are added in group order.  The order of operations is fixed, so the result is deterministic.
+constexpr int kCombineThreads = 1024, kCombineGroups = kCombineThreads / 64;
 template <typename T, bool WITH_V>
-__global__ __launch_bounds__(256) void cls_combine_kernel(const float *partials, int nchunks, int H, int G,
-                                                          T *out, int64_t osb, int64_t osh, int64_t ost,
-                                                          float *lse) {
-  const int hg = blockIdx.x, b = blockIdx.y, g = threadIdx.x >> 6, d = threadIdx.x & 63;
+__global__ __launch_bounds__(kCombineThreads) void cls_combine_kernel(const float *partials, int nchunks, int H,
+                                                                      int G, T *out, int64_t osb, int64_t osh,
+                                                                      int64_t ost, float *lse) {
+  const int hg = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, g = tid >> 6, d = tid & 63;
   const int h = hg / G, gq = hg - h * G;
   const float *rec = partials + ((size_t)b * H * G + hg) * nchunks * kClsPartialFloats;
-  __shared__ float sm[4], sl[4], so[4][64];
-  float M = -INFINITY, L = 0.f, O = 0.f;
-#pragma unroll 4
-  for (int c = g; c < nchunks; c += 4) {
-    const float mc = rec[c * kClsPartialFloats], lc = rec[c * kClsPartialFloats + 1];
-    const float oc = WITH_V ? rec[c * kClsPartialFloats + 2 + d] : 0.f;
-    const float Mn = fmaxf(M, mc);
-    const float wo = __builtin_amdgcn_exp2f((M - Mn) * kLog2e), wn = __builtin_amdgcn_exp2f((mc - Mn) * kLog2e);
-    L = __builtin_fmaf(L, wo, lc * wn);
-    O = __builtin_fmaf(O, wo, oc * wn);
-    M = Mn;
+  __shared__ float sm[kCombineGroups], sl[kCombineGroups], so[kCombineGroups][64];
+  float M = -INFINITY;
+  for (int c = tid; c < nchunks; c += kCombineThreads) M = fmaxf(M, rec[(size_t)c * kClsPartialFloats]);
+#pragma unroll
+  for (int sft = 1; sft < 64; sft <<= 1) M = fmaxf(M, __shfl_xor(M, sft));
+  if (d == 0) sm[g] = M;
+  __syncthreads();
+  M = sm[0];
+#pragma unroll
+  for (int i = 1; i < kCombineGroups; i++) M = fmaxf(M, sm[i]);   // finite: there is at least one record with a key
+  float L = 0.f, O = 0.f;
+#pragma unroll 8
+  for (int c = g; c < nchunks; c += kCombineGroups) {
+    const float *r = rec + (size_t)c * kClsPartialFloats;
+    const float w = __builtin_amdgcn_exp2f((r[0] - M) * kLog2e);   // 0 for a record without keys
+    L = __builtin_fmaf(r[1], w, L);
+    if (WITH_V) O = __builtin_fmaf(r[2 + d], w, O);
   }
-  if (d == 0) { sm[g] = M; sl[g] = L; }
+  if (d == 0) sl[g] = L;
   so[g][d] = O;
   __syncthreads();
   if (g != 0) return;
-  float Mt = fmaxf(fmaxf(sm[0], sm[1]), fmaxf(sm[2], sm[3]));   // finite: group 0 always has a chunk
   float Lt = 0.f, Ot = 0.f;
 #pragma unroll
-  for (int i = 0; i < 4; i++) {
-    const float w = __builtin_amdgcn_exp2f((sm[i] - Mt) * kLog2e);   // 0 for an empty group
-    Lt = __builtin_fmaf(sl[i], w, Lt);
-    Ot = __builtin_fmaf(so[i][d], w, Ot);
+  for (int i = 0; i < kCombineGroups; i++) {
+    Lt += sl[i];
+    Ot += so[i][d];
   }
   if (WITH_V) store_out(out + b * osb + h * osh + gq * ost + d, Ot / Lt);
-  if (lse && d == 0) lse[(size_t)b * H * G + hg] = Mt + __builtin_amdgcn_logf(Lt) * kLn2;
+  if (lse && d == 0) lse[(size_t)b * H * G + hg] = M + __builtin_amdgcn_logf(Lt) * kLn2;
 }
 
 // grid (ceil(N/256), B), 256 threads (thread = patch).  H counts the global rows of an image
@@ -236,7 +243,7 @@ ns_status launch_cls_row(const ns_attn_desc &d, const void *q, const void *k, co
 ns_status launch_cls_combine(const ns_attn_desc &d, const float *partials, void *out, float *lse,
                              bool with_v, hipStream_t s, int nchunks) {
   const int nch = nchunks > 0 ? nchunks : cls_num_chunks(d.tokens);
-  dim3 grid(d.heads * d.n_global, d.batch), blk(256);
+  dim3 grid(d.heads * d.n_global, d.batch), blk(kCombineThreads);
   if (d.dtype == NS_F32) {
     if (with_v)
       hipLaunchKernelGGL((cls_combine_kernel<float, true>), grid, blk, 0, s, partials, nch, d.heads,
