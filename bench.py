@@ -1,6 +1,6 @@
 #!/usr/bin/env python3
-"""Benchmark of the hot path on one MI355X: one "step" = ns_attn_forward (with the CLS
-by-products) -> cls_scores_from_logits -> topk_filter (select + gather) on one batch of the
+"""Benchmark of the hot path on one MI355X: one "step" = ns_attn_forward_scores (attention with
+the global query's row and by-products, importance scores) -> topk_filter (select + gather) on one batch of the
 128x128-grid workload (B=2, 16 heads x 64, 8x8 blocks, bf16, keep 60 %).
 
 Prints ONE JSON line.  `value` is tokens/s of the whole step with inputs resident in HBM;
@@ -99,11 +99,10 @@ def main() -> int:
         lib, by, vp = nb.lib, ctypes.byref, ctypes.c_void_p
         d = nb.make_desc(s["q"], g, g, blk, cfg.scale, s["out"])
         st = vp(stream.cuda_stream)
-        nb._check(lib.ns_attn_forward(by(d), vp(s["q"].data_ptr()), vp(s["k"].data_ptr()), vp(s["v"].data_ptr()),
-                                      vp(s["out"].data_ptr()), vp(s["logits"].data_ptr()), vp(s["lse"].data_ptr()),
-                                      vp(ws.data_ptr()), ws.numel(), st))
-        nb._check(lib.cls_scores_from_logits(B, H, T, 1, vp(s["logits"].data_ptr()), vp(s["lse"].data_ptr()),
-                                             vp(s["scores"].data_ptr()), st))
+        nb._check(lib.ns_attn_forward_scores(by(d), vp(s["q"].data_ptr()), vp(s["k"].data_ptr()),
+                                             vp(s["v"].data_ptr()), vp(s["out"].data_ptr()),
+                                             vp(s["logits"].data_ptr()), vp(s["lse"].data_ptr()),
+                                             vp(s["scores"].data_ptr()), vp(ws.data_ptr()), ws.numel(), st))
         nb._check(lib.topk_filter(B, T - 1, k, vp(s["scores"].data_ptr()), vp(s["x"].data_ptr()), C,
                                   nb.NS_BF16 if cfg.dtype == "bf16" else nb.NS_F32, None,
                                   vp(s["kept"].data_ptr()), vp(s["y"].data_ptr()), None, vp(ws_sel.data_ptr()),
@@ -184,7 +183,7 @@ def main() -> int:
            "config": {"workload": "%s: B=%d, %dx%d patch grid + CLS (T=%d), %d heads x %d, %dx%d blocks, 3x3 "
                                   "neighbourhood, keep %d%% (k=%d)" % (cfg.name, B, g, g, T, H, D, blk, blk,
                                                                         cfg.keep_pct, k),
-                      "step": "ns_attn_forward + cls_scores_from_logits + topk_filter(select+gather)",
+                      "step": "ns_attn_forward_scores (attention, global rows, scores) + topk_filter (select + gather)",
                       "input_sets_rotated": n_sets,
                       "background_fraction": info.get("background_fraction")},
            "roofline": roofline, "cpu_baseline": cpu, "stages": stages}

@@ -4,7 +4,7 @@
  * AMD MI355X (gfx950).
  *
  * The operations follow the paper's Methodology section:
- *   "Memory-Efficiency Optimization"  -> ns_attn_forward
+ *   "Memory-Efficiency Optimization"  -> ns_attn_forward, ns_attn_forward_scores
  *   "Time-Efficiency Optimization"    -> cls_scores, cls_scores_from_logits, topk_filter
  * and vit_block_forward wraps the attention in a pre-LayerNorm transformer block.
  *
@@ -96,6 +96,19 @@ size_t ns_attn_workspace_bytes(const ns_attn_desc *desc);
 ns_status ns_attn_forward(const ns_attn_desc *desc, const void *q, const void *k, const void *v,
                           void *out, float *cls_logits, float *cls_lse, void *workspace,
                           size_t workspace_bytes, void *stream);
+
+/*
+ * ns_attn_forward followed by cls_scores_from_logits (paper, "Time-Efficiency Optimization": the
+ * importance of a patch is the attention the global tokens pay to it, averaged over heads), with
+ * the merge of the global queries' rows and the scoring in one launch.
+ *   cls_logits out, required  [B,H,G,T] fp32 (the scoring reads it back)
+ *   cls_lse    out, nullable  [B,H,G]
+ *   scores     out, required  [B, T-G] fp32
+ * Everything else as in ns_attn_forward.
+ */
+ns_status ns_attn_forward_scores(const ns_attn_desc *desc, const void *q, const void *k, const void *v,
+                                 void *out, float *cls_logits, float *cls_lse, float *scores,
+                                 void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Importance scores (paper, "Time-Efficiency Optimization": a score per token derived from

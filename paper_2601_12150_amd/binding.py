@@ -20,7 +20,7 @@ NS_OK, NS_ERR_INVALID_ARG, NS_ERR_UNSUPPORTED, NS_ERR_WORKSPACE, NS_ERR_HIP = ra
 NS_F32, NS_BF16 = 0, 1
 
 EXPORTS = ["ns_attn_workspace_bytes", "ns_attn_forward", "cls_scores_workspace_bytes", "cls_scores",
-           "cls_scores_from_logits", "topk_filter_workspace_bytes", "topk_filter", "topk_filter_global", "vit_forward_features",
+           "cls_scores_from_logits", "ns_attn_forward_scores", "topk_filter_workspace_bytes", "topk_filter", "topk_filter_global", "vit_forward_features",
            "vit_block_workspace_bytes", "vit_block_forward", "linear_forward", "vit_workspace_bytes", "vit_forward",
            "ns_attn_patch_kernel_time", "ns_attn_patch_kernel_name", "ns_last_error",
            "ns_version"]
@@ -71,6 +71,8 @@ def _load() -> ctypes.CDLL:
     lib.ns_attn_workspace_bytes.argtypes = [dp]
     lib.ns_attn_forward.restype = ctypes.c_int
     lib.ns_attn_forward.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.ns_attn_forward_scores.restype = ctypes.c_int
+    lib.ns_attn_forward_scores.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.ns_attn_patch_kernel_time.restype = ctypes.c_int
     lib.ns_attn_patch_kernel_time.argtypes = [dp, vp, vp, vp, vp, vp, sz, i32,
                                               ctypes.POINTER(ctypes.c_float), vp]
@@ -188,6 +190,32 @@ def ns_attn_forward(q, k, v, grid_h, grid_w, block, scale=None, coords=None, out
     _check(lib.ns_attn_forward(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(logits),
                                _ptr(lse), _ptr(ws), 0 if ws is None else ws.numel(), _stream(stream)))
     return (out, logits, lse) if want_cls else out
+
+
+def ns_attn_forward_scores(q, k, v, grid_h, grid_w, block, scale=None, coords=None, out=None,
+                           workspace=None, stream=None, n_global=1):
+    """ns_attn_forward with the global queries' by-products, and the importance scores of the
+    patches from them, in one call.  Returns (out, cls_logits, cls_lse, scores [B, T - n_global])."""
+    if not (q.shape == k.shape == v.shape and q.stride() == k.stride() == v.stride()):
+        raise ValueError("q, k, v must have the same shape and strides")
+    if not (q.dtype == k.dtype == v.dtype):
+        raise ValueError("q, k, v must have the same dtype")
+    B, H, T, D = q.shape
+    G = int(n_global)
+    if out is None:
+        out = torch.empty((B, H, T, D), dtype=q.dtype, device=q.device)
+    if coords is not None and (coords.dtype != torch.int32 or not coords.is_contiguous()):
+        raise ValueError("coords must be a contiguous int32 tensor [B, T - n_global]")
+    desc = make_desc(q, grid_h, grid_w, block, scale, out, coords, 1, n_global)
+    logits = torch.empty((B, H, T) if G == 1 else (B, H, G, T), dtype=torch.float32, device=q.device)
+    lse = torch.empty((B, H) if G == 1 else (B, H, G), dtype=torch.float32, device=q.device)
+    scores = torch.empty((B, T - G), dtype=torch.float32, device=q.device)
+    nbytes = lib.ns_attn_workspace_bytes(ctypes.byref(desc))
+    ws = _workspace(nbytes, q.device, workspace)
+    _check(lib.ns_attn_forward_scores(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(logits),
+                                      _ptr(lse), _ptr(scores), _ptr(ws), 0 if ws is None else ws.numel(),
+                                      _stream(stream)))
+    return out, logits, lse, scores
 
 
 def ns_attn_patch_kernel_time(q, k, v, grid_h, grid_w, block, scale=None, coords=None, out=None,

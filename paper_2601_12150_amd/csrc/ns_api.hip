@@ -233,13 +233,23 @@ static ns_status prepare_attn(const ns_attn_desc *desc, const void *q, const voi
 ns_status ns_attn_forward(const ns_attn_desc *desc, const void *q, const void *k, const void *v,
                           void *out, float *cls_logits, float *cls_lse, void *workspace,
                           size_t workspace_bytes, void *stream) {
-  return attn_forward_impl(desc, q, k, v, out, cls_logits, cls_lse, workspace, workspace_bytes, stream, false);
+  return attn_forward_impl(desc, q, k, v, out, cls_logits, cls_lse, nullptr, workspace, workspace_bytes, stream,
+                           false);
+}
+
+ns_status ns_attn_forward_scores(const ns_attn_desc *desc, const void *q, const void *k, const void *v,
+                                 void *out, float *cls_logits, float *cls_lse, float *scores,
+                                 void *workspace, size_t workspace_bytes, void *stream) {
+  if (!cls_logits || !scores) return fail(NS_ERR_INVALID_ARG, "cls_logits and scores must not be NULL");
+  if (!aligned(scores, 4)) return fail(NS_ERR_INVALID_ARG, "scores misaligned");
+  return attn_forward_impl(desc, q, k, v, out, cls_logits, cls_lse, scores, workspace, workspace_bytes, stream,
+                           false);
 }
 
 }  // extern "C"
 
 ns_status ns::attn_forward_impl(const ns_attn_desc *desc, const void *q, const void *k, const void *v,
-                                void *out, float *cls_logits, float *cls_lse, void *workspace,
+                                void *out, float *cls_logits, float *cls_lse, float *scores, void *workspace,
                                 size_t workspace_bytes, void *stream, bool reuse_lists) {
   if ((cls_logits && !aligned(cls_logits, 4)) || (cls_lse && !aligned(cls_lse, 4)))
     return fail(NS_ERR_INVALID_ARG, "cls_logits / cls_lse misaligned");
@@ -252,6 +262,7 @@ ns_status ns::attn_forward_impl(const ns_attn_desc *desc, const void *q, const v
     // this kernel computes the global query's partials and logits on the way
     st = launch_attn_sweep(a, cls_logits, partials);
     if (st != NS_OK) return st;
+    if (scores) return launch_cls_combine_scores(d, partials, out, cls_lse, cls_logits, scores, a.stream, sweep_cls_chunks(d));
     return launch_cls_combine(d, partials, out, cls_lse, true, a.stream, sweep_cls_chunks(d));
   }
   st = launch_patch_attention(a);
@@ -259,6 +270,7 @@ ns_status ns::attn_forward_impl(const ns_attn_desc *desc, const void *q, const v
   // the global query's row: chunk partials, then the merge that also writes out[:, :, 0, :]
   st = launch_cls_row(d, q, k, v, cls_logits, partials, true, a.stream);
   if (st != NS_OK) return st;
+  if (scores) return launch_cls_combine_scores(d, partials, out, cls_lse, cls_logits, scores, a.stream);
   return launch_cls_combine(d, partials, out, cls_lse, true, a.stream);
 }
 

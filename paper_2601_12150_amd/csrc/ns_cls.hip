@@ -135,10 +135,9 @@ __device__ __forceinline__ void store_out(uint16_t *p, float x) { *p = (uint16_t
 // are added in group order.  The order of operations is fixed, so the result is deterministic.
 constexpr int kCombineThreads = 1024, kCombineGroups = kCombineThreads / 64;
 template <typename T, bool WITH_V>
-__global__ __launch_bounds__(kCombineThreads) void cls_combine_kernel(const float *partials, int nchunks, int H,
-                                                                      int G, T *out, int64_t osb, int64_t osh,
-                                                                      int64_t ost, float *lse) {
-  const int hg = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, g = tid >> 6, d = tid & 63;
+__device__ __forceinline__ void cls_combine_body(int hg, int b, const float *partials, int nchunks, int H, int G,
+                                                 T *out, int64_t osb, int64_t osh, int64_t ost, float *lse) {
+  const int tid = threadIdx.x, g = tid >> 6, d = tid & 63;
   const int h = hg / G, gq = hg - h * G;
   const float *rec = partials + ((size_t)b * H * G + hg) * nchunks * kClsPartialFloats;
   __shared__ float sm[kCombineGroups], sl[kCombineGroups], so[kCombineGroups][64];
@@ -173,20 +172,27 @@ __global__ __launch_bounds__(kCombineThreads) void cls_combine_kernel(const floa
   if (lse && d == 0) lse[(size_t)b * H * G + hg] = M + __builtin_amdgcn_logf(Lt) * kLn2;
 }
 
-// grid (ceil(N/256), B), 256 threads (thread = patch).  H counts the global rows of an image
-// (heads x global tokens): the score is the mean over all of them.  lse given directly, or
-// recomputed per row from the row kernel's (max, sum) partials.
-__global__ __launch_bounds__(256) void cls_scores_kernel(const float *logits, const float *lse,
-                                                         const float *partials, int nchunks, int H,
-                                                         int T_, int G, float *scores) {
+template <typename T, bool WITH_V>
+__global__ __launch_bounds__(kCombineThreads) void cls_combine_kernel(const float *partials, int nchunks, int H,
+                                                                      int G, T *out, int64_t osb, int64_t osh,
+                                                                      int64_t ost, float *lse) {
+  cls_combine_body<T, WITH_V>(blockIdx.x, blockIdx.y, partials, nchunks, H, G, out, osb, osh, ost, lse);
+}
+
+// Workgroup `blk` of image b scores blockDim.x patches (thread = patch).  H counts the global rows
+// of an image (heads x global tokens): the score is the mean over all of them.  lse given
+// directly, or recomputed per row from the (max, sum) of the partial records.
+__device__ __forceinline__ void cls_scores_body(int blk, int b, const float *logits, const float *lse,
+                                                const float *partials, int nchunks, int H, int T_, int G,
+                                                float *scores) {
   __shared__ float s_lse[1024];
-  const int b = blockIdx.y, tid = threadIdx.x;
+  const int tid = threadIdx.x, nthreads = blockDim.x;
   if (lse) {
-    for (int h = tid; h < H; h += 256) s_lse[h] = lse[(size_t)b * H + h];
+    for (int h = tid; h < H; h += nthreads) s_lse[h] = lse[(size_t)b * H + h];
   } else {
     // 16 lanes per head: each merges every 16th record, then the 16 are merged pairwise (fixed order)
     const int sub = tid & 15;
-    for (int h = tid >> 4; h < H; h += 16) {
+    for (int h = tid >> 4; h < H; h += nthreads >> 4) {
       const float *rec = partials + ((size_t)b * H + h) * nchunks * kClsPartialFloats;
       float M = -INFINITY, L = 0.f;
       for (int c = sub; c < nchunks; c += 16) {
@@ -213,7 +219,7 @@ __global__ __launch_bounds__(256) void cls_scores_kernel(const float *logits, co
   }
   __syncthreads();
   const int N = T_ - G;
-  const int j = blockIdx.x * 256 + tid;
+  const int j = blk * nthreads + tid;
   if (j >= N) return;
   float acc = 0.f;
   for (int h = 0; h < H; h++) {
@@ -221,6 +227,29 @@ __global__ __launch_bounds__(256) void cls_scores_kernel(const float *logits, co
     acc += __builtin_amdgcn_exp2f((x - s_lse[h]) * kLog2e);
   }
   scores[(size_t)b * N + j] = acc / (float)H;
+}
+
+// grid (ceil(N/256), B), 256 threads
+__global__ __launch_bounds__(256) void cls_scores_kernel(const float *logits, const float *lse,
+                                                         const float *partials, int nchunks, int H,
+                                                         int T_, int G, float *scores) {
+  cls_scores_body(blockIdx.x, blockIdx.y, logits, lse, partials, nchunks, H, T_, G, scores);
+}
+
+// Both in one launch, grid (H + ceil(N/1024), B), 1024 threads: the first H workgroups of an image
+// merge the records of one global row each (output row and log-sum-exp), the others score 1024
+// patches each, with the log-sum-exps they derive from the records themselves.
+template <typename T>
+__global__ __launch_bounds__(kCombineThreads) void cls_combine_scores_kernel(const float *partials, int nchunks,
+                                                                             int heads, int G, T *out, int64_t osb,
+                                                                             int64_t osh, int64_t ost, float *lse,
+                                                                             const float *logits, int T_,
+                                                                             float *scores) {
+  const int H = heads * G;
+  if ((int)blockIdx.x < H)
+    cls_combine_body<T, true>(blockIdx.x, blockIdx.y, partials, nchunks, heads, G, out, osb, osh, ost, lse);
+  else
+    cls_scores_body(blockIdx.x - H, blockIdx.y, logits, nullptr, partials, nchunks, H, T_, G, scores);
 }
 
 }  // namespace
@@ -262,6 +291,22 @@ ns_status launch_cls_combine(const ns_attn_desc &d, const float *partials, void 
                          d.out_stride_t, lse);
   }
   return check_launch("cls_combine_kernel");
+}
+
+ns_status launch_cls_combine_scores(const ns_attn_desc &d, const float *partials, void *out, float *lse,
+                                    const float *logits, float *scores, hipStream_t s, int nchunks) {
+  const int nch = nchunks > 0 ? nchunks : cls_num_chunks(d.tokens);
+  const int N = d.tokens - d.n_global;
+  dim3 grid(d.heads * d.n_global + (N + kCombineThreads - 1) / kCombineThreads, d.batch), blk(kCombineThreads);
+  if (d.dtype == NS_F32)
+    hipLaunchKernelGGL((cls_combine_scores_kernel<float>), grid, blk, 0, s, partials, nch, d.heads, d.n_global,
+                       static_cast<float *>(out), d.out_stride_b, d.out_stride_h, d.out_stride_t, lse, logits,
+                       d.tokens, scores);
+  else
+    hipLaunchKernelGGL((cls_combine_scores_kernel<uint16_t>), grid, blk, 0, s, partials, nch, d.heads, d.n_global,
+                       static_cast<uint16_t *>(out), d.out_stride_b, d.out_stride_h, d.out_stride_t, lse, logits,
+                       d.tokens, scores);
+  return check_launch("cls_combine_scores_kernel");
 }
 
 ns_status launch_cls_scores(int B, int H, int T, int G, const float *logits, const float *lse,

@@ -92,10 +92,11 @@ struct AttnArgs {
 
 // ns_attn_forward with one more knob: reuse_lists = the per-block token lists that an earlier call
 // with the same descriptor, coords contents and workspace left in the workspace are still valid
-// (a stack of blocks after its pruning stage), so they are not rebuilt.
+// (a stack of blocks after its pruning stage), so they are not rebuilt.  scores != NULL: also the
+// importance scores [B, T-G] (needs cls_logits), merged and scored in one launch.
 ns_status attn_forward_impl(const ns_attn_desc *desc, const void *q, const void *k, const void *v, void *out,
-                            float *cls_logits, float *cls_lse, void *workspace, size_t workspace_bytes,
-                            void *stream, bool reuse_lists);
+                            float *cls_logits, float *cls_lse, float *scores, void *workspace,
+                            size_t workspace_bytes, void *stream, bool reuse_lists);
 
 ns_status launch_block_lists(const ns_attn_desc &d, int32_t *lists, int32_t *counts, hipStream_t s);
 ns_status launch_grid_lists(const ns_attn_desc &d, int32_t *lists, int32_t *counts, hipStream_t s);
@@ -124,6 +125,9 @@ ns_status launch_cls_row(const ns_attn_desc &d, const void *q, const void *k, co
 ns_status launch_cls_combine(const ns_attn_desc &d, const float *partials, void *out, float *lse,
                              bool with_v, hipStream_t s, int nchunks = 0 /* 0: cls_num_chunks(tokens) */);
 // lse given directly, or (lse == nullptr) recomputed from the row kernel's partials
+// launch_cls_combine and the scoring of all patches in one launch (lse may be NULL)
+ns_status launch_cls_combine_scores(const ns_attn_desc &d, const float *partials, void *out, float *lse,
+                                    const float *logits, float *scores, hipStream_t s, int nchunks = 0);
 ns_status launch_cls_scores(int B, int H, int T, int G, const float *logits, const float *lse,
                             const float *partials, int nchunks, float *scores, hipStream_t s);
 

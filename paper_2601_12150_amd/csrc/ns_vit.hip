@@ -366,12 +366,9 @@ static ns_status block_forward_impl(const ns_vit_block_desc *desc, const ns_vit_
   st = launch_gemm(ln, static_cast<const uint16_t *>(w->w_qkv), w->b_qkv, nullptr, qkv, M, 3 * dim, dim, false, s);
   if (st != NS_OK) return st;
   st = attn_forward_impl(&ad, qkv, qkv + dim, qkv + 2 * dim, att, scores_out ? logits : nullptr,
-                         scores_out ? lse : nullptr, ws + L.attn_ws, L.total - L.attn_ws, s, reuse_lists);
+                         scores_out ? lse : nullptr, scores_out, ws + L.attn_ws, L.total - L.attn_ws, s,
+                         reuse_lists);
   if (st != NS_OK) return st;
-  if (scores_out) {
-    st = cls_scores_from_logits(ad.batch, ad.heads, ad.tokens, ad.n_global, logits, lse, scores_out, s);
-    if (st != NS_OK) return st;
-  }
   st = launch_gemm(att, static_cast<const uint16_t *>(w->w_proj), w->b_proj, x, h, M, dim, dim, false, s);
   if (st != NS_OK) return st;
   st = launch_layernorm(h, w->ln2_g, w->ln2_b, ln, M, dim, desc->ln_eps, s);

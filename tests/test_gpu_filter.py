@@ -32,6 +32,30 @@ def test_cls_scores_standalone_and_fused(nb, dtype, g, B, H):
     np.testing.assert_allclose(to_np(fused), ref, rtol=2e-5, atol=1e-9)
 
 
+@pytest.mark.parametrize("dtype,g,block,B,H,G,force", [
+    ("bf16", 24, 8, 2, 16, 1, "sweep"), ("bf16", 48, 16, 1, 4, 1, "block"), ("bf16", 30, 5, 2, 3, 1, None),
+    ("f32", 28, 7, 1, 16, 1, None), ("bf16", 37, 8, 1, 2, 1, "sweep"), ("bf16", 20, 4, 2, 3, 3, None),
+    ("bf16", 1, 8, 1, 1, 1, None)])
+def test_attention_and_scores_in_one_call(nb, monkeypatch, dtype, g, block, B, H, G, force):
+    """ns_attn_forward_scores: the attention outputs and by-products are bit-equal to
+    ns_attn_forward's, and the scores (merged and computed in one launch) match the oracle."""
+    if force:
+        monkeypatch.setenv("NSATTN_KERNEL", force)
+    if G == 1:
+        q, k, v = synth.small_case(62, B, H, 64, g, g, dtype)
+    else:
+        rng = np.random.default_rng(62)
+        shape = (B, H, G + g * g, 64)
+        q, k, v = (synth.round_to_bf16(rng.standard_normal(shape).astype(np.float32)) for _ in range(3))
+    ref = oracle.cls_scores(q, k, 0.125, n_global=G) if G > 1 else oracle.cls_scores(q, k, 0.125)
+    dq, dk, dv = (to_dev(a, dtype) for a in (q, k, v))
+    out, logits, lse, scores = nb.ns_attn_forward_scores(dq, dk, dv, g, g, block, 0.125, n_global=G)
+    out2, logits2, lse2 = nb.ns_attn_forward(dq, dk, dv, g, g, block, 0.125, want_cls=True, n_global=G)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2) and torch.equal(logits, logits2) and torch.equal(lse, lse2)
+    np.testing.assert_allclose(to_np(scores), ref, rtol=2e-5, atol=1e-9)
+
+
 def topk_case(nb, scores, k):
     ref = oracle.topk(scores, k)
     kept, _, _ = nb.topk_filter(torch.from_numpy(scores).cuda(), k)
