@@ -238,7 +238,23 @@ def measure_vit_stack(nb, torch, np, synth, layers=24, dim=1024, mlp=4096, heads
         w = synth.make_block_weights(dim, mlp, seed=100 + i)
         ws.append({kk: (torch.from_numpy(vv).to(torch.bfloat16) if kk.startswith("w_") else torch.from_numpy(vv)).cuda()
                    for kk, vv in w.items()})
-    x = torch.randn(1, 1 + N, dim, device="cuda").to(torch.bfloat16)
+    # tokens from synthetic pixels through the backbone's patch embedding (14-pixel patches)
+    ps = 14
+    pixels = torch.randn(1, 3, g * ps, g * ps, device="cuda").to(torch.bfloat16)
+    w_patch = (torch.randn(dim, 3 * ps * ps, device="cuda") * 0.02).to(torch.bfloat16)
+    b_patch = torch.zeros(dim, device="cuda")
+    cls_token = (torch.randn(dim, device="cuda") * 0.02).to(torch.bfloat16)
+    pos_embed = (torch.randn(1 + N, dim, device="cuda") * 0.02).to(torch.bfloat16)
+    x = torch.empty(1, 1 + N, dim, device="cuda", dtype=torch.bfloat16)
+    nb.vit_embed(pixels, w_patch, b_patch, cls_token, pos_embed, ps, out=x)
+    torch.cuda.synchronize()
+    t = time.perf_counter()
+    for _ in range(5):
+        nb.vit_embed(pixels, w_patch, b_patch, cls_token, pos_embed, ps, out=x)
+    torch.cuda.synchronize()
+    dte = (time.perf_counter() - t) / 5
+    # (the blocks below see unit-variance tokens, as after a trained embedding)
+    x = (x.float() / x.float().std()).to(torch.bfloat16)
     import ctypes
     out = torch.empty((1, 1 + keep, dim), dtype=torch.bfloat16, device="cuda")
     wsb = torch.empty(6 << 30, dtype=torch.uint8, device="cuda")
@@ -268,6 +284,7 @@ def measure_vit_stack(nb, torch, np, synth, layers=24, dim=1024, mlp=4096, heads
     per_tok = 2.0 * dim * (3 * dim + dim + 2 * mlp)
     gemm_flops = per_tok * ((1 + N) * after + (1 + keep) * (layers - after))
     return {"vit_l24_forward_ms": dt * 1e3, "vit_l24_forward_graph_replay_ms": dtg * 1e3,
+            "vit_patch_embed_ms": dte * 1e3,
             "vit_l24_tokens_per_s": (1 + N) / dt,
             "vit_l24_gemm_tflops_if_all_gemm": gemm_flops / dt / 1e12, "vit_l24_kept": keep}
 

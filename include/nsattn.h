@@ -250,6 +250,27 @@ ns_status vit_forward_features(const ns_vit_desc *desc, const ns_vit_block_weigh
                                void *const *tap_out, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Tokenisation of the ViT backbone the blocks belong to (paper, "Settings": a ViT foundation model
+ * is the backbone; its input is the resized image): non-overlapping patch x patch pixel squares, one
+ * linear map per patch, a learned CLS token in front, learned position embeddings added.
+ *     x_out[b, 0, :]     = cls_token + pos_embed[0, :]
+ *     x_out[b, 1 + n, :] = w_patch . pixels(patch n of image b) + b_patch + pos_embed[1 + n, :]
+ * with patch n = (row n / grid_w, column n % grid_w) of the patch grid and the pixels of a patch in
+ * the order (channel, y, x), x fastest (the layout of a convolution weight [dim, channels, patch, patch]).
+ *   pixels     in  [B, channels, grid_h*patch, grid_w*patch] bf16
+ *   w_patch    in  [dim, channels*patch*patch] bf16         b_patch  in  [dim] fp32
+ *   cls_token  in  [dim] bf16                               pos_embed in [1 + grid_h*grid_w, dim] bf16
+ *   x_out      out [B, 1 + grid_h*grid_w, dim] bf16 (the x_in of vit_forward)
+ * fp32 accumulation, one rounding to bf16.  dim must be a multiple of 128.  w_patch, b_patch,
+ * pos_embed and x_out 16-byte aligned; workspace of vit_embed_workspace_bytes bytes, 256-byte aligned.
+ */
+size_t vit_embed_workspace_bytes(int32_t batch, int32_t channels, int32_t grid_h, int32_t grid_w, int32_t patch,
+                                 int32_t dim);
+ns_status vit_embed(int32_t batch, int32_t channels, int32_t grid_h, int32_t grid_w, int32_t patch, int32_t dim,
+                    const void *pixels, const void *w_patch, const float *b_patch, const void *cls_token,
+                    const void *pos_embed, void *x_out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Measurement aid for benchmarks (not part of the method): enqueues `reps` launches of the
  * patch-query attention kernel alone (the dominant kernel of ns_attn_forward; no CLS row)
  * on `stream`, bracketed by HIP events recorded on that stream, WAITS for them, and stores

@@ -29,6 +29,28 @@ def gelu(x):
     return 0.5 * x * (1.0 + _erf(x / math.sqrt(2.0)))
 
 
+def patch_embed(pixels, w_patch, b_patch, cls_token, pos_embed, patch):
+    """Tokenisation of the ViT backbone, written out from its definition in float64: the pixels
+    of patch (pr, pc), in the order (channel, y, x), times the projection matrix, plus bias and the
+    patch's position embedding; the CLS token (plus its position embedding) in front.
+    pixels [B,ch,gh*patch,gw*patch], w_patch [dim, ch*patch*patch], pos_embed [1+gh*gw, dim]
+    -> [B, 1+gh*gw, dim]."""
+    px = np.asarray(pixels, dtype=np.float64)
+    w = np.asarray(w_patch, dtype=np.float64)
+    pos = np.asarray(pos_embed, dtype=np.float64)
+    B, ch, hp, wp = px.shape
+    gh, gw, dim = hp // patch, wp // patch, w.shape[0]
+    out = np.empty((B, 1 + gh * gw, dim), dtype=np.float64)
+    out[:, 0, :] = np.asarray(cls_token, dtype=np.float64) + pos[0]
+    for b in range(B):
+        for pr in range(gh):
+            for pc in range(gw):
+                v = px[b, :, pr * patch:(pr + 1) * patch, pc * patch:(pc + 1) * patch].reshape(-1)
+                n = pr * gw + pc
+                out[b, 1 + n, :] = w @ v + np.asarray(b_patch, dtype=np.float64) + pos[1 + n]
+    return out
+
+
 def vit_block(x, w, grid_h, grid_w, block, heads, ln_eps=1e-6, scale=None, coords=None, want_scores=False,
               n_global=1):
     """x [B,T,dim]; w: dict of numpy arrays named as in the C ABI's ns_vit_block_weights."""

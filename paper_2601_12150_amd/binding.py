@@ -21,7 +21,7 @@ NS_F32, NS_BF16 = 0, 1
 
 EXPORTS = ["ns_attn_workspace_bytes", "ns_attn_forward", "cls_scores_workspace_bytes", "cls_scores",
            "cls_scores_from_logits", "ns_attn_forward_scores", "topk_filter_workspace_bytes", "topk_filter", "topk_filter_global", "vit_forward_features",
-           "vit_block_workspace_bytes", "vit_block_forward", "linear_forward", "vit_workspace_bytes", "vit_forward",
+           "vit_embed_workspace_bytes", "vit_embed", "vit_block_workspace_bytes", "vit_block_forward", "linear_forward", "vit_workspace_bytes", "vit_forward",
            "ns_attn_patch_kernel_time", "ns_attn_patch_kernel_name", "ns_last_error",
            "ns_version"]
 
@@ -73,6 +73,10 @@ def _load() -> ctypes.CDLL:
     lib.ns_attn_forward.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.ns_attn_forward_scores.restype = ctypes.c_int
     lib.ns_attn_forward_scores.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.vit_embed_workspace_bytes.restype = sz
+    lib.vit_embed_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32]
+    lib.vit_embed.restype = ctypes.c_int
+    lib.vit_embed.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.ns_attn_patch_kernel_time.restype = ctypes.c_int
     lib.ns_attn_patch_kernel_time.argtypes = [dp, vp, vp, vp, vp, vp, sz, i32,
                                               ctypes.POINTER(ctypes.c_float), vp]
@@ -311,6 +315,30 @@ def topk_filter(scores, k, x=None, coords=None, kept_idx=None, y=None, coords_ou
                                       _ptr(kept_idx), _ptr(y), _ptr(coords_out), _ptr(ws),
                                       0 if ws is None else ws.numel(), _stream(stream)))
     return kept_idx, y, coords_out
+
+
+def vit_embed(pixels, w_patch, b_patch, cls_token, pos_embed, patch, out=None, workspace=None, stream=None):
+    """Patch embedding: pixels [B,channels,gh*patch,gw*patch] bf16 -> tokens [B, 1+gh*gw, dim] bf16
+    (CLS token in front, position embeddings added).  w_patch [dim, channels*patch*patch] bf16,
+    b_patch [dim] fp32, cls_token [dim] bf16, pos_embed [1+gh*gw, dim] bf16."""
+    for name, t, dt in (("pixels", pixels, torch.bfloat16), ("w_patch", w_patch, torch.bfloat16),
+                        ("b_patch", b_patch, torch.float32), ("cls_token", cls_token, torch.bfloat16),
+                        ("pos_embed", pos_embed, torch.bfloat16)):
+        if t.dtype != dt or not t.is_contiguous():
+            raise ValueError("%s must be a contiguous %s tensor" % (name, dt))
+    B, ch, hp, wp = pixels.shape
+    if hp % patch or wp % patch:
+        raise ValueError("image sides must be multiples of the patch side")
+    gh, gw, dim = hp // patch, wp // patch, w_patch.shape[0]
+    if w_patch.shape[1] != ch * patch * patch or pos_embed.shape != (1 + gh * gw, dim):
+        raise ValueError("w_patch must be [dim, channels*patch*patch] and pos_embed [1+gh*gw, dim]")
+    if out is None:
+        out = torch.empty((B, 1 + gh * gw, dim), dtype=torch.bfloat16, device=pixels.device)
+    nbytes = lib.vit_embed_workspace_bytes(B, ch, gh, gw, patch, dim)
+    ws = _workspace(max(nbytes, 1), pixels.device, workspace)
+    _check(lib.vit_embed(B, ch, gh, gw, patch, dim, _ptr(pixels), _ptr(w_patch), _ptr(b_patch), _ptr(cls_token),
+                         _ptr(pos_embed), _ptr(out), _ptr(ws), ws.numel(), _stream(stream)))
+    return out
 
 
 WEIGHT_NAMES = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_proj", "b_proj", "ln2_g", "ln2_b",

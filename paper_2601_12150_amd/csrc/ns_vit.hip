@@ -265,6 +265,55 @@ __global__ __launch_bounds__(256) void patch_rows_kernel(const uint4 *x, uint4 *
 }
 
 // coords[b][j] = (r << 16 | c) of patch j of the full raster grid
+// Patch embedding, step 1: the pixels of every patch as one row of a matrix [B*N, Kp] bf16, column
+// (c * ps + py) * ps + px (the order of a convolution weight [dim, channels, ps, ps]), columns
+// K..Kp-1 zero.  One thread per 8 consecutive columns.
+__global__ __launch_bounds__(256) void patch_matrix_kernel(const uint16_t *pixels, uint16_t *a, int channels,
+                                                           int grid_h, int grid_w, int ps, int K, int Kp,
+                                                           long long total8) {
+  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (t >= total8) return;
+  const int per_row = Kp / 8;
+  const long long row = t / per_row;                 // b * N + patch
+  const int col0 = (int)(t - row * per_row) * 8;
+  const int N = grid_h * grid_w;
+  const int b = (int)(row / N), n = (int)(row - (long long)b * N);
+  const int pr = n / grid_w, pc = n - pr * grid_w;
+  const long long W = (long long)grid_w * ps, plane = (long long)grid_h * ps * W;
+  const uint16_t *img = pixels + (long long)b * channels * plane;
+  uint16_t v[8];
+#pragma unroll
+  for (int e = 0; e < 8; e++) {
+    const int col = col0 + e;
+    uint16_t x = 0;
+    if (col < K) {
+      const int c = col / (ps * ps), rem = col - c * ps * ps, py = rem / ps, px = rem - py * ps;
+      x = img[c * plane + ((long long)pr * ps + py) * W + (long long)pc * ps + px];
+    }
+    v[e] = x;
+  }
+  uint4 u = {(uint32_t)v[0] | ((uint32_t)v[1] << 16), (uint32_t)v[2] | ((uint32_t)v[3] << 16),
+             (uint32_t)v[4] | ((uint32_t)v[5] << 16), (uint32_t)v[6] | ((uint32_t)v[7] << 16)};
+  *reinterpret_cast<uint4 *>(a + row * Kp + col0) = u;
+}
+
+// rows [rows, K] -> [rows, Kp], new columns zero (the projection weight, when K is no multiple of 64)
+__global__ __launch_bounds__(256) void pad_columns_kernel(const uint16_t *w, uint16_t *wp, int rows, int K, int Kp) {
+  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (t >= (long long)rows * Kp) return;
+  const int r = (int)(t / Kp), c = (int)(t - (long long)r * Kp);
+  wp[t] = c < K ? w[(long long)r * K + c] : (uint16_t)0;
+}
+
+// x[b, 0, :] = cls_token + pos_embed[0, :]
+__global__ __launch_bounds__(256) void cls_rows_kernel(const uint16_t *cls, const uint16_t *pos, uint16_t *x,
+                                                       int dim, long long image_stride) {
+  const int d = blockIdx.x * 256 + threadIdx.x;
+  if (d >= dim) return;
+  const float v = bf16_lo((uint32_t)cls[d]) + bf16_lo((uint32_t)pos[d]);
+  x[(long long)blockIdx.y * image_stride + d] = (uint16_t)(pack_bf16(v, 0.f) & 0xffffu);
+}
+
 __global__ __launch_bounds__(256) void raster_coords_kernel(int32_t *coords, int n, int grid_w) {
   const int j = blockIdx.x * 256 + threadIdx.x;
   if (j < n) coords[(size_t)blockIdx.y * n + j] = ((j / grid_w) << 16) | (j % grid_w);
@@ -386,6 +435,72 @@ size_t vit_workspace_bytes(const ns_vit_desc *desc) {
   const size_t bw = vit_block_workspace_bytes(&desc->block);   // the full grid needs the most
   if (bw == 0) return 0;
   return stack_layout(*desc, bw).total;
+}
+
+static ns_status check_embed(int32_t batch, int32_t channels, int32_t grid_h, int32_t grid_w, int32_t patch,
+                             int32_t dim) {
+  if (batch < 1 || channels < 1 || grid_h < 1 || grid_w < 1 || patch < 1)
+    return fail(NS_ERR_INVALID_ARG, "batch, channels, grid and patch must be positive");
+  if (dim < 128 || dim % 128) return fail(NS_ERR_UNSUPPORTED, "dim %d: a positive multiple of 128", dim);
+  const long long K = (long long)channels * patch * patch, N = (long long)grid_h * grid_w;
+  if (K > 65536 || N * align_up((size_t)K, 64) * 2 >= 0x7fffffffLL)
+    return fail(NS_ERR_UNSUPPORTED, "patch matrix of one image beyond 2 GiB");
+  if ((long long)batch * N >= 0x7fffffffLL) return fail(NS_ERR_UNSUPPORTED, "too many patches");
+  return NS_OK;
+}
+
+size_t vit_embed_workspace_bytes(int32_t batch, int32_t channels, int32_t grid_h, int32_t grid_w, int32_t patch,
+                                 int32_t dim) {
+  if (check_embed(batch, channels, grid_h, grid_w, patch, dim) != NS_OK) return 0;
+  const size_t K = (size_t)channels * patch * patch, Kp = align_up(K, 64);
+  return align_up((size_t)batch * grid_h * grid_w * Kp * 2, 256) + align_up((size_t)dim * Kp * 2, 256);
+}
+
+ns_status vit_embed(int32_t batch, int32_t channels, int32_t grid_h, int32_t grid_w, int32_t patch, int32_t dim,
+                    const void *pixels, const void *w_patch, const float *b_patch, const void *cls_token,
+                    const void *pos_embed, void *x_out, void *workspace, size_t workspace_bytes, void *stream) {
+  ns_status st = check_embed(batch, channels, grid_h, grid_w, patch, dim);
+  if (st != NS_OK) return st;
+  if (!pixels || !w_patch || !b_patch || !cls_token || !pos_embed || !x_out)
+    return fail(NS_ERR_INVALID_ARG, "pixels, weights, cls_token, pos_embed and x_out must not be NULL");
+  const uintptr_t bits = reinterpret_cast<uintptr_t>(w_patch) | reinterpret_cast<uintptr_t>(b_patch) |
+                         reinterpret_cast<uintptr_t>(pos_embed) | reinterpret_cast<uintptr_t>(x_out);
+  if (bits % 16 || reinterpret_cast<uintptr_t>(pixels) % 2 || reinterpret_cast<uintptr_t>(cls_token) % 2)
+    return fail(NS_ERR_INVALID_ARG, "w_patch, b_patch, pos_embed and x_out must be 16-byte aligned");
+  const size_t need = vit_embed_workspace_bytes(batch, channels, grid_h, grid_w, patch, dim);
+  if (!workspace) return fail(NS_ERR_WORKSPACE, "workspace is NULL, %zu bytes needed", need);
+  if (reinterpret_cast<uintptr_t>(workspace) % 256) return fail(NS_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+  if (workspace_bytes < need) return fail(NS_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int N = grid_h * grid_w, K = channels * patch * patch, Kp = (int)align_up((size_t)K, 64);
+  uint16_t *a = static_cast<uint16_t *>(workspace);
+  uint16_t *wp = reinterpret_cast<uint16_t *>(static_cast<unsigned char *>(workspace) +
+                                              align_up((size_t)batch * N * Kp * 2, 256));
+  const uint16_t *w = static_cast<const uint16_t *>(w_patch);
+  const long long total8 = (long long)batch * N * (Kp / 8);
+  hipLaunchKernelGGL(patch_matrix_kernel, dim3((unsigned)((total8 + 255) / 256)), dim3(256), 0, s,
+                     static_cast<const uint16_t *>(pixels), a, channels, grid_h, grid_w, patch, K, Kp, total8);
+  st = check_launch("patch_matrix_kernel");
+  if (st != NS_OK) return st;
+  if (Kp != K) {
+    hipLaunchKernelGGL(pad_columns_kernel, dim3((unsigned)(((long long)dim * Kp + 255) / 256)), dim3(256), 0, s, w, wp,
+                       dim, K, Kp);
+    st = check_launch("pad_columns_kernel");
+    if (st != NS_OK) return st;
+    w = wp;
+  }
+  const uint16_t *pos = static_cast<const uint16_t *>(pos_embed);
+  uint16_t *x = static_cast<uint16_t *>(x_out);
+  const long long image_stride = (long long)(1 + N) * dim;
+  for (int b = 0; b < batch; b++) {
+    // rows 1..N of image b: projection + bias, the position embeddings ride in as the residual
+    st = launch_gemm(a + (size_t)b * N * Kp, w, b_patch, pos + dim, x + b * image_stride + dim, N, dim, Kp, false, s);
+    if (st != NS_OK) return st;
+  }
+  hipLaunchKernelGGL(cls_rows_kernel, dim3((dim + 255) / 256, batch), dim3(256), 0, s,
+                     static_cast<const uint16_t *>(cls_token), pos, x, dim, image_stride);
+  return check_launch("cls_rows_kernel");
 }
 
 ns_status linear_forward(int32_t M, int32_t N, int32_t K, const void *x, const void *w, const float *bias,

@@ -109,6 +109,20 @@ def test_topk_and_scores_validation(nb):
     assert L.cls_scores_workspace_bytes(ctypes.byref(d)) > 0
 
 
+def test_embed_validation(nb):
+    L = nb.lib
+    assert L.vit_embed_workspace_bytes(1, 3, 128, 128, 14, 1024) == 16384 * 640 * 2 + 1024 * 640 * 2   # 588 -> 640 columns
+    assert L.vit_embed_workspace_bytes(1, 3, 8, 8, 16, 100) == 0                                      # dim % 128
+    def call(B=1, ch=3, gh=8, gw=8, ps=14, dim=512, px=FAKE, w=FAKE, ws=FAKE, ws_bytes=1 << 30):
+        return L.vit_embed(B, ch, gh, gw, ps, dim, px, w, FAKE, FAKE, FAKE, FAKE, ws, ws_bytes, None)
+    assert call(B=0) == nb.NS_ERR_INVALID_ARG
+    assert call(dim=100) == nb.NS_ERR_UNSUPPORTED
+    assert call(px=None) == nb.NS_ERR_INVALID_ARG
+    assert call(w=ctypes.c_void_p(0x10008)) == nb.NS_ERR_INVALID_ARG          # misaligned
+    assert call(ws=None) == nb.NS_ERR_WORKSPACE
+    assert call(ws_bytes=1024) == nb.NS_ERR_WORKSPACE
+
+
 def test_kernel_choice_policy(nb, monkeypatch):
     """Which kernel serves which problem (host logic; without a device the CU count defaults to 256)."""
     monkeypatch.delenv("NSATTN_KERNEL", raising=False)

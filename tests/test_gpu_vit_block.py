@@ -124,6 +124,33 @@ def test_stack_pruning_of_a_long_sequence(nb):
     assert torch.equal(out, out2)
 
 
+@pytest.mark.parametrize("B,ch,gh,gw,ps,dim", [(2, 3, 20, 24, 14, 512), (1, 3, 16, 16, 16, 1024), (1, 1, 3, 5, 7, 128),
+                                               (3, 3, 1, 1, 14, 256), (1, 3, 40, 33, 14, 1024)])
+def test_patch_embedding_matches_oracle(nb, B, ch, gh, gw, ps, dim):
+    """Tokenisation: 14-pixel patches (588 columns, padded to 640 inside) and 16-pixel patches (768),
+    grids from one patch to more than a thousand, the CLS row, position embeddings as residual."""
+    rng = np.random.default_rng(gh * 100 + gw)
+    r = synth.round_to_bf16
+    px = r(rng.standard_normal((B, ch, gh * ps, gw * ps)).astype(np.float32))
+    w = r((rng.standard_normal((dim, ch * ps * ps)) * 0.05).astype(np.float32))
+    b = (rng.standard_normal(dim) * 0.1).astype(np.float32)
+    cls = r(rng.standard_normal(dim).astype(np.float32))
+    pos = r((rng.standard_normal((1 + gh * gw, dim)) * 0.5).astype(np.float32))
+    bf = lambda a: torch.from_numpy(a).to(torch.bfloat16).cuda()
+    out = nb.vit_embed(bf(px), bf(w), torch.from_numpy(b).cuda(), bf(cls), bf(pos), ps)
+    torch.cuda.synchronize()
+    ref = ov.patch_embed(px, w, b, cls, pos, ps)
+    assert_attn_close(to_np(out), ref, "bf16", "patch embedding %dx%d, patch %d" % (gh, gw, ps))
+    # and it feeds the stack: one block on the embedded tokens equals the block on the oracle's tokens
+    if dim >= 512 and gh * gw >= 64:
+        heads = dim // 64
+        wb = synth.make_block_weights(dim, dim, seed=3)
+        y = nb.vit_block_forward(out, dev_weights(wb), gh, gw, 8, heads)
+        torch.cuda.synchronize()
+        assert_attn_close(to_np(y), ov.vit_block(to_np(out).astype(np.float64), wb, gh, gw, 8, heads), "bf16",
+                          "block on embedded tokens")
+
+
 def test_stack_without_pruning_equals_repeated_blocks(nb):
     B, g, block, heads, dim, mlp = 1, 16, 8, 8, 512, 512
     rng = np.random.default_rng(22)

@@ -39,3 +39,38 @@ def test_layer_norm_and_gelu_special_values():
     np.testing.assert_allclose(ov.gelu(np.array([0.0, 1e3, -1e3])), [0.0, 1e3, 0.0], atol=1e-12)
     # gelu(1) = 0.5 * (1 + erf(1/sqrt 2)) = Phi(1)
     np.testing.assert_allclose(ov.gelu(np.array([1.0])), [0.8413447460685429], atol=1e-15)
+
+
+def test_patch_embed_equals_library_strided_convolution():
+    """The tokenisation is a convolution with kernel = stride = patch side (library routine, fp64),
+    flattened in raster order, with the CLS token in front and the position embeddings added."""
+    rng = np.random.default_rng(5)
+    B, ch, gh, gw, ps, dim = 2, 3, 3, 5, 4, 16
+    px = rng.standard_normal((B, ch, gh * ps, gw * ps))
+    w = rng.standard_normal((dim, ch * ps * ps))
+    b = rng.standard_normal(dim)
+    cls = rng.standard_normal(dim)
+    pos = rng.standard_normal((1 + gh * gw, dim))
+    got = ov.patch_embed(px, w, b, cls, pos, ps)
+    conv = torch.nn.functional.conv2d(torch.from_numpy(px), torch.from_numpy(w.reshape(dim, ch, ps, ps)),
+                                      torch.from_numpy(b), stride=ps)          # [B, dim, gh, gw]
+    want = conv.flatten(2).transpose(1, 2).numpy() + pos[1:]
+    np.testing.assert_allclose(got[:, 1:], want, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(got[:, 0], np.broadcast_to(cls + pos[0], (B, dim)), rtol=0, atol=0)
+
+
+def test_patch_embed_one_hot_projection_picks_single_pixels():
+    """A projection row that is one-hot at (channel c, y, x) must return exactly that pixel of every
+    patch: pins the (channel, y, x) order and the raster order of the patches."""
+    rng = np.random.default_rng(6)
+    B, ch, gh, gw, ps = 1, 2, 2, 3, 3
+    px = rng.standard_normal((B, ch, gh * ps, gw * ps))
+    picks = [(0, 0, 0), (1, 2, 1), (0, 1, 2), (1, 0, 2)]
+    w = np.zeros((len(picks), ch * ps * ps))
+    for i, (c, y, x) in enumerate(picks):
+        w[i, (c * ps + y) * ps + x] = 1.0
+    got = ov.patch_embed(px, w, np.zeros(len(picks)), np.zeros(len(picks)), np.zeros((1 + gh * gw, len(picks))), ps)
+    for pr in range(gh):
+        for pc in range(gw):
+            for i, (c, y, x) in enumerate(picks):
+                assert got[0, 1 + pr * gw + pc, i] == px[0, c, pr * ps + y, pc * ps + x]
