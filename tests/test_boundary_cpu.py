@@ -82,6 +82,19 @@ def test_pointer_and_workspace_validation(nb):
     assert b"needed" in nb.lib.ns_last_error()
 
 
+def test_forward_scores_validation(nb):
+    L, d = nb.lib, good_desc(nb)
+    out, ws = ctypes.c_void_p(0x20000), ctypes.c_void_p(0x30000)
+    def call(logits=FAKE, scores=FAKE, desc=d):
+        return L.ns_attn_forward_scores(ctypes.byref(desc), FAKE, FAKE, FAKE, out, logits, None, scores, ws, 1 << 30, None)
+    assert call(logits=None) == nb.NS_ERR_INVALID_ARG            # the scoring reads the logits back
+    assert call(scores=None) == nb.NS_ERR_INVALID_ARG
+    assert call(scores=ctypes.c_void_p(0x10002)) == nb.NS_ERR_INVALID_ARG
+    bad = good_desc(nb)
+    bad.heads = 0
+    assert call(desc=bad) == nb.NS_ERR_INVALID_ARG
+
+
 def test_topk_and_scores_validation(nb):
     L = nb.lib
     args = dict(x=None, C=0, dt=nb.NS_BF16, cin=None, kept=FAKE, y=None, cout=None)
