@@ -112,3 +112,14 @@ def test_block16_kernel_addresses_with_larger_blocks(gh, gw, bm):
 @pytest.mark.parametrize("gh,gw", [(20, 27), (9, 9), (8, 100), (17, 8), (1, 1), (5, 5), (12, 30), (23, 33)])
 def test_sweep_kernel_addresses_stay_in_bounds(gh, gw):
     assert check_sweep(gh, gw) == 0
+
+
+def test_addresses_stay_in_bounds_on_random_grids():
+    """A seeded sample of grid shapes (sides 1..75) through both address models, with blocks of one,
+    two and four 16x16 squares for the block kernel."""
+    import random
+    rng = random.Random(2024)
+    for _ in range(24):
+        gh, gw = rng.randint(1, 75), rng.randint(1, 75)
+        assert check_sweep(gh, gw) == 0, (gh, gw)
+        assert check_block16(gh, gw, rng.choice([1, 2, 4])) == 0, (gh, gw)
