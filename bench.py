@@ -214,7 +214,17 @@ def measure_stages(nb, torch, sets, cfg, g, blk, k, C, B, H, T, D, ws, desc0, fl
                                                     workspace=ws))
     bytes_scores = B * H * T * D * elt + B * H * T * 4 * 2 + B * (T - 1) * 4
     bytes_gather = 2 * B * (1 + k) * C * elt + B * k * 4
+    # supplementary, outside the workloads: the selection alone on a batch that fills the chip
+    # (256 images x 16,384 scores, one workgroup per image), as a streaming rate
+    nb_img, nb_n = 256, 16384
+    nb_k = (nb_n * 60 + 99) // 100
+    bs = torch.rand((nb_img, nb_n), device="cuda", dtype=torch.float32)
+    bkept = torch.empty((nb_img, nb_k), dtype=torch.int32, device="cuda")
+    t_batched = time_call(lambda s: nb.topk_filter(bs, nb_k, kept_idx=bkept))
+    bytes_batched = nb_img * nb_n * 4 + nb_img * nb_k * 4
     return {
+        "topk_select_256x16384_ms": t_batched * 1e3,
+        "topk_select_256x16384_GBps": bytes_batched / t_batched / 1e9,
         "ns_attn_forward_ms": t_attn * 1e3,
         "ns_attn_forward_tflops_sparse": flops_layer / t_attn / 1e12,
         "cls_scores_standalone_ms": t_scores * 1e3,
@@ -230,7 +240,7 @@ def measure_stages(nb, torch, sets, cfg, g, blk, k, C, B, H, T, D, ws, desc0, fl
 def measure_vit_stack(nb, torch, np, synth, layers=24, dim=1024, mlp=4096, heads=16, g=128, blk=8, after=12):
     """24 pre-LN blocks on [1, 1+128*128, 1024] bf16 tokens, pruning to 60 % after block 12.  Weights are
     random (N(0, 0.02^2)); one set is generated and uploaded per layer.  The input tokens are synthetic
-    N(0,1) embeddings (the patch embedding itself is not part of this build)."""
+    pixels through vit_embed."""
     N = g * g
     keep = (N * 60 + 99) // 100
     ws = []
