@@ -39,8 +39,7 @@ def test_step_graph_replays_match_eager(nb, g, block, H):
         x.copy_(_bf16(np.random.default_rng(seed).standard_normal((B, T, C)).astype(np.float32)))
 
     def step():          # tensors the binding allocates while recording belong to the graph's pool
-        out, logits, lse = nb.ns_attn_forward(q, kk, v, g, g, block, 0.125, want_cls=True)
-        scores = nb.cls_scores_from_logits(logits, lse)
+        out, logits, lse, scores = nb.ns_attn_forward_scores(q, kk, v, g, g, block, 0.125)
         kept, y, _ = nb.topk_filter(scores, k, x=x, workspace=ws_sel)
         return [out, logits, lse, scores, kept, y]
 
