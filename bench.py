@@ -291,10 +291,42 @@ def measure_vit_stack(nb, torch, np, synth, layers=24, dim=1024, mlp=4096, heads
         graph.replay()
     torch.cuda.synchronize()
     dtg = (time.perf_counter() - t) / n
+    # reference point for the block's four linear maps (not part of the path): the vendor library
+    # through torch.nn.functional.linear, with the activation and the residual as separate torch ops,
+    # against linear_forward on the same full-sequence shapes
+    def t_us(fn, reps=10):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / reps * 1e6
+    M = 1 + N
+    mine_us = lib_us = 0.0
+    for (n_out, k_in, gelu, res) in ((3 * dim, dim, False, False), (dim, dim, False, True), (mlp, dim, True, False),
+                                     (dim, mlp, False, True)):
+        xa = torch.randn(M, k_in, device="cuda").to(torch.bfloat16)
+        wa = (torch.randn(n_out, k_in, device="cuda") * 0.02).to(torch.bfloat16)
+        ba = torch.zeros(n_out, device="cuda")
+        bb = ba.to(torch.bfloat16)
+        ra = torch.randn(M, n_out, device="cuda").to(torch.bfloat16) if res else None
+        ya = torch.empty(M, n_out, device="cuda", dtype=torch.bfloat16)
+        mine_us += t_us(lambda: nb.linear_forward(xa, wa, ba, ra, gelu=gelu, out=ya))
+
+        def lib():
+            z = torch.nn.functional.linear(xa, wa, bb)
+            if gelu:
+                z = torch.nn.functional.gelu(z)
+            return z + ra if res else z
+        lib_us += t_us(lib)
+        del xa, wa, ra, ya
     per_tok = 2.0 * dim * (3 * dim + dim + 2 * mlp)
     gemm_flops = per_tok * ((1 + N) * after + (1 + keep) * (layers - after))
     return {"vit_l24_forward_ms": dt * 1e3, "vit_l24_forward_graph_replay_ms": dtg * 1e3,
             "vit_patch_embed_ms": dte * 1e3,
+            "vit_layer_linear_maps_us": mine_us, "vit_layer_linear_maps_vendor_library_us": lib_us,
             "vit_l24_tokens_per_s": (1 + N) / dt,
             "vit_l24_gemm_tflops_if_all_gemm": gemm_flops / dt / 1e12, "vit_l24_kept": keep}
 
