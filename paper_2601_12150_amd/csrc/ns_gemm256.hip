@@ -38,7 +38,8 @@ struct Gemm256Params {
   int gelu;
   int ntn, ntm;      // tiles along n and m
   int extended;      // the last row tile has 288 rows
-  int tm;            // token rows per tile: 256, or 192 (three slabs per wave) where that fills the chip better
+  int n256;          // the first n256 rows of tiles have 256 token rows, the others 192 (three slabs per wave):
+                     // the mix that fills the chip's rounds of workgroups best
 };
 
 constexpr int kStageW = 256 * 128;           // bytes: 256 weight rows x 64 k
@@ -277,14 +278,16 @@ __global__ __launch_bounds__(256) void gemm256_bf16_kernel(Gemm256Params p) {
   // fastest) so that the tiles sharing token rows and the weight matrix meet in one L2
   const int total = p.ntn * p.ntm;
   int bid = blockIdx.x;
-  if (total % 8 == 0) bid = (bid & 7) * (total / 8) + (bid >> 3);
+  const bool uniform = p.n256 == 0 || p.n256 == p.ntm;     // (a mix of tile heights keeps the launch order: tall tiles first)
+  if (uniform && total % 8 == 0) bid = (bid & 7) * (total / 8) + (bid >> 3);
   const int bm = bid / p.ntn, bn = bid - bm * p.ntn;
-  const int m0 = bm * p.tm, n0 = bn * 256;
+  const int tm = bm < p.n256 ? 256 : 192;
+  const int m0 = bm < p.n256 ? bm * 256 : p.n256 * 256 + (bm - p.n256) * 192, n0 = bn * 256;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
   const bool ext = p.extended && bm == p.ntm - 1;
   const int wm = wave >> 1;
-  const int wrows = p.tm >> 1;
+  const int wrows = tm >> 1;
   const int rows = min(p.M - (m0 + wm * wrows), wrows);   // may be <= 0
   const int ntj = __builtin_amdgcn_readfirstlane(rows <= 0 ? 0 : (rows + 31) / 32);
   if (ext) {   // the extended tile is full: 256 + (1..32) rows
@@ -292,7 +295,7 @@ __global__ __launch_bounds__(256) void gemm256_bf16_kernel(Gemm256Params p) {
     else gemm256_wave<4, true, 0, GELU, RES>(p, smem, m0, n0, wave, lane);
     return;
   }
-  if (p.tm == 192) {
+  if (tm == 192) {
     switch (ntj) {
       case 3: gemm256_wave<3, false, 0, GELU, RES, 192>(p, smem, m0, n0, wave, lane); break;
       case 2: gemm256_wave<2, false, 0, GELU, RES, 192>(p, smem, m0, n0, wave, lane); break;
@@ -321,13 +324,15 @@ ns_status launch_gemm256(const uint16_t *a, const uint16_t *w, const float *bias
   if (!gemm256_supported(M, N, K)) return fail(NS_ERR_UNSUPPORTED, "GEMM shape M=%d N=%d K=%d", M, N, K);
   if ((long long)M * K * 2 >= 0x7fffffffLL || (long long)N * K * 2 >= 0x7fffffffLL)
     return fail(NS_ERR_UNSUPPORTED, "GEMM operand beyond 2 GiB");
-  Gemm256Params p{a, w, r, bias, c, M, N, K, gelu ? 1 : 0, N / 256, 0, 0, 256};
+  Gemm256Params p{a, w, r, bias, c, M, N, K, gelu ? 1 : 0, N / 256, 0, 0, 0};
   const int q = M / 256, rem = M % 256;
   p.extended = (rem > 0 && rem <= 32) ? 1 : 0;
   p.ntm = (rem == 0 || p.extended) ? q : q + 1;
-  p.tm = 256;
+  p.n256 = p.ntm;
   {
-    // rounds of workgroups x rows per tile: 192-row tiles where they shorten the launch
+    // Rows of tiles: a of 256 token rows, then b of 192, a*256 + b*192 >= M.  Workgroups start in
+    // launch order, a CU takes the next one when it is free: the mix with the shortest makespan
+    // (a 192-row tile costs 0.8 of a 256-row one).
     static int cus = 0;
     if (cus == 0) {
       int dev = 0;
@@ -335,10 +340,37 @@ ns_status launch_gemm256(const uint16_t *a, const uint16_t *w, const float *bias
       cus = (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
                 ? prop.multiProcessorCount : 256;
     }
-    const long long ntm192 = (M + 191) / 192;
-    const long long cost256 = ((long long)p.ntm * p.ntn + cus - 1) / cus * 256;
-    const long long cost192 = (ntm192 * p.ntn + cus - 1) / cus * 192;
-    if (cost192 < cost256) { p.tm = 192; p.ntm = (int)ntm192; p.extended = 0; }
+    auto makespan = [&](long long na, long long nb) -> double {
+      // na*ntn tiles of cost 1.0, then nb*ntn of cost 0.8, each given to the unit that is free first.
+      // After the tall tiles n2 units are free at t2 and the other n1 one tile time earlier, at t1.
+      const long long ta = na * p.ntn;
+      long long left = nb * p.ntn;
+      const long long n2 = ta % cus, n1 = cus - n2;
+      double t1 = (double)(ta / cus), t2 = t1 + 1.0;
+      double end = n2 ? t2 : t1;
+      while (left > 0) {
+        if (n2 == 0 || t1 <= t2) {
+          left -= std::min(left, n1);
+          t1 += 0.8;
+          end = std::max(end, t1);
+        } else {
+          left -= std::min(left, n2);
+          t2 += 0.8;
+          end = std::max(end, t2);
+        }
+      }
+      return end;
+    };
+    double best = makespan(p.ntm, 0);    // (the ninth slab of an extended tile is not counted: it is cheap)
+    int best_a = p.ntm, best_b = 0;
+    const int max_b = (M + 191) / 192;
+    for (int nb = 1; nb <= max_b; nb++) {
+      const long long covered = (long long)nb * 192;
+      const int na = covered >= M ? 0 : (int)((M - covered + 255) / 256);
+      const double t = makespan(na, nb);
+      if (t < best - 1e-9) { best = t; best_a = na; best_b = nb; }
+    }
+    if (best_b > 0) { p.n256 = best_a; p.ntm = best_a + best_b; p.extended = 0; }
   }
   const long long wgs = (long long)p.ntm * p.ntn;
   if (wgs > 0x7fffffffLL) return fail(NS_ERR_UNSUPPORTED, "GEMM grid too large");

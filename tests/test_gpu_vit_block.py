@@ -198,6 +198,9 @@ def test_stack_feature_maps(nb):
     (300, 768, 2048, True, True),       # remainder 44 -> partial tile with two slabs; long k
     (1154, 640, 512, False, True),      # N not a multiple of 256: the 128 x 128 kernel
     (37, 128, 64, True, True),          # fewer rows than any tile
+    (9832, 4096, 128, False, True),     # more tiles than CUs: 19 rows of 256-row tiles, then 26 rows of 192-row tiles
+    (7000, 4096, 64, False, False),     # 16 rows of each
+    (12000, 2048, 64, False, True),     # 2 rows of 256-row tiles, then 60 of 192-row tiles
 ])
 def test_linear_forward(nb, M, N, K, gelu, res):
     """The fused linear map against float64 matmul / erf GELU on the same bf16 inputs."""
