@@ -124,6 +124,19 @@ size_t cls_scores_workspace_bytes(const ns_attn_desc *desc);
 ns_status cls_scores(const ns_attn_desc *desc, const void *q, const void *k, float *scores,
                      void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * cls_scores for callers that cannot allocate device memory or pass a workspace: code recorded
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * and results as cls_scores (same kernels), but the scratch memory is a buffer inside the library
+ * (cls_scores_static_max_bytes() bytes per GPU, 8 MiB, held until the process ends).  The call
+ * allocates and frees nothing.  A problem whose cls_scores_workspace_bytes exceeds the buffer is
+ * rejected with NS_ERR_WORKSPACE before anything is launched.  All calls on one GPU share the
+ * buffer: calls that may overlap in time on the same GPU (different streams, different threads)
+ * race and must be serialised by the caller; calls on one stream are ordered and safe.
+ */
+size_t cls_scores_static_max_bytes(void);
+ns_status cls_scores_static(const ns_attn_desc *desc, const void *q, const void *k, float *scores, void *stream);
+
 /* The same scores from ns_attn_forward's by-products: logits [B,H,G,T], lse [B,H,G]. */
 ns_status cls_scores_from_logits(int32_t batch, int32_t heads, int32_t tokens, int32_t n_global,
                                  const float *cls_logits, const float *cls_lse, float *scores,

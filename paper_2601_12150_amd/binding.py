@@ -20,6 +20,7 @@ NS_OK, NS_ERR_INVALID_ARG, NS_ERR_UNSUPPORTED, NS_ERR_WORKSPACE, NS_ERR_HIP = ra
 NS_F32, NS_BF16 = 0, 1
 
 EXPORTS = ["ns_attn_workspace_bytes", "ns_attn_forward", "cls_scores_workspace_bytes", "cls_scores",
+           "cls_scores_static_max_bytes", "cls_scores_static",
            "cls_scores_from_logits", "ns_attn_forward_scores", "topk_filter_workspace_bytes", "topk_filter", "topk_filter_global", "vit_forward_features",
            "vit_embed_workspace_bytes", "vit_embed", "vit_block_workspace_bytes", "vit_block_forward", "linear_forward", "vit_workspace_bytes", "vit_forward",
            "ns_attn_patch_kernel_time", "ns_attn_patch_kernel_name", "ns_last_error",
@@ -86,6 +87,10 @@ def _load() -> ctypes.CDLL:
     lib.cls_scores_workspace_bytes.argtypes = [dp]
     lib.cls_scores.restype = ctypes.c_int
     lib.cls_scores.argtypes = [dp, vp, vp, vp, vp, sz, vp]
+    lib.cls_scores_static_max_bytes.restype = sz
+    lib.cls_scores_static_max_bytes.argtypes = []
+    lib.cls_scores_static.restype = ctypes.c_int
+    lib.cls_scores_static.argtypes = [dp, vp, vp, vp, vp]
     lib.cls_scores_from_logits.restype = ctypes.c_int
     lib.cls_scores_from_logits.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp]
     lib.topk_filter_workspace_bytes.restype = sz
@@ -260,6 +265,18 @@ def cls_scores(q, k, scale=None, n_global=1, scores=None, workspace=None, stream
     ws = _workspace(nbytes, q.device, workspace)
     _check(lib.cls_scores(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(scores), _ptr(ws),
                           0 if ws is None else ws.numel(), _stream(stream)))
+    return scores
+
+
+def cls_scores_static(q, k, scale=None, n_global=1, scores=None, stream=None):
+    """cls_scores on the library's own scratch buffer: the call allocates nothing when `scores` is given."""
+    if not (q.shape == k.shape and q.stride() == k.stride() and q.dtype == k.dtype):
+        raise ValueError("q and k must have the same shape, strides and dtype")
+    B, H, T, D = q.shape
+    desc = make_desc(q, 1, T - n_global, 1, scale, None, None, 1, n_global)
+    if scores is None:
+        scores = torch.empty((B, T - n_global), dtype=torch.float32, device=q.device)
+    _check(lib.cls_scores_static(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(scores), _stream(stream)))
     return scores
 
 

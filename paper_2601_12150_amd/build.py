@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libnsattn.so")
 SOURCES = ["ns_api.hip", "ns_attn_generic.hip", "ns_attn_mfma.hip", "ns_attn_persist.hip", "ns_attn_sweep.hip", "ns_attn_block16.hip", "ns_attn_ragged.hip", "ns_gemm256.hip", "ns_cls.hip", "ns_topk.hip",
-           "ns_vit.hip"]
+           "ns_vit.hip", "ns_static.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # keep packed-fp32 VALU ops out

@@ -248,6 +248,26 @@ ns_status ns_attn_forward_scores(const ns_attn_desc *desc, const void *q, const 
 
 }  // extern "C"
 
+ns_status ns::cls_scores_impl(const ns_attn_desc *desc, const void *q, const void *k, float *scores,
+                              void *workspace, size_t workspace_bytes, void *stream) {
+  ns_status st = validate_desc(desc, false, false);
+  if (st != NS_OK) return st;
+  if (!q || !k || !scores) return fail(NS_ERR_INVALID_ARG, "q, k and scores must not be NULL");
+  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(scores, 4))
+    return fail(NS_ERR_INVALID_ARG, "q and k must be 16-byte aligned, scores 4-byte aligned");
+  const ns_attn_desc &d = *desc;
+  st = check_workspace(workspace, workspace_bytes, cls_scores_workspace_bytes(desc));
+  if (st != NS_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  float *logits = static_cast<float *>(workspace);
+  float *partials = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) +
+                                              align_up((size_t)d.batch * d.heads * d.n_global * d.tokens * 4, 256));
+  st = launch_cls_row(d, q, k, nullptr, logits, partials, false, s);
+  if (st != NS_OK) return st;
+  return launch_cls_scores(d.batch, d.heads, d.tokens, d.n_global, logits, nullptr, partials,
+                           cls_num_chunks(d.tokens), scores, s);
+}
+
 ns_status ns::attn_forward_impl(const ns_attn_desc *desc, const void *q, const void *k, const void *v,
                                 void *out, float *cls_logits, float *cls_lse, float *scores, void *workspace,
                                 size_t workspace_bytes, void *stream, bool reuse_lists) {
@@ -325,22 +345,7 @@ size_t cls_scores_workspace_bytes(const ns_attn_desc *desc) {
 
 ns_status cls_scores(const ns_attn_desc *desc, const void *q, const void *k, float *scores,
                      void *workspace, size_t workspace_bytes, void *stream) {
-  ns_status st = validate_desc(desc, false, false);
-  if (st != NS_OK) return st;
-  if (!q || !k || !scores) return fail(NS_ERR_INVALID_ARG, "q, k and scores must not be NULL");
-  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(scores, 4))
-    return fail(NS_ERR_INVALID_ARG, "q and k must be 16-byte aligned, scores 4-byte aligned");
-  const ns_attn_desc &d = *desc;
-  st = check_workspace(workspace, workspace_bytes, cls_scores_workspace_bytes(desc));
-  if (st != NS_OK) return st;
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  float *logits = static_cast<float *>(workspace);
-  float *partials = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) +
-                                              align_up((size_t)d.batch * d.heads * d.n_global * d.tokens * 4, 256));
-  st = launch_cls_row(d, q, k, nullptr, logits, partials, false, s);
-  if (st != NS_OK) return st;
-  return launch_cls_scores(d.batch, d.heads, d.tokens, d.n_global, logits, nullptr, partials,
-                           cls_num_chunks(d.tokens), scores, s);
+  return cls_scores_impl(desc, q, k, scores, workspace, workspace_bytes, stream);
 }
 
 ns_status cls_scores_from_logits(int32_t batch, int32_t heads, int32_t tokens, int32_t n_global,

@@ -98,6 +98,11 @@ ns_status attn_forward_impl(const ns_attn_desc *desc, const void *q, const void 
                             float *cls_logits, float *cls_lse, float *scores, void *workspace,
                             size_t workspace_bytes, void *stream, bool reuse_lists);
 
+// cls_scores behind its validation: shared by the entry point that takes a workspace and the one
+// that brings its own scratch memory
+ns_status cls_scores_impl(const ns_attn_desc *desc, const void *q, const void *k, float *scores,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
 ns_status launch_block_lists(const ns_attn_desc &d, int32_t *lists, int32_t *counts, hipStream_t s);
 ns_status launch_grid_lists(const ns_attn_desc &d, int32_t *lists, int32_t *counts, hipStream_t s);
 ns_status launch_attn_generic(const AttnArgs &a);
