@@ -248,6 +248,8 @@ ns_status ns_attn_forward_scores(const ns_attn_desc *desc, const void *q, const 
 
 }  // extern "C"
 
+ns_status ns::attn_validate(const ns_attn_desc *desc) { return validate_desc(desc, true); }
+
 ns_status ns::cls_scores_impl(const ns_attn_desc *desc, const void *q, const void *k, float *scores,
                               void *workspace, size_t workspace_bytes, void *stream) {
   ns_status st = validate_desc(desc, false, false);

@@ -98,6 +98,9 @@ ns_status attn_forward_impl(const ns_attn_desc *desc, const void *q, const void 
                             float *cls_logits, float *cls_lse, float *scores, void *workspace,
                             size_t workspace_bytes, void *stream, bool reuse_lists);
 
+// the descriptor checks of ns_attn_forward alone (status and message as that call would give)
+ns_status attn_validate(const ns_attn_desc *desc);
+
 // cls_scores behind its validation: shared by the entry point that takes a workspace and the one
 // that brings its own scratch memory
 ns_status cls_scores_impl(const ns_attn_desc *desc, const void *q, const void *k, float *scores,

@@ -386,7 +386,8 @@ static ns_status block_forward_impl(const ns_vit_block_desc *desc, const ns_vit_
   ns_attn_desc ad;
   ns_status st = block_attn_desc(desc, ad);
   if (st != NS_OK) return st;
-  if (ns_attn_workspace_bytes(&ad) == 0) return NS_ERR_INVALID_ARG;   // message set by the validation
+  st = attn_validate(&ad);
+  if (st != NS_OK) return st;
   if (!w || !x_in || !x_out) return fail(NS_ERR_INVALID_ARG, "weights, x_in and x_out must not be NULL");
   if (!w->ln1_g || !w->ln1_b || !w->w_qkv || !w->b_qkv || !w->w_proj || !w->b_proj || !w->ln2_g ||
       !w->ln2_b || !w->w_fc1 || !w->b_fc1 || !w->w_fc2 || !w->b_fc2)
@@ -427,12 +428,27 @@ static ns_status block_forward_impl(const ns_vit_block_desc *desc, const ns_vit_
   return launch_gemm(hid, static_cast<const uint16_t *>(w->w_fc2), w->b_fc2, h, y, M, dim, mlp, false, s);
 }
 
+// Workspace of one block of the stack: the larger of what a block on the full grid and a block on
+// the pruned sequence need (the latter also holds per-block token lists and counts, and with a
+// keep count within a few tokens of the grid size that is more than the full grid's).
+static size_t stack_block_workspace_bytes(const ns_vit_desc &d, bool prune) {
+  size_t bw = vit_block_workspace_bytes(&d.block);
+  if (bw == 0 || !prune) return bw;
+  ns_vit_block_desc pd = d.block;
+  pd.attn.tokens = d.block.attn.n_global + d.keep_k;
+  // (only "not NULL" matters for the size; the pointer is never dereferenced on the host)
+  pd.attn.coords = reinterpret_cast<const int32_t *>(static_cast<uintptr_t>(256));
+  const size_t pw = vit_block_workspace_bytes(&pd);
+  if (pw == 0) return 0;
+  return bw > pw ? bw : pw;
+}
+
 extern "C" {
 
 size_t vit_workspace_bytes(const ns_vit_desc *desc) {
   bool prune;
   if (check_stack(desc, prune) != NS_OK) return 0;
-  const size_t bw = vit_block_workspace_bytes(&desc->block);   // the full grid needs the most
+  const size_t bw = stack_block_workspace_bytes(*desc, prune);
   if (bw == 0) return 0;
   return stack_layout(*desc, bw).total;
 }
@@ -540,8 +556,13 @@ ns_status vit_forward_features(const ns_vit_desc *desc, const ns_vit_block_weigh
     if (!tap_out[i] || reinterpret_cast<uintptr_t>(tap_out[i]) % 16)
       return fail(NS_ERR_INVALID_ARG, "tap_out[%d] is NULL or misaligned", i);
   }
-  const size_t bw = vit_block_workspace_bytes(&desc->block);
-  if (bw == 0) return NS_ERR_INVALID_ARG;   // message set by the block validation
+  const size_t bw = stack_block_workspace_bytes(*desc, prune);
+  if (bw == 0) {                      // the block's own validation says why: pass its status on
+    ns_attn_desc ad;
+    st = block_attn_desc(&desc->block, ad);
+    if (st == NS_OK) st = attn_validate(&ad);
+    return st != NS_OK ? st : fail(NS_ERR_INVALID_ARG, "invalid block descriptor");
+  }
   if (!weights || !x_in || !x_out) return fail(NS_ERR_INVALID_ARG, "weights, x_in and x_out must not be NULL");
   const StackWorkspace L = stack_layout(*desc, bw);
   if (!workspace) return fail(NS_ERR_WORKSPACE, "workspace is NULL, %zu bytes needed", L.total);

@@ -186,3 +186,42 @@ def test_kernel_choice_policy(nb, monkeypatch):
     bad = desc(2, 16, 128, 8)
     bad.heads = 0
     assert name(bad) == ""
+
+
+def _stack_desc(nb, keep_k, grid=128, block=8):
+    d = nb.ns_vit_desc()
+    a = d.block.attn
+    a.batch, a.heads, a.head_dim = 1, 16, 64
+    a.grid_h = a.grid_w = grid
+    a.block, a.radius, a.n_global, a.dtype, a.tokens = block, 1, 1, nb.NS_BF16, 1 + grid * grid
+    a.scale = 0.125
+    d.block.dim, d.block.mlp_dim, d.block.ln_eps = 1024, 4096, 1e-6
+    d.layers, d.prune_after, d.keep_k = 4, 2, keep_k
+    return d
+
+
+def test_stack_workspace_covers_the_pruned_blocks(nb):
+    """A keep count within a few tokens of the grid size makes the blocks after the pruning stage need
+    more workspace (token lists and counts) than the blocks on the full grid: the stack's workspace
+    must cover both, for every proportion 0 <= p < 1 of the paper's pruning stage (keep_k = N is p = 0)."""
+    N = 128 * 128
+    for keep_k in (N, N - 1, N - 3, N - 100, (N * 60 + 99) // 100, 1):
+        d = _stack_desc(nb, keep_k)
+        total = nb.lib.vit_workspace_bytes(ctypes.byref(d))
+        assert total > 0, nb.lib.ns_last_error()
+        # the block on the pruned sequence, sized on its own
+        pd = nb.ns_vit_block_desc()
+        ctypes.memmove(ctypes.byref(pd), ctypes.byref(d.block), ctypes.sizeof(pd))
+        pd.attn.tokens = 1 + keep_k
+        pd.attn.coords = 0x1000          # never dereferenced on the host
+        need_pruned = nb.lib.vit_block_workspace_bytes(ctypes.byref(pd))
+        need_full = nb.lib.vit_block_workspace_bytes(ctypes.byref(d.block))
+        assert need_pruned > 0 and need_full > 0
+        no_prune = _stack_desc(nb, 0)
+        base = nb.lib.vit_workspace_bytes(ctypes.byref(no_prune))
+        # what the stack adds around a block does not depend on the block's workspace
+        assert total - max(need_full, need_pruned) >= base - need_full - 4096
+        assert total >= max(need_full, need_pruned)
+    # the case that used to fall short: keep_k = N needs more than the full grid
+    pd.attn.tokens = 1 + N
+    assert nb.lib.vit_block_workspace_bytes(ctypes.byref(pd)) > nb.lib.vit_block_workspace_bytes(ctypes.byref(d.block))

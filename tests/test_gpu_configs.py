@@ -1,5 +1,6 @@
 """GPU parity at the benchmark's full sizes, in the launch configuration bench.py times:
-outputs of sampled query rows (the oracle computes them one by one), scores and kept sets."""
+outputs of all query rows (sampled per query tile where a row is too long for the oracle), scores
+and kept sets."""
 import numpy as np
 import pytest
 import torch
@@ -17,29 +18,41 @@ def nb():
     return binding
 
 
-def sample_rows(cfg, n, seed):
-    """CLS, the four grid corners, edge and interior patches, then random ones."""
+def band_rows(cfg, seed):
+    """CLS, the grid corners, and one random patch in every 4 x 16 band of every 16 x 16 square of the grid:
+    the 64-query tiles of the kernels are 8 x 8 blocks or such bands, so every query tile of every
+    workgroup has a row in the sample."""
     g = cfg.grid
-    fixed = [0, 1, g, 1 + (g - 1) * g, g * g, 1 + g // 2, 1 + (g // 2) * g, 1 + (g // 2) * g + g // 2,
-             1 + (cfg.block - 1) * g + cfg.block - 1, 1 + cfg.block * g + cfg.block]
     rng = np.random.default_rng(seed)
-    rest = rng.choice(np.arange(1, cfg.tokens), size=n - len(fixed), replace=False)
-    return np.unique(np.concatenate([fixed, rest])).astype(np.int32)
+    rows = [0, 1, g, 1 + (g - 1) * g, g * g]
+    for r0 in range(0, g, 4):
+        for c0 in range(0, g, 16):
+            r = r0 + int(rng.integers(0, min(4, g - r0)))
+            c = c0 + int(rng.integers(0, min(16, g - c0)))
+            rows.append(1 + r * g + c)
+    return np.unique(np.array(rows)).astype(np.int32)
 
 
-@pytest.mark.parametrize("cfg_id,n_rows", [(1, 785), (2, 160), (3, 96), (4, 40),
-                                           (11, 96), (12, 48), (13, 40), (14, 24), (15, 64)])
-def test_config_pipeline(nb, cfg_id, n_rows):
+# Every query row of every head and image is compared with the oracle (it finishes these sizes in
+# seconds to tens of seconds on the box's host cores); only the 245 x 245 grid with window 64, where a
+# row has 36,864 keys, is sampled: one row per 64-query tile.
+@pytest.mark.parametrize("cfg_id,all_rows", [(1, True), (2, True), (3, True), (4, True),
+                                             (11, True), (12, True), (13, True), (14, False), (15, True)])
+def test_config_pipeline(nb, cfg_id, all_rows):
     cfg = synth.CONFIGS[cfg_id]
     print("config", cfg.name, flush=True)
     q, k, v, info = synth.make_qkv(cfg)
     dq, dk, dv = (to_dev(a, cfg.dtype) for a in (q, k, v))
     out, logits, lse = nb.ns_attn_forward(dq, dk, dv, cfg.grid, cfg.grid, cfg.block, cfg.scale, want_cls=True)
     torch.cuda.synchronize()
-    rows = np.arange(cfg.tokens, dtype=np.int32) if n_rows >= cfg.tokens else sample_rows(cfg, n_rows, cfg.seed)
+    rows = np.arange(cfg.tokens, dtype=np.int32) if all_rows else band_rows(cfg, cfg.seed)
+    import time
+    t0 = time.time()
     ref = oracle.ns_attn(q, k, v, cfg.grid, cfg.grid, cfg.block, cfg.scale, rows=rows)
+    print("oracle: %d rows x %d heads x %d images in %.1f s" % (len(rows), cfg.heads, cfg.batch, time.time() - t0), flush=True)
     got = to_np(out[:, :, torch.from_numpy(rows.astype(np.int64)).cuda()])
     assert_attn_close(got, ref, cfg.dtype, cfg.name)
+    del ref, got
     # property that holds at any size: every output row is a convex combination of value rows
     vmin = dv.float().amin(dim=2, keepdim=True) - 1e-2
     vmax = dv.float().amax(dim=2, keepdim=True) + 1e-2

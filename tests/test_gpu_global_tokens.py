@@ -84,15 +84,16 @@ def test_block_and_stack_with_two_global_tokens(nb):
     w = synth.make_block_weights(dim, mlp, seed=5, ln_random=True)
     rng = np.random.default_rng(12)
     x = synth.round_to_bf16(rng.standard_normal((B, T, dim)).astype(np.float32))
-    ref, ref_scores = oracle_block(x, w, g, g, block, H, want_scores=True, n_global=G)
+    ref, ref_scores = oracle_block(x, w, g, g, block, H, want_scores=True, n_global=G, storage="bf16")
     dw = {n: (torch.from_numpy(a).to(torch.bfloat16) if n.startswith("w_") else torch.from_numpy(a)).cuda()
           for n, a in w.items()}
     y, scores = nb.vit_block_forward(to_dev(x, "bf16"), dw, g, g, block, H, want_scores=True, n_global=G)
     torch.cuda.synchronize()
     got = to_np(y)
-    err = np.abs(got - ref)
-    assert (err <= 2e-2 * np.abs(ref) + 2e-2 * np.sqrt((ref ** 2).mean())).all()
-    np.testing.assert_allclose(to_np(scores), ref_scores, rtol=2e-2, atol=1e-7)
+    assert_attn_close(got, ref, "bf16", "block with two global tokens")
+    # (the block oracle in its bf16 storage model: what is left is the rare bf16 step where fp32 and
+    # float64 accumulation round q or k differently)
+    np.testing.assert_allclose(to_np(scores), ref_scores, rtol=5e-4, atol=0)
     # a stack of two such blocks with a pruning stage in between keeps both global rows
     keep = 100
     out, kept = nb.vit_forward(to_dev(x, "bf16"), [dw, dw], g, g, block, H, prune_after=1, keep_k=keep, n_global=G)
@@ -102,6 +103,5 @@ def test_block_and_stack_with_two_global_tokens(nb):
     assert np.array_equal(kept_np, oracle.topk(to_np(scores), keep))      # selection on the GPU's own scores
     x1 = oracle.gather(got, kept_np, n_global=G)                            # block 1 output, compacted
     coords = np.ascontiguousarray(synth.raster_coords(g, g)[kept_np])
-    ref2 = oracle_block(x1, w, g, g, block, H, coords=coords, n_global=G)
-    err = np.abs(to_np(out) - ref2)
-    assert (err <= 3e-2 * np.abs(ref2) + 3e-2 * np.sqrt((ref2 ** 2).mean())).all()
+    ref2 = oracle_block(x1, w, g, g, block, H, coords=coords, n_global=G, storage="bf16")
+    assert_attn_close(to_np(out), ref2, "bf16", "second block on the pruned sequence")

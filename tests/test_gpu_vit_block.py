@@ -10,6 +10,9 @@ from _util import assert_attn_close, assert_kept_sets_match, to_np
 
 pytestmark = pytest.mark.gpu
 
+# Importance scores of a whole block against the block oracle in its bf16 storage model: see block_case.
+SCORE_RTOL = 5e-4
+
 
 @pytest.fixture(scope="module")
 def nb():
@@ -34,15 +37,22 @@ def block_case(nb, B, g, block, heads, dim, mlp, seed, coords_keep=None):
         coords = np.ascontiguousarray(np.broadcast_to(synth.raster_coords(g, g)[kept], (B, len(kept))))
     x = synth.round_to_bf16(rng.standard_normal((B, T, dim)).astype(np.float32))
     w = synth.make_block_weights(dim, mlp, seed=seed, dtype="bf16", ln_random=True)
-    ref, ref_scores = ov.vit_block(x, w, g, g, block, heads, ln_eps=1e-6, coords=coords, want_scores=True)
+    # the oracle in its "bf16 storage" precision model: every tensor the block keeps in memory between
+    # two steps is rounded to bf16 there as well, all arithmetic in float64
+    ref, ref_scores = ov.vit_block(x, w, g, g, block, heads, ln_eps=1e-6, coords=coords, want_scores=True,
+                                   storage="bf16")
     dx = torch.from_numpy(x).to(torch.bfloat16).cuda()
     dc = None if coords is None else torch.from_numpy(coords).cuda()
     out, scores = nb.vit_block_forward(dx, dev_weights(w), g, g, block, heads, ln_eps=1e-6, coords=dc,
                                        want_scores=True)
     torch.cuda.synchronize()
     assert_attn_close(to_np(out), ref, "bf16", "block output")
-    # scores are computed from bf16-rounded q, k: a few 1e-3 relative
-    np.testing.assert_allclose(to_np(scores), ref_scores, rtol=3e-2, atol=1e-7)
+    # q and k of both sides are bf16 values computed from the same bf16 inputs; they differ where
+    # fp32 and float64 accumulation fall on different sides of a bf16 rounding boundary (about one
+    # element in a thousand, by one bf16 step = 2^-8 of one of 64 products of a logit)
+    rel = np.abs(to_np(scores) - ref_scores) / ref_scores
+    print("scores: max relative deviation %.2e, mean %.2e" % (rel.max(), rel.mean()), flush=True)
+    np.testing.assert_allclose(to_np(scores), ref_scores, rtol=SCORE_RTOL, atol=0)
     return out
 
 
@@ -88,17 +98,17 @@ def test_stack_with_pruning_stage(nb, layers, after, keep_pct, g, block):
     h = x.astype(np.float64)
     for i in range(after):
         if i + 1 == after:
-            h, scores = ov.vit_block(h, ws[i], g, g, block, heads, want_scores=True)
+            h, scores = ov.vit_block(h, ws[i], g, g, block, heads, want_scores=True, storage="bf16")
         else:
-            h = ov.vit_block(h, ws[i], g, g, block, heads)
+            h = ov.vit_block(h, ws[i], g, g, block, heads, storage="bf16")
     ref_kept = oracle.topk(scores.astype(np.float32), keep)
-    # bf16 storage of q, k between the GEMM and the attention moves the scores by ~1e-2 relative
-    assert_kept_sets_match(kept_np, ref_kept, scores, keep, band=5e-2)
+    # kept sets agree outside the stated tie band (1e-3 relative around the k-th score)
+    assert_kept_sets_match(kept_np, ref_kept, scores, keep)
     idx = np.concatenate([np.zeros((B, 1), dtype=np.int64), 1 + kept_np.astype(np.int64)], axis=1)
     h = np.take_along_axis(h, idx[:, :, None], axis=1)
     coords = np.stack([synth.raster_coords(g, g)[kept_np[b]] for b in range(B)])
     for i in range(after, layers):
-        h = ov.vit_block(h, ws[i], g, g, block, heads, coords=coords)
+        h = ov.vit_block(h, ws[i], g, g, block, heads, coords=coords, storage="bf16")
     assert_attn_close(to_np(out), h, "bf16", "stack output")
 
 
@@ -166,13 +176,23 @@ def test_stack_without_pruning_equals_repeated_blocks(nb):
 
 def test_stack_feature_maps(nb):
     """Segmentation mode: sparse attention in every layer, no pruning, patch tokens after chosen
-    blocks handed out in raster order.  Each map equals the patch rows of the block-by-block run
-    (which the block tests pin to the oracle), bit for bit."""
+    blocks handed out in raster order.  Each map is compared with the oracle's chain of blocks
+    (patch rows after blocks 1, 3 and 4, raster order) and, bit for bit, with the block-by-block run."""
     B, g, block, heads, dim, mlp = 2, 20, 8, 8, 512, 512       # 20 is not a multiple of 8
     rng = np.random.default_rng(23)
-    x = torch.from_numpy(synth.round_to_bf16(rng.standard_normal((B, 1 + g * g, dim)).astype(np.float32))).to(torch.bfloat16).cuda()
-    ws = [dev_weights(synth.make_block_weights(dim, mlp, seed=50 + i)) for i in range(4)]
+    x_np = synth.round_to_bf16(rng.standard_normal((B, 1 + g * g, dim)).astype(np.float32))
+    x = torch.from_numpy(x_np).to(torch.bfloat16).cuda()
+    ws_np = [synth.make_block_weights(dim, mlp, seed=50 + i) for i in range(4)]
+    ws = [dev_weights(w) for w in ws_np]
     out, kept, taps = nb.vit_forward(x, ws, g, g, block, heads, tap_layers=[1, 3, 4])
+    torch.cuda.synchronize()
+    ref_h, ref_maps = x_np.astype(np.float64), {}
+    for i, w in enumerate(ws_np):
+        ref_h = ov.vit_block(ref_h, w, g, g, block, heads, storage="bf16")
+        ref_maps[i + 1] = ref_h[:, 1:]
+    for t, l in zip(taps, (1, 3, 4)):
+        assert_attn_close(to_np(t), ref_maps[l], "bf16", "feature map after block %d" % l)
+    assert_attn_close(to_np(out), ref_h, "bf16", "stack output")
     h, hs = x, []
     for w in ws:
         h = nb.vit_block_forward(h, w, g, g, block, heads)

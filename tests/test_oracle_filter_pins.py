@@ -107,3 +107,28 @@ def test_gather_is_a_bit_copy_with_cls_first():
             assert np.array_equal(y[b, 1 + t], x[b, 1 + kept[b, t]])
     with pytest.raises(ValueError):
         oracle.gather(x, np.array([[0, 30], [0, 1]], dtype=np.int32))
+
+
+def test_gather_with_several_global_tokens_hand_built():
+    """oracle.gather with G > 1: the G leading rows stay, then rows G + kept[b, t]; expected rows
+    written out by hand (no formula shared with the oracle)."""
+    B, G, N, C = 2, 3, 5, 4
+    x = (np.arange(B * (G + N) * C, dtype=np.float32).reshape(B, G + N, C) * 7 % 31).astype(np.float32)
+    kept = np.array([[0, 2, 4], [1, 2, 3]], dtype=np.int32)
+    y = oracle.gather(x, kept, n_global=G)
+    assert y.shape == (B, G + 3, C)
+    want0 = [x[0, 0], x[0, 1], x[0, 2], x[0, 3], x[0, 5], x[0, 7]]        # globals 0..2, patches 0, 2, 4 -> rows 3, 5, 7
+    want1 = [x[1, 0], x[1, 1], x[1, 2], x[1, 4], x[1, 5], x[1, 6]]        # patches 1, 2, 3 -> rows 4, 5, 6
+    assert np.array_equal(y[0], np.stack(want0)) and np.array_equal(y[1], np.stack(want1))
+    # bit copy also of patterns that are not numbers
+    xb = np.full((1, G + N, 2), 0x7FC1, dtype=np.uint16)
+    xb[0, :, 1] = np.arange(G + N, dtype=np.uint16) + 0xFF80
+    yb = oracle.gather(xb, np.array([[4]], dtype=np.int32), n_global=G)
+    assert np.array_equal(yb[0, :, 1], np.array([0xFF80, 0xFF81, 0xFF82, 0xFF87], dtype=np.uint16))
+    # G = 1 on the same data keeps one leading row and shifts the patches by one
+    y1 = oracle.gather(x, kept, n_global=1)
+    assert np.array_equal(y1[0], np.stack([x[0, 0], x[0, 1], x[0, 3], x[0, 5]]))
+    # an index beyond the patches of the G > 1 layout is refused
+    import pytest
+    with pytest.raises(ValueError):
+        oracle.gather(x, np.array([[0, 1, 5], [0, 1, 2]], dtype=np.int32), n_global=G)

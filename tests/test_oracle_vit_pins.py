@@ -74,3 +74,35 @@ def test_patch_embed_one_hot_projection_picks_single_pixels():
         for pc in range(gw):
             for i, (c, y, x) in enumerate(picks):
                 assert got[0, 1 + pr * gw + pc, i] == px[0, c, pr * ps + y, pc * ps + x]
+
+
+def test_round_bf16_equals_library_conversion():
+    """The block oracle's storage rounding against torch's float32 -> bfloat16 conversion (round to
+    nearest even), including exact ties, signed zeros, denormals and values next to overflow."""
+    rng = np.random.default_rng(8)
+    x = np.concatenate([rng.standard_normal(20000) * np.exp(rng.uniform(-30, 30, 20000)),
+                        [0.0, -0.0, 1.0, 1.00390625, 1.01171875, -1.00390625, 3.3895313892515355e38, 1e-40, -1e-45],
+                        # exact ties: bf16 has 8 significand bits, so 1 + (2k+1) * 2^-8 lies half way
+                        1.0 + (2 * np.arange(64) + 1) * 2.0 ** -8])
+    want = torch.from_numpy(x.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    got = ov.round_bf16(x)
+    assert np.array_equal(got.view(np.uint64), want.view(np.uint64))
+    assert ov.round_bf16(np.array([1.00390625]))[0] == 1.0            # tie -> even (down)
+    assert ov.round_bf16(np.array([1.01171875]))[0] == 1.015625       # tie -> even (up)
+
+
+def test_bf16_storage_model_rounds_every_stored_tensor():
+    """storage="bf16": outputs and the q, k behind the scores are bfloat16 values, and the result stays
+    within a few bf16 steps of the unrounded block (the model changes precision, not the function)."""
+    rng = np.random.default_rng(9)
+    B, g, heads, D, mlp = 1, 8, 2, 8, 24
+    dim, T = heads * D, 1 + g * g
+    x = ov.round_bf16(rng.standard_normal((B, T, dim)))
+    w = synth.make_block_weights(dim, mlp, seed=6, dtype="bf16", ln_random=True)
+    y64, s64 = ov.vit_block(x, w, g, g, 4, heads, want_scores=True)
+    y16, s16 = ov.vit_block(x, w, g, g, 4, heads, want_scores=True, storage="bf16")
+    assert np.array_equal(ov.round_bf16(y16), y16)
+    assert not np.array_equal(y16, y64)
+    np.testing.assert_allclose(y16, y64, rtol=3e-2, atol=3e-2 * np.sqrt((y64 ** 2).mean()))
+    np.testing.assert_allclose(s16, s64, rtol=5e-2)
+    np.testing.assert_allclose(s16.sum(axis=1) + 0, s16.sum(axis=1))   # finite
