@@ -5,7 +5,7 @@
 // in-index-order compaction, so the kept indices come out ascending and exact ties resolve to
 // the lower index.
 //   topk_select_reg_kernel: rows of up to 16384 scores, one workgroup of 16 waves per image, keys
-//     in registers, bisection on the key's bits: latency-bound, a score row is 64 KB.
+//     in registers, four 8-bit digit passes (radix select): latency-bound, a score row is 64 KB.
 //   topk_digit_pass_kernel / topk_place_kernel: longer rows, several
 //     workgroups per image, four 8-bit digit passes (radix select), one launch each.
 // gather_rows_kernel: copies the kept token rows (and the global rows) with 16-byte accesses.
@@ -41,6 +41,32 @@ __device__ __forceinline__ void wave_histogram_add(uint32_t *h, bool cand, uint3
   if ((rem >> lane) & 1ull) atomicAdd(&h[digit], 1u);
 }
 
+// Threads 0..255 bring the number of candidates per digit; sel[0] = the digit that holds the
+// need-th largest candidate, sel[1] = how many keys of that digit are still needed.
+__device__ __forceinline__ void choose_digit(uint32_t tot, uint32_t need, int tid, int wave, int lane,
+                                             uint32_t *wtot, uint32_t *sel) {
+  uint32_t above = 0;
+  if (tid < 256) {
+    uint32_t incl = tot;   // inclusive suffix sum inside the wave: lanes >= lane
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const uint32_t t = __shfl_down(incl, off);
+      if (lane + off < 64) incl += t;
+    }
+    if (lane == 0) wtot[wave] = incl;
+    above = incl - tot;
+  }
+  __syncthreads();
+  if (tid < 256) {
+    for (int w = wave + 1; w < 4; w++) above += wtot[w];
+    if (above < need && need <= above + tot) {   // exactly one digit satisfies this
+      sel[0] = (uint32_t)tid;
+      sel[1] = need - above;
+    }
+  }
+  __syncthreads();
+}
+
 // Rows of N <= 1024 * KPT scores: every thread keeps its KPT keys in registers (thread t holds
 // indices i*1024 + t), so the selection and the compaction read global memory exactly once.
 template <int KPT>
@@ -52,6 +78,8 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_reg_kernel(const floa
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const float *sc = scores + (size_t)b * N;
   __shared__ uint32_t wtot[2][kSelWaves];
+  __shared__ uint32_t hist[256 * 32];
+  __shared__ uint32_t wsum[4], sel[2];
   __shared__ uint32_t pgt[KPT * kSelWaves], peq[KPT * kSelWaves];   // per (i, wave) counts -> prefixes
   __shared__ uint32_t sgt[kSelWaves], seq[kSelWaves];
 
@@ -63,12 +91,6 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_reg_kernel(const floa
     const int j = i * kSelThreads + tid;
     key[i] = j < N ? order_key(sc[j]) : 0u;
   }
-  // k-th largest key by bisection on its bits, most significant first: tau keeps a bit iff at
-  // least k keys are >= the candidate.  A wave counts with one compare + one scalar popcount per
-  // key slot (no LDS atomics, cost independent of how the scores cluster); the 16 wave counts
-  // are exchanged through LDS, double-buffered so that one barrier per bit suffices.  (Measured:
-  // the step time is set by the compares of all N keys on this one CU; two bits per step, with
-  // three candidates, was slower.)
   auto block_total = [&](uint32_t wave_count, int slot) -> uint32_t {
     if (lane == 0) wtot[slot][wave] = wave_count;
     __syncthreads();
@@ -80,20 +102,35 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_reg_kernel(const floa
     t += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)t, 0x118, 0xf, 0xf, true);
     return (uint32_t)__builtin_amdgcn_readlane((int)t, 15);
   };
-  uint32_t tau = 0;
-  int slot = 0;      // exchange buffer of the next block_total (they alternate)
-  for (int bit = 31; bit >= 0; bit--) {
-    const uint32_t cand = tau | (1u << bit);
-    uint32_t c = 0;   // wave-uniform: lives in a scalar register
+  // k-th largest key by four 8-bit digit passes, most significant digit first (radix select): a
+  // pass histograms the digit of the keys that match the prefix chosen so far, and the digit that
+  // holds the left-th largest candidate extends the prefix.  The histogram is kept in 32 copies,
+  // bin d of copy c at word 32*d + c, and lane l adds to copy l % 32: scores that cluster (most
+  // keys of a wave in one bin) then still spread over 32 LDS banks instead of serialising on one
+  // address, so a pass costs the same whatever the scores look like.  Four passes of a few
+  // barriers each replace the 32 compare-and-count steps of a bisection over all keys (22 us for
+  // 16384 scores).
+  uint32_t tau = 0, left = (uint32_t)k;
+  for (int pass = 0; pass < 4; pass++) {
+    for (int i = tid; i < 256 * 32; i += kSelThreads) hist[i] = 0;
+    __syncthreads();
+    const uint32_t mask = pass ? 0xffffffffu << (32 - 8 * pass) : 0u;
+    const int shift = 24 - 8 * pass;
 #pragma unroll
-    for (int i = 0; i < KPT; i++) c += (uint32_t)__popcll(__ballot(key[i] >= cand));   // padding keys are 0 < cand
-    const uint32_t tot = block_total(c, slot);
-    slot ^= 1;
-    if (tot >= (uint32_t)k) tau = cand;
-    // exactly k keys are >= cand: they are the kept set, the remaining bits of the k-th key do
-    // not matter (below, every key >= tau is then either above it or one of `need` equal ones)
-    if (tot == (uint32_t)k) break;
+    for (int i = 0; i < KPT; i++)
+      if (key[i] != 0u && (key[i] & mask) == tau) atomicAdd(&hist[(((key[i] >> shift) & 255u) << 5) + (lane & 31)], 1u);
+    __syncthreads();
+    uint32_t tot = 0;
+    if (tid < 256) {
+      // (copy (c + tid) % 32 in round c: the 64 lanes of a wave read 64 different banks)
+#pragma unroll
+      for (int c = 0; c < 32; c++) tot += hist[(tid << 5) + ((c + tid) & 31)];
+    }
+    choose_digit(tot, left, tid, wave, lane, wsum, sel);
+    tau |= sel[0] << shift;
+    left = sel[1];
   }
+  int slot = 0;
   uint32_t cg = 0;
 #pragma unroll
   for (int i = 0; i < KPT; i++) cg += (uint32_t)__popcll(__ballot(key[i] > tau));
@@ -153,32 +190,6 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_reg_kernel(const floa
 // digit that holds the k-th largest key.  No atomics on global memory, no waiting between
 // workgroups: the launches order the passes.
 struct SelState { uint32_t prefix, need; };
-
-// Threads 0..255 bring the number of candidates per digit; sel[0] = the digit that holds the
-// need-th largest candidate, sel[1] = how many keys of that digit are still needed.
-__device__ __forceinline__ void choose_digit(uint32_t tot, uint32_t need, int tid, int wave, int lane,
-                                             uint32_t *wtot, uint32_t *sel) {
-  uint32_t above = 0;
-  if (tid < 256) {
-    uint32_t incl = tot;   // inclusive suffix sum inside the wave: lanes >= lane
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const uint32_t t = __shfl_down(incl, off);
-      if (lane + off < 64) incl += t;
-    }
-    if (lane == 0) wtot[wave] = incl;
-    above = incl - tot;
-  }
-  __syncthreads();
-  if (tid < 256) {
-    for (int w = wave + 1; w < 4; w++) above += wtot[w];
-    if (above < need && need <= above + tot) {   // exactly one digit satisfies this
-      sel[0] = (uint32_t)tid;
-      sel[1] = need - above;
-    }
-  }
-  __syncthreads();
-}
 
 // The state after digit `upto` (0..3) has been chosen, from the state before and that digit's
 // histograms; workgroup 0 of the image records it for the next launch.  The histograms were
@@ -333,7 +344,11 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const uint4 *x, const 
   const int src = row < G ? row : G + kept[(size_t)b * k + row - G];
   const uint4 *xs = x + ((size_t)b * (G + N) + src) * vec_per_row;
   uint4 *yd = y + ((size_t)b * (G + k) + row) * vec_per_row;
-  for (int i = lane; i < vec_per_row; i += 64) yd[i] = xs[i];
+  // (streamed once: non-temporal accesses leave the caches to the kernels around this one)
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 *src4 = reinterpret_cast<const u32x4 *>(xs);
+  u32x4 *dst4 = reinterpret_cast<u32x4 *>(yd);
+  for (int i = lane; i < vec_per_row; i += 64) __builtin_nontemporal_store(__builtin_nontemporal_load(src4 + i), dst4 + i);
 }
 
 }  // namespace
