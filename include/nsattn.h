@@ -59,7 +59,11 @@ typedef enum { NS_F32 = 0, NS_BF16 = 1 } ns_dtype;
  * coords != NULL (after pruning): device array [batch, tokens - n_global] holding the
  * original grid position (r << 16 | c) of each surviving patch token; positions must be
  * distinct within an image and inside the grid.  The mask is evaluated on those original
- * positions.
+ * positions.  This precondition is the caller's: the positions live in device memory and no
+ * call checks them.  A token whose position lies outside the grid, or one of several tokens
+ * that claim the same position beyond what a block holds, belongs to no block: no key set is
+ * defined for it, its row of out is left as it was, and the call still returns NS_OK.  The
+ * coords_out that topk_filter and gather write from valid coords_in always satisfy it.
  */
 typedef struct ns_attn_desc {
   int32_t batch;     /* B >= 1                                                           */

@@ -5,6 +5,8 @@
 
 #include "ns_common.h"
 #include <algorithm>
+#include <mutex>
+#include <vector>
 
 namespace ns {
 
@@ -21,6 +23,28 @@ ns_status fail(ns_status code, const char *fmt, ...) {
 ns_status check_launch(const char *what) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(NS_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+  return NS_OK;
+}
+
+int device_cu_count() {
+  // (a function-local static is initialised once, thread-safely)
+  static const int num_cus = [] {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    return (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+               ? prop.multiProcessorCount : 256;
+  }();
+  return num_cus;
+}
+
+ns_status reserve_lds_once(const void *kernel, int bytes) {
+  static std::mutex mu;
+  static std::vector<const void *> done;
+  std::lock_guard<std::mutex> lock(mu);
+  if (std::find(done.begin(), done.end(), kernel) != done.end()) return NS_OK;
+  if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess)
+    return fail(NS_ERR_HIP, "cannot reserve %d bytes of LDS", bytes);
+  done.push_back(kernel);
   return NS_OK;
 }
 
@@ -143,17 +167,9 @@ size_t ns_attn_workspace_bytes(const ns_attn_desc *desc) {
 // NSATTN_KERNEL = sweep | block | persist | mfma | lists | generic forces one of them where it applies.
 enum PatchKernel { PK_SWEEP, PK_BLOCK16, PK_PERSIST, PK_MFMA, PK_RAGGED, PK_GENERIC };
 
-static int device_cus() {
-  static int num_cus = 0;
-  if (num_cus == 0) {
-    int dev = 0;
-    hipDeviceProp_t prop;
-    num_cus = (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-                  ? prop.multiProcessorCount : 256;
-  }
-  return num_cus;
-}
+static int device_cus() { return device_cu_count(); }
 
+// (the environment is read once per call, here; the choice travels in AttnArgs::kernel)
 static PatchKernel choose_patch_kernel(const ns_attn_desc &d) {
   const char *e = getenv("NSATTN_KERNEL");
   const char force = e ? e[0] : 0;
@@ -182,7 +198,7 @@ static PatchKernel choose_patch_kernel(const ns_attn_desc &d) {
 }
 
 static ns_status launch_patch_attention(const AttnArgs &a) {
-  switch (choose_patch_kernel(a.d)) {
+  switch (a.kernel) {
     case PK_SWEEP: return launch_attn_sweep(a, nullptr, nullptr);
     case PK_BLOCK16: return launch_attn_block16(a);
     case PK_PERSIST: return launch_attn_persist(a);
@@ -218,7 +234,8 @@ static ns_status prepare_attn(const ns_attn_desc *desc, const void *q, const voi
   g.lists = nullptr; g.counts = nullptr;
   // (the workspace has room for lists whenever wants_lists(); a complete grid that the sweep serves
   // does without them)
-  if (wants_lists(d) && (d.coords || choose_patch_kernel(d) == PK_RAGGED)) {
+  a.kernel = choose_patch_kernel(d);
+  if (wants_lists(d) && (d.coords || a.kernel == PK_RAGGED)) {
     int32_t *lists = reinterpret_cast<int32_t *>(ws + w.lists_off);
     int32_t *counts = reinterpret_cast<int32_t *>(ws + w.counts_off);
     if (!reuse_lists) {
@@ -280,7 +297,7 @@ ns_status ns::attn_forward_impl(const ns_attn_desc *desc, const void *q, const v
   ns_status st = prepare_attn(desc, q, k, v, out, workspace, workspace_bytes, stream, a, partials, reuse_lists);
   if (st != NS_OK) return st;
   const ns_attn_desc &d = a.d;
-  if (choose_patch_kernel(d) == PK_SWEEP) {
+  if (a.kernel == PK_SWEEP) {
     // this kernel computes the global query's partials and logits on the way
     st = launch_attn_sweep(a, cls_logits, partials);
     if (st != NS_OK) return st;
@@ -311,7 +328,7 @@ ns_status ns_attn_patch_kernel_time(const ns_attn_desc *desc, const void *q, con
   if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
     return fail(NS_ERR_HIP, "hipEventCreate failed");
   hipError_t e = hipEventRecord(e0, a.stream);
-  const bool sweep = choose_patch_kernel(a.d) == PK_SWEEP;
+  const bool sweep = a.kernel == PK_SWEEP;
   for (int i = 0; i < reps && st == NS_OK; i++)
     st = sweep ? launch_attn_sweep(a, nullptr, partials) : launch_patch_attention(a);
   if (e == hipSuccess) e = hipEventRecord(e1, a.stream);

@@ -29,7 +29,6 @@ struct BlockParams {
 
 typedef s16x4 __attribute__((address_space(3))) *lds_s16x4_ptr;
 typedef bf16x8 __attribute__((address_space(3))) *lds_bf16x8_ptr;
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr uint32_t kSlot = 16384;     // one key tile: K [64][64] bf16, then V [64][64] bf16
 constexpr uint32_t kVOff = 8192;
@@ -37,31 +36,6 @@ constexpr int kSlots = 3;
 constexpr uint32_t kK0Row = 3 * 16384;         // k_0 in the first 128 bytes of a 1 KB transfer
 constexpr uint32_t kV0Row = 3 * 16384 + 1024;  // v_0 likewise
 
-__device__ __forceinline__ float bswap_max(float x) {
-  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-__device__ __forceinline__ float bswap_sum(float x) {
-  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-// 16 bytes per lane, global -> LDS at lds + 16*lane, no registers.
-__device__ __forceinline__ void bdma16(const char *base, uint32_t voff, uint32_t lds) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :: "s"(lds), "v"(voff), "s"(base) : "memory", "m0");
-}
-// 4 bytes per lane to global memory, one request.
-__device__ __forceinline__ void bstore4(void *ptr, float v) {
-  asm volatile("global_store_dword %0, %1, off" :: "v"(ptr), "v"(v) : "memory");
-}
-// 8 bytes per lane to global memory, issued from asm so that it is exactly one request.
-__device__ __forceinline__ void bstore8(void *ptr, u32x2 v) {
-  asm volatile("global_store_dwordx2 %0, %1, off" :: "v"(ptr), "v"(v) : "memory");
-}
-template <int N>
-__device__ __forceinline__ void bwait_vm() {
-  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
-}
 
 #define NS_U(x) __builtin_amdgcn_readfirstlane(x)
 
@@ -161,14 +135,14 @@ __global__ __launch_bounds__(256, 2) void attn_block16_kernel(BlockParams p) {
 #pragma unroll
       for (int j = 0; j < 2; j++) {
         const uint32_t shift = (uint32_t)(min(8 * j + drow, wv_last - 1) - drow) * rowB;   // sum below is >= 0
-        bdma16(kb + base, dma_koff[j] + shift, dst + j * 1024);
-        bdma16(vb + base, dma_voff + shift, dst + kVOff + j * 1024);
+        dma16(kb + base, dma_koff[j] + shift, dst + j * 1024);
+        dma16(vb + base, dma_voff + shift, dst + kVOff + j * 1024);
       }
     } else {
 #pragma unroll
-      for (int j = 0; j < 2; j++) bdma16(kb + base + (size_t)j * 8 * rowB, dma_koff[j], dst + j * 1024);
+      for (int j = 0; j < 2; j++) dma16(kb + base + (size_t)j * 8 * rowB, dma_koff[j], dst + j * 1024);
 #pragma unroll
-      for (int j = 0; j < 2; j++) bdma16(vb + base + (size_t)j * 8 * rowB, dma_voff, dst + kVOff + j * 1024);
+      for (int j = 0; j < 2; j++) dma16(vb + base + (size_t)j * 8 * rowB, dma_voff, dst + kVOff + j * 1024);
     }
     islot = islot == kSlots - 1 ? 0 : islot + 1;
     const bool next_block = isub == subs_of(ir) - 1, next_row = next_block && ic == C1;
@@ -265,7 +239,7 @@ __global__ __launch_bounds__(256, 2) void attn_block16_kernel(BlockParams p) {
     char *t = ob + (size_t)tile_token(R, C, wave) * (size_t)(p.ost * 2);
 #pragma unroll
     for (int nt = 0; nt < 2; nt++) {
-      const float inv = 1.f / bswap_sum(l[nt]);
+      const float inv = 1.f / half_swap_sum(l[nt]);
       const int i = l32 + 32 * nt;
       const int r = min(4 * wave + (i >> 4), rows_of(R) - 1) - 4 * wave;   // as in tile_off
       char *row = t + (ptrdiff_t)(r * p.grid_w + min(i & 15, cols_of(C) - 1)) * (ptrdiff_t)(p.ost * 2) + 8 * hh;
@@ -283,13 +257,13 @@ __global__ __launch_bounds__(256, 2) void attn_block16_kernel(BlockParams p) {
 
   // ---- prologue: the first three key tiles are requested, the first has landed
   if (wave == 0) {                   // the global token's rows, 8 lanes x 16 bytes each (the other lanes repeat them)
-    bdma16(kb, 16u * (lane & 7), lds_base + kK0Row);
-    bdma16(vb, 16u * (lane & 7), lds_base + kV0Row);
+    dma16(kb, 16u * (lane & 7), lds_base + kK0Row);
+    dma16(vb, 16u * (lane & 7), lds_base + kV0Row);
   }
   issue_next();
   issue_next();
   issue_next();
-  bwait_vm<8>();                     // k_0, v_0 and tile 0
+  wait_vm<8>();                     // k_0, v_0 and tile 0
   __syncthreads();
   load_tile();                       // consumed at once: no load is pending at the loop head
   init_tile();
@@ -324,7 +298,7 @@ __global__ __launch_bounds__(256, 2) void attn_block16_kernel(BlockParams p) {
       stage_c(1, 0, p2, slot);
       stage_c(1, 1, p3, slot);
     }
-    bwait_vm<4>();     // tile s+1: this wave's share has landed (its share of tile s+2 may still be in flight)
+    wait_vm<4>();     // tile s+1: this wave's share has landed (its share of tile s+2 may still be in flight)
     __syncthreads();   // ... and everybody's; and everybody is done with tile s, whose slot tile s+3 takes
     issue_next();
     cslot = cslot == kSlots - 1 ? 0 : cslot + 1;
@@ -335,7 +309,7 @@ __global__ __launch_bounds__(256, 2) void attn_block16_kernel(BlockParams p) {
       cr = nr2 ? cr + 1 : cr;
     }
   }
-  bwait_vm<0>();
+  wait_vm<0>();
   const bool bad = finish_tile();
   __syncthreads();                   // the ring is free: each wave takes 16 KB of it below
   if (!bad) return;
@@ -363,9 +337,9 @@ __global__ __launch_bounds__(256, 2) void attn_block16_kernel(BlockParams p) {
           const int grow = min(4 * sub + (it >> 1), hvk - 1);
           // (unsigned lane offset: the clamped column goes into it whole, see issue_next)
           const uint32_t shift = (uint32_t)(min(8 * (it & 1) + drow, wvk - 1) - drow) * rowB;
-          bdma16(vb + vblock + (size_t)grow * gridrowB, dma_voff + shift, lds_base + mine + kVOff + it * 1024);
+          dma16(vb + vblock + (size_t)grow * gridrowB, dma_voff + shift, lds_base + mine + kVOff + it * 1024);
         }
-        bwait_vm<0>();               // also the K fragments above
+        wait_vm<0>();               // also the K fragments above
 #pragma unroll
         for (int nt = 0; nt < 2; nt++) {
           f32x16 s0 = stage_a(kt[0], nt), s1 = stage_a(kt[1], nt);
@@ -379,7 +353,7 @@ __global__ __launch_bounds__(256, 2) void attn_block16_kernel(BlockParams p) {
             mx0 = fmaxf(fmaxf(mx0, s0[e]), s0[e + 1]);
             mx1 = fmaxf(fmaxf(mx1, s1[e]), s1[e + 1]);
           }
-          const float m_new = fmaxf(m[nt], bswap_max(fmaxf(mx0, mx1)) * p.c);
+          const float m_new = fmaxf(m[nt], half_swap_max(fmaxf(mx0, mx1)) * p.c);
           const float alpha = __builtin_amdgcn_exp2f(m[nt] - m_new);
           m[nt] = m_new;
           const float nmm = -m_new;
@@ -437,16 +411,11 @@ ns_status launch_attn_block16(const AttnArgs &a) {
   const long long blocks = (long long)d.batch * d.heads * p.nbh * p.nbw;
   if (blocks > 0x7fffffffLL) return fail(NS_ERR_UNSUPPORTED, "launch grid too large");
   p.blocks = (int)blocks;
-  static bool attr_set = false;
   const int lds = 4 * 16384;        // three ring slots and the global token's rows; the redo gives each wave a slot
-  if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(attn_block16_kernel<false>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess ||
-        hipFuncSetAttribute(reinterpret_cast<const void *>(attn_block16_kernel<true>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
-      return fail(NS_ERR_HIP, "cannot reserve %d bytes of LDS", lds);
-    attr_set = true;
-  }
+  const bool even = d.grid_h % 16 == 0 && d.grid_w % 16 == 0;
+  const ns_status rs = reserve_lds_once(even ? reinterpret_cast<const void *>(attn_block16_kernel<false>)
+                                             : reinterpret_cast<const void *>(attn_block16_kernel<true>), lds);
+  if (rs != NS_OK) return rs;
   if (d.grid_h % 16 == 0 && d.grid_w % 16 == 0)
     hipLaunchKernelGGL(attn_block16_kernel<false>, dim3((unsigned)blocks), dim3(256), lds, a.stream, p);
   else

@@ -34,23 +34,7 @@ struct MfmaParams {
   int total_wgs;
 };
 
-__device__ __forceinline__ float half_swap_max(float x) {
-  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-__device__ __forceinline__ float half_swap_sum(float x) {
-  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
 
-// 16 bytes per lane, global -> LDS, no registers: LDS address = lds + 16 * lane.  Issued as asm
-// so that the compiler does not guard later LDS reads with a full vmcnt(0) wait (it cannot tell
-// this tile's transfer from the next tile's, which is still in flight); the kernel orders its
-// memory requests so that no wait on these transfers is needed at all (see the tile loop).
-__device__ __forceinline__ void dma16(const char *base, uint32_t voff, uint32_t lds) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :: "s"(lds), "v"(voff), "s"(base) : "memory", "m0");
-}
 
 typedef s16x4 __attribute__((address_space(3))) *lds_s16x4_ptr;
 

@@ -52,7 +52,6 @@ struct PersistParams {
 
 typedef s16x4 __attribute__((address_space(3))) *lds_s16x4_ptr;
 typedef bf16x8 __attribute__((address_space(3))) *lds_bf16x8_ptr;
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kStoresPerQuery = 16;   // 8-byte stores of one query tile's output
 constexpr int kQueryRequests = 10;    // transfers of the next query tile: 8 (Q) + 1 (k_0) + 1 (v_0)
@@ -65,28 +64,7 @@ constexpr uint32_t K0ROW = 36864;     // k_0 in the first 128 bytes of a 1 KB re
 constexpr uint32_t V0ROW = 37888;     // v_0 likewise
 constexpr uint32_t kLdsUsed = 38912;
 
-__device__ __forceinline__ float hswap_max(float x) {
-  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-__device__ __forceinline__ float hswap_sum(float x) {
-  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
 
-// 16 bytes per lane, global -> LDS at lds + 16*lane, no registers.
-__device__ __forceinline__ void dma16(const char *base, uint32_t voff, uint32_t lds) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :: "s"(lds), "v"(voff), "s"(base) : "memory", "m0");
-}
-// 8 bytes per lane to global memory, issued from asm so that it is exactly one request.
-__device__ __forceinline__ void store8(void *ptr, u32x2 v) {
-  asm volatile("global_store_dwordx2 %0, %1, off" :: "v"(ptr), "v"(v) : "memory");
-}
-template <int N>
-__device__ __forceinline__ void wait_vm() {
-  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
-}
 
 #define NS_U(x) __builtin_amdgcn_readfirstlane(x)
 
@@ -410,7 +388,7 @@ __global__ __launch_bounds__(64, 2) void attn_mfma_persist_kernel(PersistParams 
     auto store = [&]() {             // lane (query, hh) owns channels 32*dt + 8*ig + 4*hh + 0..3; kStoresPerQuery stores
 #pragma unroll
       for (int nt = 0; nt < 2; nt++) {
-        const float inv = 1.f / hswap_sum(l[nt]);
+        const float inv = 1.f / half_swap_sum(l[nt]);
         char *row = cq.ob + (size_t)(qbase + tile_off(l32 + 32 * nt)) * (size_t)(p.ost * 2) + 8 * hh;
 #pragma unroll
         for (int dt = 0; dt < 2; dt++)
@@ -461,7 +439,7 @@ __global__ __launch_bounds__(64, 2) void attn_mfma_persist_kernel(PersistParams 
             mx0 = fmaxf(fmaxf(mx0, s0[e]), s0[e + 1]);
             mx1 = fmaxf(fmaxf(mx1, s1[e]), s1[e + 1]);
           }
-          const float m_new = fmaxf(m[nt], hswap_max(fmaxf(mx0, mx1)) * p.c);
+          const float m_new = fmaxf(m[nt], half_swap_max(fmaxf(mx0, mx1)) * p.c);
           const float alpha = __builtin_amdgcn_exp2f(m[nt] - m_new);
           m[nt] = m_new;
           const float nmm = -m_new;
@@ -517,14 +495,7 @@ bool persist_attn_supported(const ns_attn_desc &d) {
 
 ns_status launch_attn_persist(const AttnArgs &a) {
   const ns_attn_desc &d = a.d;
-  static int num_cus = 0;
-  if (num_cus == 0) {
-    int dev = 0;
-    hipDeviceProp_t prop;
-    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
-      return fail(NS_ERR_HIP, "cannot query the device");
-    num_cus = prop.multiProcessorCount;
-  }
+  const int num_cus = device_cu_count();
   PersistParams p;
   p.q = static_cast<const uint16_t *>(a.q);
   p.k = static_cast<const uint16_t *>(a.k);

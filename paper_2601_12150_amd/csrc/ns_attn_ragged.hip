@@ -2,8 +2,8 @@
 // sequences, grids that the block side does not divide, and block sides other than 8 and 16.
 //
 // After pruning (paper, "Time-Efficiency Optimization") the sequence is [CLS; surviving patches] and
-// the mask is still defined on the survivors' original grid positions (paper, "Memory-Efficiency
-// Optimization": adjacency "in the original pixel space").  block_lists_kernel has bucketed the
+// the mask is still evaluated on each survivor's original grid position (paper, "Memory-Efficiency
+// Optimization").  block_lists_kernel has bucketed the
 // survivors by block (grid_lists_kernel does the same for a complete grid whose last blocks may be
 // short).  A block's list is cut into runs of 64 entries: a wave owns one run as its query tile
 // and walks the runs of the up to nine neighbouring blocks as key tiles, the rows beyond a run's
@@ -36,18 +36,6 @@ struct RaggedParams {
 
 typedef s16x4 __attribute__((address_space(3))) *lds_s16x4_ptr;
 
-__device__ __forceinline__ float rswap_max(float x) {
-  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-__device__ __forceinline__ float rswap_sum(float x) {
-  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-__device__ __forceinline__ void rdma16(const char *base, uint32_t voff, uint32_t lds) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :: "s"(lds), "v"(voff), "s"(base) : "memory", "m0");
-}
 
 // grid (ceil(nblocks*tpb/4), H, B), 256 threads: one wave per query tile (tpb = runs per block).
 __global__ __launch_bounds__(256, 2) void attn_mfma_ragged_kernel(RaggedParams p) {
@@ -122,7 +110,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_ragged_kernel(RaggedParams p
       for (int s = 0; s < 4; s++)
 #pragma unroll
         for (int j = 0; j < 8; j++) acc = __builtin_fmaf((float)qf[nt][s][j], (float)k0[s][j], acc);
-      m[nt] = rswap_sum(acc) * p.c;
+      m[nt] = half_swap_sum(acc) * p.c;
       l[nt] = hh == 0 ? 1.f : 0.f;
     }
 #pragma unroll
@@ -179,7 +167,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_ragged_kernel(RaggedParams p
 #pragma unroll
     for (int it = 0; it < 8; it++) {
       const uint32_t vt = (uint32_t)__shfl(tok, it * 8 + (lane >> 3));
-      rdma16(vb, vt * rowB + vchunk, lds_base + buf * 8192 + it * 1024);
+      dma16(vb, vt * rowB + vchunk, lds_base + buf * 8192 + it * 1024);
     }
 #pragma unroll
     for (int mt = 0; mt < 2; mt++) {
@@ -229,7 +217,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_ragged_kernel(RaggedParams p
         mx1 = fmaxf(fmaxf(mx1, s1[e]), s1[e + 1]);
       }
       // the tile holds at least one key, and m starts finite: m_new is finite
-      const float m_new = fmaxf(m[nt], rswap_max(fmaxf(mx0, mx1)) * p.c);
+      const float m_new = fmaxf(m[nt], half_swap_max(fmaxf(mx0, mx1)) * p.c);
       const float alpha = __builtin_amdgcn_exp2f(m[nt] - m_new);
       m[nt] = m_new;
       const float nm = -m_new;
@@ -282,7 +270,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_ragged_kernel(RaggedParams p
   char *ob = reinterpret_cast<char *>(p.out + b * p.osb + h * p.osh);
 #pragma unroll
   for (int nt = 0; nt < 2; nt++) {
-    const float inv = 1.f / rswap_sum(l[nt]);
+    const float inv = 1.f / half_swap_sum(l[nt]);
     if (l32 + 32 * nt >= qcnt) continue;
     char *row = ob + (size_t)qrow[nt] * (size_t)(p.ost * 2) + 8 * hh;
 #pragma unroll

@@ -54,7 +54,6 @@ struct SweepParams {
 
 typedef s16x4 __attribute__((address_space(3))) *lds_s16x4_ptr;
 typedef bf16x8 __attribute__((address_space(3))) *lds_bf16x8_ptr;
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr uint32_t kSlot = 16384;     // one key tile: K [64][64] bf16, then V [64][64] bf16
 constexpr uint32_t kVOff = 8192;
@@ -67,31 +66,6 @@ constexpr uint32_t kClsLogit = 3 * 16384 + 3072 + 4 * 512;   // per wave 256 B: 
 constexpr float kEmptyMax = -1e30f;
 constexpr float kMasked = -1e30f;     // logit of a key that does not exist (edge blocks of a grid 8 does not divide)
 
-__device__ __forceinline__ float sswap_max(float x) {
-  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-__device__ __forceinline__ float sswap_sum(float x) {
-  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-// 16 bytes per lane, global -> LDS at lds + 16*lane, no registers.
-__device__ __forceinline__ void sdma16(const char *base, uint32_t voff, uint32_t lds) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :: "s"(lds), "v"(voff), "s"(base) : "memory", "m0");
-}
-// 4 bytes per lane to global memory, one request.
-__device__ __forceinline__ void sstore4(void *ptr, float v) {
-  asm volatile("global_store_dword %0, %1, off" :: "v"(ptr), "v"(v) : "memory");
-}
-// 8 bytes per lane to global memory, issued from asm so that it is exactly one request.
-__device__ __forceinline__ void sstore8(void *ptr, u32x2 v) {
-  asm volatile("global_store_dwordx2 %0, %1, off" :: "v"(ptr), "v"(v) : "memory");
-}
-template <int N>
-__device__ __forceinline__ void swait_vm() {
-  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
-}
 
 #define NS_U(x) __builtin_amdgcn_readfirstlane(x)
 
@@ -201,12 +175,12 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
 #pragma unroll
     for (int j = 0; j < 2; j++) {
       const char *src = kb + base + (size_t)min(2 * wave + j, hvk - 1) * gridrowB;
-      sdma16(src, dma_koff[j] - back, dst + j * 1024);
+      dma16(src, dma_koff[j] - back, dst + j * 1024);
     }
 #pragma unroll
     for (int j = 0; j < 2; j++) {
       const char *src = vb + base + (size_t)min(2 * wave + j, hvk - 1) * gridrowB;
-      sdma16(src, dma_voff - back, dst + kVOff + j * 1024);
+      dma16(src, dma_voff - back, dst + kVOff + j * 1024);
     }
     islot = islot == kSlots - 1 ? 0 : islot + 1;
     const bool last = ic == ncols - 1 && ir == nr - 1;
@@ -307,7 +281,7 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
     if (__any(!(big < 1e30f))) badmask |= 1u << (qc >> 2);
 #pragma unroll
     for (int nt = 0; nt < 2; nt++) {
-      const float inv = 1.f / sswap_sum(l[nt]);
+      const float inv = 1.f / half_swap_sum(l[nt]);
 #pragma unroll
       for (int dt = 0; dt < 2; dt++)
 #pragma unroll
@@ -327,7 +301,7 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
 #pragma unroll
       for (int dt = 0; dt < 2; dt++)
 #pragma unroll
-        for (int ig = 0; ig < 4; ig++) sstore8(row + 64 * dt + 16 * ig, packed[nt][dt][ig]);
+        for (int ig = 0; ig < 4; ig++) store8(row + 64 * dt + 16 * ig, packed[nt][dt][ig]);
     }
   };
 
@@ -371,12 +345,12 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
       // a key that does not exist repeats the store of the key it copies
       const int kr = min(lane >> 3, hvq - 1), kc = min(lane & 7, wvc - 1);
       const float x = cls_logit[8 * kr + kc];
-      sstore4(logit_row + block_token(R, col) + kr * p.grid_w + kc, x);
+      store4(logit_row + block_token(R, col) + kr * p.grid_w + kc, x);
     }
     float mx = fmaxf(sa[0], sb[0]);
 #pragma unroll
     for (int e = 1; e < 16; e++) mx = fmaxf(mx, fmaxf(sa[e], sb[e]));
-    mx = sswap_max(mx) * p.c;
+    mx = half_swap_max(mx) * p.c;
     float m2 = cls_state[64], l0 = cls_state[65];
     float k0logit = 0.f;
     if (with_global_key) {
@@ -389,7 +363,7 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
       for (int ks = 0; ks < 4; ks++) s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0[ks], q0f[ks], s0, 0, 0, 0);
       k0logit = s0[0];
       mx = fmaxf(mx, k0logit * p.c);
-      if (logit_row && lane == 0) sstore4(logit_row, k0logit * p.scale);
+      if (logit_row && lane == 0) store4(logit_row, k0logit * p.scale);
     }
     const float m_new = fmaxf(m2, mx);
     const float alpha = __builtin_amdgcn_exp2f(m2 - m_new), nmm = -m_new;
@@ -407,7 +381,7 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
       pa[e >> 3][e & 7] = ka[0]; pa[e >> 3][(e & 7) + 1] = ka[1];
       pb[e >> 3][e & 7] = kb2[0]; pb[e >> 3][(e & 7) + 1] = kb2[1];
     }
-    ls = sswap_sum(ls);                       // the two half-waves hold different keys
+    ls = half_swap_sum(ls);                       // the two half-waves hold different keys
     // O (one column's worth, the same in every column): channel 32*dt + 8*(e/4) + 4*hh + e%4
     f32x16 oc[2];
 #pragma unroll
@@ -463,16 +437,16 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
   // ---- prologue: the first three key tiles are requested, the first has landed
   int qc = wave;                     // this wave's query block in progress
   if (wave == 0) {                   // the global token's rows, 8 lanes x 16 bytes each (the other lanes repeat them)
-    sdma16(kb, 16u * (lane & 7), lds_base + kK0Row);
-    sdma16(vb, 16u * (lane & 7), lds_base + kV0Row);
-    sdma16(qb, 16u * (lane & 7), lds_base + kQ0Row);
+    dma16(kb, 16u * (lane & 7), lds_base + kK0Row);
+    dma16(vb, 16u * (lane & 7), lds_base + kV0Row);
+    dma16(qb, 16u * (lane & 7), lds_base + kQ0Row);
   }
   cls_state[lane] = 0.f;             // this wave's partial of the global query: nothing seen yet
   if (lane < 2) cls_state[64 + lane] = lane == 0 ? kEmptyMax : 0.f;
   issue_next();
   issue_next();
   issue_next();
-  swait_vm<8>();                     // k_0, v_0, q_0 and tile 0
+  wait_vm<8>();                     // k_0, v_0, q_0 and tile 0
   __syncthreads();
   // (loading and consuming the rows under ONE condition matters: the compiler places its waits
   // per program point, not per path, and a load that looks pending at the loop head would put a
@@ -555,12 +529,12 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
     }
     // tile s+1: this wave's share has landed (its share of tile s+2 and the stores above may still be in flight)
     switch (extra) {
-      case 0: swait_vm<4>(); break;
-      case 1: swait_vm<5>(); break;
-      case 2: swait_vm<6>(); break;
-      case kStores: swait_vm<4 + kStores>(); break;
-      case kStores + 1: swait_vm<5 + kStores>(); break;
-      default: swait_vm<6 + kStores>(); break;
+      case 0: wait_vm<4>(); break;
+      case 1: wait_vm<5>(); break;
+      case 2: wait_vm<6>(); break;
+      case kStores: wait_vm<4 + kStores>(); break;
+      case kStores + 1: wait_vm<5 + kStores>(); break;
+      default: wait_vm<6 + kStores>(); break;
     }
     // everybody's share of tile s+1 has landed; and everybody is done with tile s, whose slot tile s+3 takes
     __syncthreads();
@@ -569,7 +543,7 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
     ri++;
     if (ri == nr) { ri = 0; c++; }
   }
-  swait_vm<0>();
+  wait_vm<0>();
   if (p.cls_partials) {
     // this wave's partial of the global query's row: (max, sum, weighted V sum), natural-log units
     float *rec = p.cls_partials + ((((size_t)b * p.heads + h) * (4 * p.nbh)) + (size_t)R * 4 + wave) * kClsPartialFloats;
@@ -606,8 +580,8 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
         const uint32_t back = (uint32_t)max(drow - (wvk - 1), 0) * rowB;
 #pragma unroll
         for (int it = 0; it < 8; it++)
-          sdma16(vb + base + (size_t)min(it, hvk - 1) * gridrowB, dma_voff - back, lds_base + mine + kVOff + it * 1024);
-        swait_vm<0>();               // also the K fragments above
+          dma16(vb + base + (size_t)min(it, hvk - 1) * gridrowB, dma_voff - back, lds_base + mine + kVOff + it * 1024);
+        wait_vm<0>();               // also the K fragments above
 #pragma unroll
         for (int nt = 0; nt < 2; nt++) {
           f32x16 s0 = stage_a(kt[0], nt), s1 = stage_a(kt[1], nt);
@@ -626,7 +600,7 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
             mx0 = fmaxf(fmaxf(mx0, s0[e]), s0[e + 1]);
             mx1 = fmaxf(fmaxf(mx1, s1[e]), s1[e + 1]);
           }
-          const float m_new = fmaxf(m[nt], sswap_max(fmaxf(mx0, mx1)) * p.c);
+          const float m_new = fmaxf(m[nt], half_swap_max(fmaxf(mx0, mx1)) * p.c);
           const float alpha = __builtin_amdgcn_exp2f(m[nt] - m_new);
           m[nt] = m_new;
           const float nmm = -m_new;
@@ -693,32 +667,16 @@ ns_status launch_attn_sweep(const AttnArgs &a, float *cls_logits, float *cls_par
   // a wave records the query blocks it has to redo in a 32-bit mask
   if (p.nbw > 128) return fail(NS_ERR_UNSUPPORTED, "more than 128 blocks per grid row");
   p.strips = (int)strips;
-  {
-    static int num_cus = 0;
-    if (num_cus == 0) {
-      int dev = 0;
-      hipDeviceProp_t prop;
-      num_cus = (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-                    ? prop.multiProcessorCount : 256;
-    }
-    p.num_cus = num_cus;
-  }
+  p.num_cus = device_cu_count();
   typedef void (*kern_t)(SweepParams);
   static const kern_t kerns[3][2] = {{attn_sweep_kernel<false, 8>, attn_sweep_kernel<true, 8>},
                                      {attn_sweep_kernel<false, 4>, attn_sweep_kernel<true, 4>},
                                      {attn_sweep_kernel<false, 2>, attn_sweep_kernel<true, 2>}};
-  static bool attr_set = false;
   const int lds = 4 * 16384;        // three ring slots and the global token's rows; the redo gives each wave a slot
-  if (!attr_set) {
-    for (int i = 0; i < 3; i++)
-      for (int j = 0; j < 2; j++)
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kerns[i][j]), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                lds) != hipSuccess)
-          return fail(NS_ERR_HIP, "cannot reserve %d bytes of LDS", lds);
-    attr_set = true;
-  }
   const int wi = d.block == 8 ? 0 : (d.block == 4 ? 1 : 2);
   const int ei = (d.grid_h % 8 == 0 && d.grid_w % 8 == 0) ? 0 : 1;
+  const ns_status rs = reserve_lds_once(reinterpret_cast<const void *>(kerns[wi][ei]), lds);
+  if (rs != NS_OK) return rs;
   hipLaunchKernelGGL(kerns[wi][ei], dim3((unsigned)strips), dim3(256), lds, a.stream, p);
   return check_launch("attn_sweep_kernel");
 }

@@ -81,6 +81,47 @@ __device__ __forceinline__ int block_token(const BlockGeom &g, int b, int R, int
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// ---- device helpers shared by the MFMA kernels ------------------------------
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// max / sum of a value over the two half-waves (lane l and lane l ^ 32); both lanes get it
+__device__ __forceinline__ float half_swap_max(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float half_swap_sum(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+// 16 bytes per lane, global -> LDS, no registers: LDS address = lds + 16 * lane.  Issued as asm
+// so that the compiler does not guard later LDS reads with a full vmcnt(0) wait (it cannot tell
+// one tile's transfer from the next tile's, which is still in flight); the kernels order and
+// count their memory requests themselves (wait_vm).
+__device__ __forceinline__ void dma16(const char *base, uint32_t voff, uint32_t lds) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(lds), "v"(voff), "s"(base) : "memory", "m0");
+}
+// 4 / 8 bytes per lane to global memory, issued from asm so that each is exactly one request
+__device__ __forceinline__ void store4(void *ptr, float v) {
+  asm volatile("global_store_dword %0, %1, off" :: "v"(ptr), "v"(v) : "memory");
+}
+__device__ __forceinline__ void store8(void *ptr, u32x2 v) {
+  asm volatile("global_store_dwordx2 %0, %1, off" :: "v"(ptr), "v"(v) : "memory");
+}
+// at most N vector memory requests of this wave still in flight (they complete in issue order)
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+
+// ---- host helpers -------------------------------------------------------------
+// Compute units of the current device (256 if the query fails).  Thread-safe; looked up once.
+int device_cu_count();
+// hipFuncSetAttribute(MaxDynamicSharedMemorySize) for a kernel that wants more than 64 KB of LDS;
+// every kernel is set up once per process (thread-safe).  `slot` tells the kernels of a file apart.
+ns_status reserve_lds_once(const void *kernel, int bytes);
+
+
 // ---- launchers implemented in the individual .hip files --------------------
 struct AttnArgs {
   ns_attn_desc d;
@@ -88,6 +129,7 @@ struct AttnArgs {
   void *out;
   BlockGeom geom;
   hipStream_t stream;
+  int kernel;            // the patch-query kernel chosen for this call (ns_api.hip: PatchKernel)
 };
 
 // ns_attn_forward with one more knob: reuse_lists = the per-block token lists that an earlier call

@@ -52,14 +52,6 @@ constexpr int kEpiWave = 32 * kEpiRow;
 typedef bf16x8 __attribute__((address_space(3))) *lds_bf16x8_ptr;
 
 
-__device__ __forceinline__ void gdma16(const char *base, uint32_t voff, uint32_t lds) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :: "s"(lds), "v"(voff), "s"(base) : "memory", "m0");
-}
-template <int N>
-__device__ __forceinline__ void gwait_vm() {
-  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
-}
 
 // Accumulators of NS weight slabs x one 32-token slab -> LDS (fp32, [token][32*NS n]) -> lanes that
 // own 8 consecutive n of one token: + bias, GELU, + residual, one 16-byte store.
@@ -162,9 +154,9 @@ __device__ __forceinline__ void gemm256_wave(const Gemm256Params &p, unsigned ch
     const char *ak = ab + (size_t)kt * 128, *wk = wb + (size_t)kt * 128;
     const uint32_t base = lds0 + stage * kStage;
 #pragma unroll
-    for (int j = 0; j < 8; j++) gdma16(wk + (size_t)j * 8 * rowB, woff[j & 1], base + (wreq0 + j) * 1024);
+    for (int j = 0; j < 8; j++) dma16(wk + (size_t)j * 8 * rowB, woff[j & 1], base + (wreq0 + j) * 1024);
 #pragma unroll
-    for (int j = 0; j < XREQ; j++) gdma16(ak, xoff[j], base + kStageW + (xreq0 + j) * 1024);
+    for (int j = 0; j < XREQ; j++) dma16(ak, xoff[j], base + kStageW + (xreq0 + j) * 1024);
   };
   constexpr int PER_SLICE = 8 + XREQ;
 
@@ -233,7 +225,7 @@ __device__ __forceinline__ void gemm256_wave(const Gemm256Params &p, unsigned ch
   const int nk = p.K / 64;
   issue(0, 0);
   issue(min(1, nk - 1), 1);
-  gwait_vm<PER_SLICE>();
+  wait_vm<PER_SLICE>();
   __syncthreads();
   read_frags(0, 0, 0);
   for (int kt = 0; kt < nk; kt++) {
@@ -247,7 +239,7 @@ __device__ __forceinline__ void gemm256_wave(const Gemm256Params &p, unsigned ch
     read_frags(1, cur, 3);
     mma(0);
     interleave();
-    gwait_vm<0>();                                     // slice kt+1 (this wave's share)
+    wait_vm<0>();                                     // slice kt+1 (this wave's share)
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the fragments of slice kt are in registers
     __syncthreads();
     issue(min(kt + 2, nk - 1), cur);
@@ -255,7 +247,7 @@ __device__ __forceinline__ void gemm256_wave(const Gemm256Params &p, unsigned ch
     mma(1);
     interleave();
   }
-  gwait_vm<0>();               // the repeated requests of the last iterations
+  wait_vm<0>();               // the repeated requests of the last iterations
   __syncthreads();             // every wave is done with the stages: they become the epilogue's staging area
 
   // ---- epilogue, one 32-token slab at a time
@@ -333,13 +325,7 @@ ns_status launch_gemm256(const uint16_t *a, const uint16_t *w, const float *bias
     // Rows of tiles: a of 256 token rows, then b of 192, a*256 + b*192 >= M.  Workgroups start in
     // launch order, a CU takes the next one when it is free: the mix with the shortest makespan
     // (a 192-row tile costs 0.8 of a 256-row one).
-    static int cus = 0;
-    if (cus == 0) {
-      int dev = 0;
-      hipDeviceProp_t prop;
-      cus = (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-                ? prop.multiProcessorCount : 256;
-    }
+    const int cus = device_cu_count();
     auto makespan = [&](long long na, long long nb) -> double {
       // na*ntn tiles of cost 1.0, then nb*ntn of cost 0.8, each given to the unit that is free first.
       // After the tall tiles n2 units are free at t2 and the other n1 one tile time earlier, at t1.
@@ -377,14 +363,8 @@ ns_status launch_gemm256(const uint16_t *a, const uint16_t *w, const float *bias
   typedef void (*kern_t)(Gemm256Params);
   static const kern_t kerns[4] = {gemm256_bf16_kernel<false, false>, gemm256_bf16_kernel<false, true>,
                                   gemm256_bf16_kernel<true, false>, gemm256_bf16_kernel<true, true>};
-  static bool attr_set = false;
-  if (!attr_set) {
-    for (int i = 0; i < 4; i++)
-      if (hipFuncSetAttribute(reinterpret_cast<const void *>(kerns[i]), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              kStages * kStage) != hipSuccess)
-        return fail(NS_ERR_HIP, "cannot reserve %d bytes of LDS", kStages * kStage);
-    attr_set = true;
-  }
+  const ns_status rs = reserve_lds_once(reinterpret_cast<const void *>(kerns[(gelu ? 2 : 0) + (r ? 1 : 0)]), kStages * kStage);
+  if (rs != NS_OK) return rs;
   hipLaunchKernelGGL(kerns[(gelu ? 2 : 0) + (r ? 1 : 0)], dim3((unsigned)wgs), dim3(256), kStages * kStage, s, p);
   return check_launch("gemm256_bf16_kernel");
 }

@@ -81,10 +81,6 @@ struct GemmParams {
   int gelu;
 };
 
-__device__ __forceinline__ void dma16(const char *base, uint32_t voff, uint32_t lds) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :: "s"(lds), "v"(voff), "s"(base) : "memory", "m0");
-}
 
 typedef bf16x8 __attribute__((address_space(3))) *lds_bf16x8_ptr;
 
@@ -204,9 +200,9 @@ ns_status launch_layernorm(const uint16_t *x, const float *g, const float *b, ui
 
 ns_status launch_gemm(const uint16_t *a, const uint16_t *w, const float *bias, const uint16_t *r,
                       uint16_t *c, int M, int N, int K, bool gelu, hipStream_t s) {
-  // NSATTN_GEMM=128 keeps the 128 x 128 kernel for every shape
-  const char *e = getenv("NSATTN_GEMM");
-  if (gemm256_supported(M, N, K) && !(e && e[0] == '1')) return launch_gemm256(a, w, bias, r, c, M, N, K, gelu, s);
+  // NSATTN_GEMM=128 keeps the 128 x 128 kernel for every shape; read once per process
+  static const bool only128 = [] { const char *e = getenv("NSATTN_GEMM"); return e && e[0] == '1'; }();
+  if (gemm256_supported(M, N, K) && !only128) return launch_gemm256(a, w, bias, r, c, M, N, K, gelu, s);
   if (N % 128 || K % 64) return fail(NS_ERR_UNSUPPORTED, "GEMM needs N %% 128 == 0 and K %% 64 == 0 (N=%d K=%d)", N, K);
   if ((long long)M * K * 2 >= 0x7fffffffLL || (long long)N * K * 2 >= 0x7fffffffLL)
     return fail(NS_ERR_UNSUPPORTED, "GEMM operand beyond 2 GiB");
