@@ -218,7 +218,9 @@ def measure_stages(nb, torch, sets, cfg, g, blk, k, C, B, H, T, D, ws, desc0, fl
     # (256 images x 16,384 scores, one workgroup per image), as a streaming rate
     nb_img, nb_n = 256, 16384
     nb_k = (nb_n * 60 + 99) // 100
-    bs = torch.rand((nb_img, nb_n), device="cuda", dtype=torch.float32)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5)
+    bs = torch.rand((nb_img, nb_n), device="cuda", dtype=torch.float32, generator=gen)
     bkept = torch.empty((nb_img, nb_k), dtype=torch.int32, device="cuda")
     t_batched = time_call(lambda s: nb.topk_filter(bs, nb_k, kept_idx=bkept))
     bytes_batched = nb_img * nb_n * 4 + nb_img * nb_k * 4
@@ -239,8 +241,8 @@ def measure_stages(nb, torch, sets, cfg, g, blk, k, C, B, H, T, D, ws, desc0, fl
 
 def measure_vit_stack(nb, torch, np, synth, layers=24, dim=1024, mlp=4096, heads=16, g=128, blk=8, after=12):
     """24 pre-LN blocks on [1, 1+128*128, 1024] bf16 tokens, pruning to 60 % after block 12.  Weights are
-    random (N(0, 0.02^2)); one set is generated and uploaded per layer.  The input tokens are synthetic
-    pixels through vit_embed."""
+    random (N(0, 0.02^2)); one set is generated and uploaded per layer.  The input tokens are the seeded
+    synthetic tile through vit_embed."""
     N = g * g
     keep = (N * 60 + 99) // 100
     ws = []
@@ -248,13 +250,15 @@ def measure_vit_stack(nb, torch, np, synth, layers=24, dim=1024, mlp=4096, heads
         w = synth.make_block_weights(dim, mlp, seed=100 + i)
         ws.append({kk: (torch.from_numpy(vv).to(torch.bfloat16) if kk.startswith("w_") else torch.from_numpy(vv)).cuda()
                    for kk, vv in w.items()})
-    # tokens from synthetic pixels through the backbone's patch embedding (14-pixel patches)
-    ps = 14
-    pixels = torch.randn(1, 3, g * ps, g * ps, device="cuda").to(torch.bfloat16)
-    w_patch = (torch.randn(dim, 3 * ps * ps, device="cuda") * 0.02).to(torch.bfloat16)
-    b_patch = torch.zeros(dim, device="cuda")
-    cls_token = (torch.randn(dim, device="cuda") * 0.02).to(torch.bfloat16)
-    pos_embed = (torch.randn(1 + N, dim, device="cuda") * 0.02).to(torch.bfloat16)
+    # tokens from the seeded synthetic tile (2048 x 2048 RGB, 40 % near-white background rectangles,
+    # gradient-noise tissue) through the backbone's patch embedding with 16-pixel patches
+    ps = 16
+    tile, bg = synth.make_tile(seed=5, side=g * ps, patch=ps, background=0.40)
+    e = synth.make_embed_weights(dim, ps, N, seed=5)
+    pixels = torch.from_numpy(tile).to(torch.bfloat16).cuda()
+    w_patch, cls_token, pos_embed = (torch.from_numpy(e[n]).to(torch.bfloat16).cuda()
+                                     for n in ("w_patch", "cls_token", "pos_embed"))
+    b_patch = torch.from_numpy(e["b_patch"]).cuda()
     x = torch.empty(1, 1 + N, dim, device="cuda", dtype=torch.bfloat16)
     nb.vit_embed(pixels, w_patch, b_patch, cls_token, pos_embed, ps, out=x)
     torch.cuda.synchronize()
@@ -263,8 +267,6 @@ def measure_vit_stack(nb, torch, np, synth, layers=24, dim=1024, mlp=4096, heads
         nb.vit_embed(pixels, w_patch, b_patch, cls_token, pos_embed, ps, out=x)
     torch.cuda.synchronize()
     dte = (time.perf_counter() - t) / 5
-    # (the blocks below see unit-variance tokens, as after a trained embedding)
-    x = (x.float() / x.float().std()).to(torch.bfloat16)
     import ctypes
     out = torch.empty((1, 1 + keep, dim), dtype=torch.bfloat16, device="cuda")
     wsb = torch.empty(6 << 30, dtype=torch.uint8, device="cuda")
@@ -305,13 +307,15 @@ def measure_vit_stack(nb, torch, np, synth, layers=24, dim=1024, mlp=4096, heads
         return (time.perf_counter() - t0) / reps * 1e6
     M = 1 + N
     mine_us = lib_us = 0.0
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5)
     for (n_out, k_in, gelu, res) in ((3 * dim, dim, False, False), (dim, dim, False, True), (mlp, dim, True, False),
                                      (dim, mlp, False, True)):
-        xa = torch.randn(M, k_in, device="cuda").to(torch.bfloat16)
-        wa = (torch.randn(n_out, k_in, device="cuda") * 0.02).to(torch.bfloat16)
+        xa = torch.randn(M, k_in, device="cuda", generator=gen).to(torch.bfloat16)
+        wa = (torch.randn(n_out, k_in, device="cuda", generator=gen) * 0.02).to(torch.bfloat16)
         ba = torch.zeros(n_out, device="cuda")
         bb = ba.to(torch.bfloat16)
-        ra = torch.randn(M, n_out, device="cuda").to(torch.bfloat16) if res else None
+        ra = torch.randn(M, n_out, device="cuda", generator=gen).to(torch.bfloat16) if res else None
         ya = torch.empty(M, n_out, device="cuda", dtype=torch.bfloat16)
         mine_us += t_us(lambda: nb.linear_forward(xa, wa, ba, ra, gelu=gelu, out=ya))
 
@@ -328,7 +332,8 @@ def measure_vit_stack(nb, torch, np, synth, layers=24, dim=1024, mlp=4096, heads
             "vit_patch_embed_ms": dte * 1e3,
             "vit_layer_linear_maps_us": mine_us, "vit_layer_linear_maps_vendor_library_us": lib_us,
             "vit_l24_tokens_per_s": (1 + N) / dt,
-            "vit_l24_gemm_tflops_if_all_gemm": gemm_flops / dt / 1e12, "vit_l24_kept": keep}
+            "vit_l24_gemm_tflops_if_all_gemm": gemm_flops / dt / 1e12, "vit_l24_kept": keep,
+            "vit_tile_background_fraction": float(bg.mean())}
 
 
 def cpu_baseline(np, cfg, q, kk, v, g, blk, k, B, H, T, seconds):

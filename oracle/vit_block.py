@@ -23,10 +23,9 @@ from __future__ import annotations
 import math
 
 import numpy as np
+from scipy.special import erf as _erf    # the error function as a library routine, float64
 
 from . import cls_scores, ns_attn
-
-_erf = np.vectorize(math.erf, otypes=[np.float64])
 
 
 def round_bf16(x):

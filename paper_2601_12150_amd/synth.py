@@ -187,3 +187,65 @@ def make_block_weights(dim: int, mlp_dim: int, seed: int = 0, dtype: str = "bf16
             w[n + "_g"] = np.ones(dim, dtype=np.float32)
             w[n + "_b"] = np.zeros(dim, dtype=np.float32)
     return w
+
+
+def _fade(t: np.ndarray) -> np.ndarray:
+    return t * t * t * (t * (t * 6.0 - 15.0) + 10.0)
+
+
+def gradient_noise(rng: np.random.Generator, side: int, period: int) -> np.ndarray:
+    """[side, side] float32 lattice gradient noise (Perlin's construction): a random unit gradient
+    at every lattice point `period` pixels apart; a pixel's value blends the four dot products
+    (gradient . offset to the pixel) of its cell's corners with the quintic fade curve.  Values lie
+    in about [-0.7, 0.7] and vanish towards the lattice points (pixel centres sit half a pixel off)."""
+    n = side // period + 2
+    ang = rng.uniform(0.0, 2.0 * np.pi, size=(n, n))
+    gy, gx = np.sin(ang).astype(np.float32), np.cos(ang).astype(np.float32)
+    p = (np.arange(side, dtype=np.float64) + 0.5) / period
+    i = np.floor(p).astype(np.int64)
+    f = (p - i).astype(np.float32)
+    fy, fx = f[:, None], f[None, :]
+    def corner(dy, dx):
+        def spread(a):   # lattice values of every pixel's cell corner
+            return np.take(np.take(a, i + dy, axis=0), i + dx, axis=1)
+        return spread(gy) * (fy - np.float32(dy)) + spread(gx) * (fx - np.float32(dx))
+    u, v = _fade(fx), _fade(fy)
+    top = corner(0, 0) * (1 - u) + corner(0, 1) * u
+    bot = corner(1, 0) * (1 - u) + corner(1, 1) * u
+    return (top * (1 - v) + bot * v).astype(np.float32)
+
+
+def make_tile(seed: int = 5, side: int = 2048, patch: int = 16, background: float = 0.40, batch: int = 1):
+    """A synthetic stained-tissue tile: pixels [batch, 3, side, side] float32 (bf16-representable,
+    normalised as (p - 0.5) / 0.25 from p in [0, 1]) and the background mask [batch, side/patch,
+    side/patch].  Background = the union of seeded rectangles in units of patches (the recipe of
+    the 128 x 128 attention workload), near white (0.94 +- 0.02); everywhere else each colour
+    channel is a stain-like base colour plus four octaves of seeded gradient noise (periods 256,
+    128, 64, 32 pixels, amplitudes halving) and a little pixel noise."""
+    g = side // patch
+    bg = background_mask(g, background, seed, batch)
+    base = np.array([0.72, 0.42, 0.68], dtype=np.float32)
+    pixels = np.empty((batch, 3, side, side), dtype=np.float32)
+    for b in range(batch):
+        mask = np.repeat(np.repeat(bg[b], patch, axis=0), patch, axis=1)
+        for c in range(3):
+            rng = _rng(seed, 200 + 3 * b + c)
+            tissue = np.full((side, side), base[c], dtype=np.float32)
+            for o in range(4):
+                tissue += np.float32(0.45 / (1 << o)) * gradient_noise(rng, side, 256 >> o)
+            tissue += np.float32(0.02) * rng.standard_normal((side, side), dtype=np.float32)
+            white = np.float32(0.94) + np.float32(0.02) * rng.uniform(-1.0, 1.0, size=(side, side)).astype(np.float32)
+            pixels[b, c] = np.where(mask, white, np.clip(tissue, 0.0, 1.0))
+    pixels = (pixels - np.float32(0.5)) / np.float32(0.25)
+    return round_to_bf16(pixels), bg
+
+
+def make_embed_weights(dim: int, patch: int, n_patches: int, channels: int = 3, seed: int = 0, dtype: str = "bf16"):
+    """Random-init tokenisation weights: projection [dim, channels*patch*patch], CLS token [dim] and
+    position embeddings [1+n_patches, dim] ~N(0, 0.02^2) in `dtype`; projection bias fp32 ~N(0, 0.02^2)."""
+    g = _rng(seed, 90)
+    def arr(*shape):
+        return _finish(np.float32(0.02) * g.standard_normal(shape, dtype=np.float32), dtype)
+    return {"w_patch": arr(dim, channels * patch * patch),
+            "b_patch": (np.float32(0.02) * g.standard_normal(dim, dtype=np.float32)).astype(np.float32),
+            "cls_token": arr(dim), "pos_embed": arr(1 + n_patches, dim)}
