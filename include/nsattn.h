@@ -159,7 +159,7 @@ ns_status cls_scores_from_logits(int32_t batch, int32_t heads, int32_t tokens, i
  *              row 1+t = x row 1+kept_idx[t]; bit copies.  C*elt must be a multiple of 16.
  *   coords_out out, nullable (required iff coords_in given) [B,k]
  *   workspace  device scratch of topk_filter_workspace_bytes(batch, n, k) bytes, 16-byte aligned
- *              (0 bytes for n <= 16384: NULL is accepted then); NS_ERR_WORKSPACE if missing or short.
+ *              (0 bytes for n <= 32768: NULL is accepted then); NS_ERR_WORKSPACE if missing or short.
  *              Rows longer than that are selected by several workgroups per image, which exchange
  *              digit histograms through it between launches.
  */

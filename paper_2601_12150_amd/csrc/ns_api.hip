@@ -384,7 +384,7 @@ ns_status cls_scores_from_logits(int32_t batch, int32_t heads, int32_t tokens, i
 size_t topk_filter_workspace_bytes(int32_t batch, int32_t n, int32_t k) {
   (void)k;
   if (batch < 1 || n < 1) return 0;
-  return topk_select_workspace_bytes(batch, n);   // 0 for n <= 16384: the selection keeps its state in LDS
+  return topk_select_workspace_bytes(batch, n);   // 0 for n <= 32768: the selection keeps its state in registers and LDS
 }
 
 ns_status topk_filter(int32_t batch, int32_t n, int32_t k, const float *scores, const void *x,

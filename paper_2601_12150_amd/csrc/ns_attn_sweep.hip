@@ -343,7 +343,11 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
       }
       // lane = key of the tile: token (grid row 8R + lane/8, grid column 8*col + lane%8); the lane of
       // a key that does not exist repeats the store of the key it copies
-      const int kr = min(lane >> 3, hvq - 1), kc = min(lane & 7, wvc - 1);
+      // (addresses computed here, from an untraceable copy of the lane number: hoisted out of the
+      // key-tile loop they cost three registers that the compute branch does not have, and their
+      // reload from scratch memory waits for every transfer in flight)
+      const int ln = opaque(lane);
+      const int kr = min(ln >> 3, hvq - 1), kc = min(ln & 7, wvc - 1);
       const float x = cls_logit[8 * kr + kc];
       store4(logit_row + block_token(R, col) + kr * p.grid_w + kc, x);
     }

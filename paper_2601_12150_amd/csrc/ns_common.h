@@ -84,6 +84,13 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // ---- device helpers shared by the MFMA kernels ------------------------------
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
+// A value the compiler can no longer trace back: what is computed from it stays where it is written
+// instead of being hoisted out of a loop into registers that live for the whole kernel.
+__device__ __forceinline__ int opaque(int x) {
+  asm volatile("" : "+v"(x));
+  return x;
+}
+
 // max / sum of a value over the two half-waves (lane l and lane l ^ 32); both lanes get it
 __device__ __forceinline__ float half_swap_max(float x) {
   auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);

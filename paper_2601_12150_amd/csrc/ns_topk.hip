@@ -4,8 +4,9 @@
 // Exact k-th largest score on an order-preserving integer image of the floats, then an
 // in-index-order compaction, so the kept indices come out ascending and exact ties resolve to
 // the lower index.
-//   topk_select_reg_kernel: rows of up to 16384 scores, one workgroup of 16 waves per image, keys
-//     in registers, four 8-bit digit passes (radix select): latency-bound, a score row is 64 KB.
+//   topk_select_reg_kernel: rows of up to 32768 scores, one workgroup of 16 waves per image, keys
+//     in registers, 8-bit digit passes (radix select) until at most 1024 candidates are left, which
+//     are ranked against each other: latency-bound, a score row is 64 - 128 KB.
 //   topk_digit_pass_kernel / topk_place_kernel: longer rows, several
 //     workgroups per image, four 8-bit digit passes (radix select), one launch each.
 // gather_rows_kernel: copies the kept token rows (and the global rows) with 16-byte accesses.
@@ -41,18 +42,47 @@ __device__ __forceinline__ void wave_histogram_add(uint32_t *h, bool cand, uint3
   if ((rem >> lane) & 1ull) atomicAdd(&h[digit], 1u);
 }
 
+// Sums inside a wave without a trip through LDS: DPP row shifts add up the 16 lanes of a row, the
+// four row totals travel through scalar registers.
+// Inclusive prefix sum over the lanes of a wave (lane l: x of lanes 0..l).
+__device__ __forceinline__ uint32_t wave_prefix_incl(uint32_t x, int lane) {
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xf, 0xf, true);   // row_shr:1
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xf, 0xf, true);
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xf, 0xf, true);
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xf, 0xf, true);
+  const uint32_t r0 = (uint32_t)__builtin_amdgcn_readlane((int)x, 15), r1 = (uint32_t)__builtin_amdgcn_readlane((int)x, 31),
+                 r2 = (uint32_t)__builtin_amdgcn_readlane((int)x, 47);
+  const int row = lane >> 4;
+  return x + (row > 0 ? r0 : 0u) + (row > 1 ? r1 : 0u) + (row > 2 ? r2 : 0u);
+}
+// Inclusive suffix sum (lane l: x of lanes l..63).
+__device__ __forceinline__ uint32_t wave_suffix_incl(uint32_t x, int lane) {
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x101, 0xf, 0xf, true);   // row_shl:1
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x102, 0xf, 0xf, true);
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x104, 0xf, 0xf, true);
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x108, 0xf, 0xf, true);
+  const uint32_t r1 = (uint32_t)__builtin_amdgcn_readlane((int)x, 16), r2 = (uint32_t)__builtin_amdgcn_readlane((int)x, 32),
+                 r3 = (uint32_t)__builtin_amdgcn_readlane((int)x, 48);
+  const int row = lane >> 4;
+  return x + (row < 1 ? r1 : 0u) + (row < 2 ? r2 : 0u) + (row < 3 ? r3 : 0u);
+}
+// Sum of x over lanes 0..15 (one DPP row), the same in every lane.
+__device__ __forceinline__ uint32_t row0_total(uint32_t x) {
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xf, 0xf, true);
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xf, 0xf, true);
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xf, 0xf, true);
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xf, 0xf, true);
+  return (uint32_t)__builtin_amdgcn_readlane((int)x, 15);
+}
+
 // Threads 0..255 bring the number of candidates per digit; sel[0] = the digit that holds the
-// need-th largest candidate, sel[1] = how many keys of that digit are still needed.
+// need-th largest candidate, sel[1] = how many keys of that digit are still needed, sel[2] = how
+// many candidates that digit holds.
 __device__ __forceinline__ void choose_digit(uint32_t tot, uint32_t need, int tid, int wave, int lane,
                                              uint32_t *wtot, uint32_t *sel) {
   uint32_t above = 0;
   if (tid < 256) {
-    uint32_t incl = tot;   // inclusive suffix sum inside the wave: lanes >= lane
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const uint32_t t = __shfl_down(incl, off);
-      if (lane + off < 64) incl += t;
-    }
+    const uint32_t incl = wave_suffix_incl(tot, lane);   // lanes >= lane
     if (lane == 0) wtot[wave] = incl;
     above = incl - tot;
   }
@@ -62,122 +92,170 @@ __device__ __forceinline__ void choose_digit(uint32_t tot, uint32_t need, int ti
     if (above < need && need <= above + tot) {   // exactly one digit satisfies this
       sel[0] = (uint32_t)tid;
       sel[1] = need - above;
+      sel[2] = tot;
     }
   }
   __syncthreads();
 }
 
-// Rows of N <= 1024 * KPT scores: every thread keeps its KPT keys in registers (thread t holds
-// indices i*1024 + t), so the selection and the compaction read global memory exactly once.
+constexpr int kDirectMax = 1024;   // candidates that the direct ranking below takes: one per thread
+
+// Rows of N <= 1024 * KPT scores, one workgroup per image, every key in a register: the selection
+// and the compaction read global memory exactly once.  Wave w owns the 64*KPT consecutive indices
+// from w*64*KPT; in its group i (256 indices) lane l holds the four indices 256*i + 4*l .. + 3.
+// So a wave loads 1 KB of consecutive scores per instruction, index order is (wave, group, lane,
+// element), and the kept indices of a group go to consecutive output positions in lane order.
 template <int KPT>
 __global__ __launch_bounds__(kSelThreads) void topk_select_reg_kernel(const float *scores, int N, int k,
                                                                       const int32_t *coords_in,
                                                                       int32_t *kept,
                                                                       int32_t *coords_out) {
+  static_assert(KPT % 4 == 0, "keys are held in groups of four");
   const int b = blockIdx.x;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const float *sc = scores + (size_t)b * N;
-  __shared__ uint32_t wtot[2][kSelWaves];
-  __shared__ uint32_t hist[256 * 32];
-  __shared__ uint32_t wsum[4], sel[2];
-  __shared__ uint32_t pgt[KPT * kSelWaves], peq[KPT * kSelWaves];   // per (i, wave) counts -> prefixes
-  __shared__ uint32_t sgt[kSelWaves], seq[kSelWaves];
+  __shared__ __attribute__((aligned(16))) uint32_t hist[256 * 32];
+  __shared__ uint32_t wsum[4], sel[3], ncand;
+  __shared__ uint32_t wgt[kSelWaves], weq[kSelWaves];
 
   // Padding slots hold key 0.  A real key is never 0 (that would be a NaN bit pattern), and
   // tau, the k-th largest real key, is therefore > 0: padding never passes "> tau" or "== tau".
   uint32_t key[KPT];
+  const int j0 = wave * (64 * KPT) + 4 * lane;       // index of key[4*i + e]: j0 + 256*i + e
+  const bool vec = (reinterpret_cast<uintptr_t>(sc) & 15) == 0;
 #pragma unroll
-  for (int i = 0; i < KPT; i++) {
-    const int j = i * kSelThreads + tid;
-    key[i] = j < N ? order_key(sc[j]) : 0u;
+  for (int i = 0; i < KPT / 4; i++) {
+    const int j = j0 + 256 * i;
+    if (vec && j + 4 <= N) {
+      const f32x4 x = *reinterpret_cast<const f32x4 *>(sc + j);
+#pragma unroll
+      for (int e = 0; e < 4; e++) key[4 * i + e] = order_key(x[e]);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; e++) key[4 * i + e] = j + e < N ? order_key(sc[j + e]) : 0u;
+    }
   }
-  auto block_total = [&](uint32_t wave_count, int slot) -> uint32_t {
-    if (lane == 0) wtot[slot][wave] = wave_count;
-    __syncthreads();
-    uint32_t t = lane < kSelWaves ? wtot[slot][lane] : 0u;
-    // sum over lanes 0..15 (one DPP row): row_shr 1, 2, 4, 8 leaves the total in lane 15
-    t += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)t, 0x111, 0xf, 0xf, true);
-    t += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)t, 0x112, 0xf, 0xf, true);
-    t += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)t, 0x114, 0xf, 0xf, true);
-    t += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)t, 0x118, 0xf, 0xf, true);
-    return (uint32_t)__builtin_amdgcn_readlane((int)t, 15);
-  };
-  // k-th largest key by four 8-bit digit passes, most significant digit first (radix select): a
-  // pass histograms the digit of the keys that match the prefix chosen so far, and the digit that
-  // holds the left-th largest candidate extends the prefix.  The histogram is kept in 32 copies,
-  // bin d of copy c at word 32*d + c, and lane l adds to copy l % 32: scores that cluster (most
-  // keys of a wave in one bin) then still spread over 32 LDS banks instead of serialising on one
-  // address, so a pass costs the same whatever the scores look like.  Four passes of a few
-  // barriers each replace the 32 compare-and-count steps of a bisection over all keys (22 us for
-  // 16384 scores).
+  if (tid == 0) ncand = 0;
+  // k-th largest key by 8-bit digit passes, most significant digit first (radix select): a pass
+  // histograms the digit of the keys that match the prefix chosen so far, and the digit that holds
+  // the left-th largest candidate extends the prefix.  The histogram is kept in 32 copies, bin d of
+  // copy c at word 32*d + c, and lane l adds to copy l % 32: scores that cluster (most keys of a
+  // wave in one bin) then still spread over 32 LDS banks instead of serialising on one address, so
+  // a pass costs the same whatever the scores look like.  Once the candidates are few enough (after
+  // two digits, as a rule), they are ranked against each other directly instead.
+  // In the end `left` is the number of keys equal to tau that are kept.
   uint32_t tau = 0, left = (uint32_t)k;
+  uint4 *hist4 = reinterpret_cast<uint4 *>(hist);
   for (int pass = 0; pass < 4; pass++) {
-    for (int i = tid; i < 256 * 32; i += kSelThreads) hist[i] = 0;
-    __syncthreads();
     const uint32_t mask = pass ? 0xffffffffu << (32 - 8 * pass) : 0u;
+    if (pass > 0 && sel[2] <= (uint32_t)kDirectMax) {
+      // ---- the candidates (keys that match the prefix) into a list, in any order: one atomic
+      // per wave reserves the places of the wave's candidates
+      uint32_t *cand = hist;
+      __syncthreads();                       // everybody has read sel
+      cand[tid] = 0u;                        // (a key 0 is below every real key)
+      uint32_t m = 0;
+#pragma unroll
+      for (int i = 0; i < KPT; i++) m += key[i] != 0u && (key[i] & mask) == tau;
+      const uint32_t incl = wave_prefix_incl(m, lane);
+      const uint32_t wave_m = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+      __syncthreads();
+      if (wave_m) {                          // (uniform in the wave)
+        uint32_t base = 0;
+        if (lane == 0) base = atomicAdd(&ncand, wave_m);
+        uint32_t at = (uint32_t)__builtin_amdgcn_readlane((int)base, 0) + incl - m;
+        if (m) {
+#pragma unroll
+          for (int i = 0; i < KPT; i++)
+            if (key[i] != 0u && (key[i] & mask) == tau) cand[at++] = key[i];
+        }
+      }
+      __syncthreads();
+      // thread t ranks candidate t: tau is the candidate with fewer than `left` candidates above it
+      // and at least `left` candidates not below it (equal candidates all say the same)
+      // (waves without a candidate have nothing to do: the list is short)
+      const uint32_t nc = ncand;
+      if ((uint32_t)(tid & ~63) < nc) {
+        const uint32_t n4 = (nc + 3u) >> 2, mine = cand[tid];
+        uint32_t gt = 0, ge = 0;
+        for (uint32_t c = 0; c < n4; c++) {
+          const uint4 o = hist4[c];
+          gt += (o.x > mine) + (o.y > mine) + (o.z > mine) + (o.w > mine);
+          ge += (o.x >= mine) + (o.y >= mine) + (o.z >= mine) + (o.w >= mine);
+        }
+        if (mine != 0u && gt < left && left <= ge) {
+          sel[0] = mine;
+          sel[1] = left - gt;
+        }
+      }
+      __syncthreads();
+      tau = sel[0];
+      left = sel[1];
+      break;
+    }
     const int shift = 24 - 8 * pass;
+    __syncthreads();                         // (sel and the previous pass's histogram have been read)
+    hist4[tid] = make_uint4(0u, 0u, 0u, 0u);
+    hist4[tid + kSelThreads] = make_uint4(0u, 0u, 0u, 0u);
+    __syncthreads();
 #pragma unroll
     for (int i = 0; i < KPT; i++)
       if (key[i] != 0u && (key[i] & mask) == tau) atomicAdd(&hist[(((key[i] >> shift) & 255u) << 5) + (lane & 31)], 1u);
     __syncthreads();
     uint32_t tot = 0;
     if (tid < 256) {
-      // (copy (c + tid) % 32 in round c: the 64 lanes of a wave read 64 different banks)
+      // (four copies per read, group (c + tid) % 8 in round c: two lanes per bank group in every
+      // quarter wave, which is what a 16-byte read costs anyway)
 #pragma unroll
-      for (int c = 0; c < 32; c++) tot += hist[(tid << 5) + ((c + tid) & 31)];
+      for (int c = 0; c < 8; c++) {
+        const uint4 h4 = hist4[(tid << 3) + ((c + tid) & 7)];
+        tot += (h4.x + h4.y) + (h4.z + h4.w);
+      }
     }
     choose_digit(tot, left, tid, wave, lane, wsum, sel);
     tau |= sel[0] << shift;
     left = sel[1];
   }
-  int slot = 0;
-  uint32_t cg = 0;
-#pragma unroll
-  for (int i = 0; i < KPT; i++) cg += (uint32_t)__popcll(__ballot(key[i] > tau));
   // every score above tau is kept; of those equal to it, the first `need` in index order
-  const uint32_t need = (uint32_t)k - block_total(cg, slot);
-  // index order = (i, wave, lane); count per (i, wave), scan, then place
+  const uint32_t need = left;
+  // keys above tau and equal to it in this wave: counted on the scalar unit from the compare masks
+  {
+    uint32_t wave_gt = 0, wave_eq = 0;
 #pragma unroll
-  for (int i = 0; i < KPT; i++) {
-    const unsigned long long bgt = __ballot(key[i] > tau);
-    const unsigned long long beq = __ballot(key[i] == tau);
-    if (lane == 0) {
-      pgt[i * kSelWaves + wave] = (uint32_t)__popcll(bgt);
-      peq[i * kSelWaves + wave] = (uint32_t)__popcll(beq);
+    for (int i = 0; i < KPT; i++) {
+      wave_gt += (uint32_t)__popcll(__ballot(key[i] > tau));
+      wave_eq += (uint32_t)__popcll(__ballot(key[i] == tau));
     }
+    if (lane == 0) { wgt[wave] = wave_gt; weq[wave] = wave_eq; }
   }
   __syncthreads();
-  {
-    // block-wide exclusive scan of the KPT*16 (<= 1024) counts: thread t owns entry t
-    const bool own = tid < KPT * kSelWaves;
-    const uint32_t g = own ? pgt[tid] : 0u, e = own ? peq[tid] : 0u;
-    uint32_t ig = g, ie = e;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const uint32_t tg = __shfl_up(ig, off), te = __shfl_up(ie, off);
-      if (lane >= off) { ig += tg; ie += te; }
-    }
-    if (lane == 63) { sgt[wave] = ig; seq[wave] = ie; }
-    __syncthreads();
-    uint32_t bg = 0, be = 0;
-    for (int w = 0; w < wave; w++) { bg += sgt[w]; be += seq[w]; }
-    if (own) { pgt[tid] = bg + ig - g; peq[tid] = be + ie - e; }
-    __syncthreads();
-  }
+  const uint32_t og = lane < wave ? wgt[lane & (kSelWaves - 1)] : 0u, oe = lane < wave ? weq[lane & (kSelWaves - 1)] : 0u;
+  uint32_t run_gt = row0_total(og), run_eq = row0_total(oe);   // in the waves before this one (wave < 16 lanes of row 0)
   int32_t *kb = kept + (size_t)b * k;
-  const unsigned long long lt = (1ull << lane) - 1ull;
 #pragma unroll
-  for (int i = 0; i < KPT; i++) {
-    const int j = i * kSelThreads + tid;
-    const bool gt = key[i] > tau, eq = key[i] == tau;
-    const unsigned long long bgt = __ballot(gt), beq = __ballot(eq);
-    const uint32_t my_gt = pgt[i * kSelWaves + wave] + (uint32_t)__popcll(bgt & lt);
-    const uint32_t my_eq = peq[i * kSelWaves + wave] + (uint32_t)__popcll(beq & lt);
-    if (gt || (eq && my_eq < need)) {
-      const uint32_t pos = my_gt + min(my_eq, need);
-      kb[pos] = j;
-      if (coords_in) coords_out[(size_t)b * k + pos] = coords_in[(size_t)b * N + j];
+  for (int i = 0; i < KPT / 4; i++) {
+    uint32_t c = 0;
+#pragma unroll
+    for (int e = 0; e < 4; e++) c += (uint32_t)(key[4 * i + e] > tau) + ((uint32_t)(key[4 * i + e] == tau) << 16);
+    const uint32_t incl = wave_prefix_incl(c, lane);           // at most 256 per half
+    const uint32_t group = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+    uint32_t ngt = run_gt + ((incl - c) & 0xffffu), neq = run_eq + ((incl - c) >> 16);
+#pragma unroll
+    for (int e = 0; e < 4; e++) {
+      const bool gt = key[4 * i + e] > tau, eq = key[4 * i + e] == tau;
+      if (gt || (eq && neq < need)) {
+        const uint32_t pos = ngt + min(neq, need);
+        const int j = j0 + 256 * i + e;
+        if (pos < (uint32_t)k) {   // always
+          kb[pos] = j;
+          if (coords_in) coords_out[(size_t)b * k + pos] = coords_in[(size_t)b * N + j];
+        }
+      }
+      ngt += gt;
+      neq += eq;
     }
+    run_gt += group & 0xffffu;
+    run_eq += group >> 16;
   }
 }
 
@@ -231,7 +309,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_digit_pass_kernel(const floa
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const float *sc = scores + (size_t)b * N;
   __shared__ uint32_t hist[kSelWaves][256];
-  __shared__ uint32_t wtot[4], sel[2], wabove[kSelWaves];
+  __shared__ uint32_t wtot[4], sel[3], wabove[kSelWaves];
   SelState st = {0u, (uint32_t)k};
   if (pass > 0)     // (the first rows of hist serve as its exchange buffer)
     st = advance_state(pass - 1, b, B, k, nchunk, part, state, c == 0, -1, tid, wave, lane, wtot, sel, hist);
@@ -281,7 +359,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_place_kernel(const float *sc
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const float *sc = scores + (size_t)b * N;
   __shared__ uint32_t quarter[8][256];
-  __shared__ uint32_t wtot[4], sel[2];
+  __shared__ uint32_t wtot[4], sel[3];
   __shared__ uint32_t wgt[kSelWaves], weq[kSelWaves];
   const uint32_t above_mine = tid < c ? above[(size_t)b * nchunk + tid] : 0u;     // at most 128 chunks
   const SelState st = advance_state(3, b, B, k, nchunk, part, state, false, c, tid, wave, lane, wtot, sel, quarter);
@@ -357,17 +435,28 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const uint4 *x, const 
 static int multi_kpt(int N) { return (int)(((long long)N + 128LL * kSelThreads - 1) / (128LL * kSelThreads)); }
 static int multi_chunks(int N) { return (N + multi_kpt(N) * kSelThreads - 1) / (multi_kpt(N) * kSelThreads); }
 
+// Keys per thread of the one-workgroup selection at most.  (With 64 keys a row of 65536 scores takes one
+// compute unit 43 us; the five launches of the several-workgroup selection take 26 us plus their gaps.)
+constexpr int kRegMaxKeys = 32;
+
 size_t topk_select_workspace_bytes(int B, int N) {
-  if (N <= 16 * kSelThreads) return 0;                    // one workgroup per image, state in registers and LDS
+  if (N <= kRegMaxKeys * kSelThreads) return 0;                    // one workgroup per image, state in registers and LDS
   return (size_t)4 * B * multi_chunks(N) * 256 * sizeof(uint32_t) + (size_t)4 * B * sizeof(SelState) +
          (size_t)B * multi_chunks(N) * sizeof(uint32_t);
 }
 
 ns_status launch_topk_select(int B, int N, int k, const float *scores, const int32_t *coords_in,
                              int32_t *kept, int32_t *coords_out, void *ws, hipStream_t s) {
-  if (N <= 16 * kSelThreads) {
-    hipLaunchKernelGGL(topk_select_reg_kernel<16>, dim3(B), dim3(kSelThreads), 0, s, scores, N, k,
-                       coords_in, kept, coords_out);
+  if (N <= kRegMaxKeys * kSelThreads) {
+    const dim3 grid(B), block(kSelThreads);
+    if (N <= 4 * kSelThreads)
+      hipLaunchKernelGGL(topk_select_reg_kernel<4>, grid, block, 0, s, scores, N, k, coords_in, kept, coords_out);
+    else if (N <= 8 * kSelThreads)
+      hipLaunchKernelGGL(topk_select_reg_kernel<8>, grid, block, 0, s, scores, N, k, coords_in, kept, coords_out);
+    else if (N <= 16 * kSelThreads)
+      hipLaunchKernelGGL(topk_select_reg_kernel<16>, grid, block, 0, s, scores, N, k, coords_in, kept, coords_out);
+    else
+      hipLaunchKernelGGL(topk_select_reg_kernel<32>, grid, block, 0, s, scores, N, k, coords_in, kept, coords_out);
     return check_launch("topk_select_reg_kernel");
   }
   const int kpt = multi_kpt(N), nchunk = multi_chunks(N);

@@ -109,11 +109,12 @@ def test_topk_and_scores_validation(nb):
     assert call(1, 100, 10, x=FAKE, C=64) == nb.NS_ERR_INVALID_ARG                   # y missing
     assert call(1, 100, 10, x=FAKE, y=ctypes.c_void_p(0x20000), C=3) == nb.NS_ERR_UNSUPPORTED
     assert call(1, 100, 10, cin=FAKE) == nb.NS_ERR_INVALID_ARG                       # coords_out missing
-    # rows above 16384 scores need a workspace (several workgroups per image)
+    # rows above 32768 scores need a workspace (several workgroups per image)
     assert L.topk_filter_workspace_bytes(4, 16384, 100) == 0
-    assert L.topk_filter_workspace_bytes(1, 60025, 100) == 4 * 59 * 1024 + 4 * 8 + 59 * 4
+    assert L.topk_filter_workspace_bytes(1, 32768, 100) == 0
+    assert L.topk_filter_workspace_bytes(1, 70001, 100) == 4 * 69 * 1024 + 4 * 8 + 69 * 4
     assert L.topk_filter_workspace_bytes(2, 300000, 100) == 2 * (4 * 98 * 1024 + 4 * 8 + 98 * 4)   # 3 keys per thread
-    assert call(1, 60025, 10) == nb.NS_ERR_WORKSPACE
+    assert call(1, 70001, 10) == nb.NS_ERR_WORKSPACE
     assert b"needed" in nb.lib.ns_last_error()
     assert L.cls_scores_from_logits(1, 2, 1, 1, FAKE, FAKE, FAKE, None) == nb.NS_ERR_INVALID_ARG
     assert L.cls_scores_from_logits(1, 2, 10, 1, None, FAKE, FAKE, None) == nb.NS_ERR_INVALID_ARG

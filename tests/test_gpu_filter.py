@@ -91,11 +91,12 @@ def test_topk_ties_signs_and_clusters(nb):
     topk_case(nb, c, 9831)
 
 
-@pytest.mark.parametrize("N", [16385, 17408, 60025, 131072, 131073, 300000])
-def test_topk_long_rows_several_workgroups(nb, N):
-    """Rows above 16384 scores are selected by several workgroups per image (digit histograms
-    exchanged between launches): random, tied, clustered and signed scores, k from 1 to N, the
-    coordinates compacted along."""
+@pytest.mark.parametrize("N", [16385, 17408, 32768, 32769, 60025, 65536, 65537, 131072, 131073, 300000])
+def test_topk_long_rows(nb, N):
+    """Rows of up to 32768 scores are selected by one workgroup per image with up to 32 keys per
+    thread, longer ones by several workgroups per image (digit histograms exchanged between
+    launches): random, tied, clustered and signed scores, k from 1 to N, the coordinates compacted
+    along."""
     rng = np.random.default_rng(N)
     topk_case(nb, rng.random((2, N)).astype(np.float32), (N * 6) // 10)
     topk_case(nb, rng.integers(0, 4, size=(2, N)).astype(np.float32), N // 3)          # heavy ties across chunks

@@ -113,10 +113,10 @@ def test_stack_with_pruning_stage(nb, layers, after, keep_pct, g, block):
 
 
 def test_stack_pruning_of_a_long_sequence(nb):
-    """More than 16384 patches: the stack's selection runs with several workgroups per image and
+    """More than 32768 patches: the stack's selection runs with several workgroups per image and
     takes its scratch from the stack's workspace.  The stack must keep exactly what topk_filter
     (checked against the oracle elsewhere) keeps from the same block's scores, and continue on it."""
-    B, g, block, heads, dim, mlp = 1, 132, 8, 8, 512, 512
+    B, g, block, heads, dim, mlp = 1, 184, 8, 8, 512, 512
     N = g * g
     keep = (N * 60 + 99) // 100
     rng = np.random.default_rng(23)
