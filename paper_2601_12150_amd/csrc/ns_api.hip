@@ -297,7 +297,7 @@ ns_status ns::attn_forward_impl(const ns_attn_desc *desc, const void *q, const v
   ns_status st = prepare_attn(desc, q, k, v, out, workspace, workspace_bytes, stream, a, partials, reuse_lists);
   if (st != NS_OK) return st;
   const ns_attn_desc &d = a.d;
-  if (a.kernel == PK_SWEEP) {
+  if (a.kernel == PK_SWEEP && d.n_global == 1) {
     // this kernel computes the global query's partials and logits on the way
     st = launch_attn_sweep(a, cls_logits, partials);
     if (st != NS_OK) return st;

@@ -25,6 +25,7 @@ struct BlockParams {
   int bm;               // squares per block side: block / 16
   int heads;
   int blocks;           // batch * heads * nbh * nbw
+  int n_global;         // G leading global tokens, 1 .. 8 (their K and V rows sit in LDS)
 };
 
 typedef s16x4 __attribute__((address_space(3))) *lds_s16x4_ptr;
@@ -68,7 +69,7 @@ __global__ __launch_bounds__(256, 2) void attn_block16_kernel(BlockParams p) {
   const uint32_t gridrowB = (uint32_t)p.grid_w * rowB;
   // tile `sub` of block (Rb, Cb) is grid rows 16*Rb + 4*sub .. +3, columns 16*Cb .. +15; its row i
   // is the token at grid row offset i/16, column offset i%16
-  auto tile_token = [&](int Rb, int Cb, int sub) { return 1 + (Rb * 16 + sub * 4) * p.grid_w + Cb * 16; };
+  auto tile_token = [&](int Rb, int Cb, int sub) { return p.n_global + (Rb * 16 + sub * 4) * p.grid_w + Cb * 16; };
   // Short edge blocks: a tile is filled up with copies of existing tokens (row and column index
   // within the block are clamped).  A copied QUERY computes what its original computes and is
   // stored to the same place (same bits); a copied KEY gets the logit kMasked, i.e. the weight 0.
@@ -199,7 +200,9 @@ __global__ __launch_bounds__(256, 2) void attn_block16_kernel(BlockParams p) {
   };
   // The state the global token gives a query tile: m = its logit (the fixed exponent reference),
   // l = 1, O = v_0; k_0 and v_0 sit in LDS.  The k_0 fragment is that of a key tile whose rows
-  // are all k_0, so every register of its product with Q is q . k_0.
+  // are all k_0, so every register of its product with Q is q . k_0.  Further global tokens
+  // (rows 1 .. G-1 of the same LDS areas) are added one by one with a running maximum, so the
+  // reference becomes the largest of the global tokens' logits.
   auto init_tile = [&]() {
     bf16x8 k0[4];
 #pragma unroll
@@ -224,6 +227,36 @@ __global__ __launch_bounds__(256, 2) void attn_block16_kernel(BlockParams p) {
           o[dt][1][4 * ig + e] = (float)v4[e];
         }
       }
+    for (int g = 1; g < p.n_global; g++) {
+      bf16x8 kg[4];
+#pragma unroll
+      for (int s = 0; s < 4; s++) kg[s] = *(lds_bf16x8_ptr)(smem + kK0Row + 128 * g + 64 * hh + 16 * s);
+      float pg[2];
+#pragma unroll
+      for (int nt = 0; nt < 2; nt++) {
+        const f32x16 s = stage_a(kg, nt);
+        const float sg = s[0] * p.c, m_new = fmaxf(m[nt], sg);
+        const float alpha = __builtin_amdgcn_exp2f(m[nt] - m_new);
+        pg[nt] = __builtin_amdgcn_exp2f(sg - m_new);
+        m[nt] = m_new;
+        nm[nt] = -m_new;
+        l[nt] = __builtin_fmaf(l[nt], alpha, hh == 0 ? pg[nt] : 0.f);
+#pragma unroll
+        for (int e = 0; e < 16; e++) { o[0][nt][e] *= alpha; o[1][nt][e] *= alpha; }
+      }
+#pragma unroll
+      for (int dt = 0; dt < 2; dt++)
+#pragma unroll
+        for (int ig = 0; ig < 4; ig++) {
+          const u32x2 v2 = *(u32x2 __attribute__((address_space(3))) *)(smem + kV0Row + 128 * g + 64 * dt + 16 * ig + 8 * hh);
+          const bf16x4 v4 = __builtin_bit_cast(bf16x4, v2);
+#pragma unroll
+          for (int e = 0; e < 4; e++) {
+            o[dt][0][4 * ig + e] = __builtin_fmaf(pg[0], (float)v4[e], o[dt][0][4 * ig + e]);
+            o[dt][1][4 * ig + e] = __builtin_fmaf(pg[1], (float)v4[e], o[dt][1][4 * ig + e]);
+          }
+        }
+    }
   };
   // normalise and store; returns whether a weight overflowed the fixed reference (then some sum or
   // output is not finite).  Lane (query, hh) owns channels 32*dt + 8*ig + 4*hh + 0..3.
@@ -256,9 +289,11 @@ __global__ __launch_bounds__(256, 2) void attn_block16_kernel(BlockParams p) {
   };
 
   // ---- prologue: the first three key tiles are requested, the first has landed
-  if (wave == 0) {                   // the global token's rows, 8 lanes x 16 bytes each (the other lanes repeat them)
-    dma16(kb, 16u * (lane & 7), lds_base + kK0Row);
-    dma16(vb, 16u * (lane & 7), lds_base + kV0Row);
+  if (wave == 0) {
+    // the global tokens' rows, 8 lanes x 16 bytes each: LDS row r = token min(r, G-1)
+    const uint32_t goff = (uint32_t)min(lane >> 3, p.n_global - 1) * rowB + 16u * (lane & 7);
+    dma16(kb, goff, lds_base + kK0Row);
+    dma16(vb, goff, lds_base + kV0Row);
   }
   issue_next();
   issue_next();
@@ -385,8 +420,8 @@ __global__ __launch_bounds__(256, 2) void attn_block16_kernel(BlockParams p) {
 }  // namespace
 
 bool block16_attn_supported(const ns_attn_desc &d) {
-  return d.dtype == NS_BF16 && d.head_dim == 64 && d.radius == 1 && d.n_global == 1 && d.coords == nullptr &&
-         d.block >= 16 && d.block % 16 == 0 && d.scale > 0.f &&
+  return d.dtype == NS_BF16 && d.head_dim == 64 && d.radius == 1 && d.n_global >= 1 && d.n_global <= 8 &&
+         d.coords == nullptr && d.block >= 16 && d.block % 16 == 0 && d.scale > 0.f &&
          // tokens are addressed with 32-bit byte offsets from the (batch, head) base
          (long long)d.tokens * d.q_stride_t * 2 < 0x7fffffffLL &&
          (long long)d.tokens * d.out_stride_t * 2 < 0x7fffffffLL;
@@ -408,6 +443,7 @@ ns_status launch_attn_block16(const AttnArgs &a) {
   p.nbw = (d.grid_w + 15) / 16;
   p.bm = d.block / 16;
   p.heads = d.heads;
+  p.n_global = d.n_global;
   const long long blocks = (long long)d.batch * d.heads * p.nbh * p.nbw;
   if (blocks > 0x7fffffffLL) return fail(NS_ERR_UNSUPPORTED, "launch grid too large");
   p.blocks = (int)blocks;

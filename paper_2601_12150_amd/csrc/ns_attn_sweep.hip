@@ -47,6 +47,7 @@ struct SweepParams {
   int strips;           // batch * heads * nbh
   int num_cus;
   int tokens;
+  int n_global;         // G leading global tokens, 1 .. 8 (their K and V rows sit in LDS for the whole strip)
   float scale;
   float *cls_logits;    // [B,H,T] raw logits of the global query, or NULL
   float *cls_partials;  // [B,H,4*nbh,66] softmax partials of the global query, or NULL: no global row
@@ -97,7 +98,7 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
   const uint32_t rowB = (uint32_t)p.qst * 2u;
   const uint32_t gridrowB = (uint32_t)p.grid_w * rowB;
   // token (grid row 8*Rb + i/8, grid column 8*Cb + i%8) is row i of the tile of block (Rb, Cb)
-  auto block_token = [&](int Rb, int Cb) { return 1 + Rb * 8 * p.grid_w + Cb * 8; };
+  auto block_token = [&](int Rb, int Cb) { return p.n_global + Rb * 8 * p.grid_w + Cb * 8; };
   auto block_base = [&](int Rb, int Cb) { return (uint32_t)block_token(Rb, Cb) * rowB; };
   // Blocks at the right and bottom edge of a grid that 8 does not divide are short.  Their tiles
   // are filled up with copies of existing rows (the row and column index within the block are
@@ -240,6 +241,8 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
   // The state the global token gives a query block: m = its logit (the fixed exponent reference),
   // l = 1, O = v_0.  k_0 and v_0 sit in LDS for the whole strip.  The k_0 fragment is that of a
   // key tile whose rows are all k_0, so every register of its product with Q is q . k_0.
+  // Further global tokens (rows 1 .. G-1 of the same LDS areas) are added one by one with a
+  // running maximum, so the reference becomes the largest of the global tokens' logits.
   auto init_block = [&]() {
     bf16x8 k0[4];
 #pragma unroll
@@ -264,6 +267,36 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
           o[dt][1][4 * ig + e] = (float)v4[e];
         }
       }
+    for (int g = 1; g < p.n_global; g++) {
+      bf16x8 kg[4];
+#pragma unroll
+      for (int s = 0; s < 4; s++) kg[s] = *(lds_bf16x8_ptr)(smem + kK0Row + 128 * g + 64 * hh + 16 * s);
+      float pg[2];
+#pragma unroll
+      for (int nt = 0; nt < 2; nt++) {
+        const f32x16 s = stage_a(kg, nt);
+        const float sg = s[0] * p.c, m_new = fmaxf(m[nt], sg);
+        const float alpha = __builtin_amdgcn_exp2f(m[nt] - m_new);
+        pg[nt] = __builtin_amdgcn_exp2f(sg - m_new);
+        m[nt] = m_new;
+        nm[nt] = -m_new;
+        l[nt] = __builtin_fmaf(l[nt], alpha, hh == 0 ? pg[nt] : 0.f);
+#pragma unroll
+        for (int e = 0; e < 16; e++) { o[0][nt][e] *= alpha; o[1][nt][e] *= alpha; }
+      }
+#pragma unroll
+      for (int dt = 0; dt < 2; dt++)
+#pragma unroll
+        for (int ig = 0; ig < 4; ig++) {
+          const u32x2 v2 = *(u32x2 __attribute__((address_space(3))) *)(smem + kV0Row + 128 * g + 64 * dt + 16 * ig + 8 * hh);
+          const bf16x4 v4 = __builtin_bit_cast(bf16x4, v2);
+#pragma unroll
+          for (int e = 0; e < 4; e++) {
+            o[dt][0][4 * ig + e] = __builtin_fmaf(pg[0], (float)v4[e], o[dt][0][4 * ig + e]);
+            o[dt][1][4 * ig + e] = __builtin_fmaf(pg[1], (float)v4[e], o[dt][1][4 * ig + e]);
+          }
+        }
+    }
   };
   uint32_t badmask = 0;              // bit j: this wave's j-th query block has to be redone
   // Normalised rows of the finished block, packed: lane (query, hh) owns channels
@@ -440,9 +473,11 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
 
   // ---- prologue: the first three key tiles are requested, the first has landed
   int qc = wave;                     // this wave's query block in progress
-  if (wave == 0) {                   // the global token's rows, 8 lanes x 16 bytes each (the other lanes repeat them)
-    dma16(kb, 16u * (lane & 7), lds_base + kK0Row);
-    dma16(vb, 16u * (lane & 7), lds_base + kV0Row);
+  if (wave == 0) {
+    // the global tokens' rows, 8 lanes x 16 bytes each: LDS row r = token min(r, G-1)
+    const uint32_t goff = (uint32_t)min(lane >> 3, p.n_global - 1) * rowB + 16u * (lane & 7);
+    dma16(kb, goff, lds_base + kK0Row);
+    dma16(vb, goff, lds_base + kV0Row);
     dma16(qb, 16u * (lane & 7), lds_base + kQ0Row);
   }
   cls_state[lane] = 0.f;             // this wave's partial of the global query: nothing seen yet
@@ -640,7 +675,8 @@ __global__ __launch_bounds__(256, 2) void attn_sweep_kernel(SweepParams p) {
 }  // namespace
 
 bool sweep_attn_supported(const ns_attn_desc &d) {
-  return d.dtype == NS_BF16 && d.head_dim == 64 && d.radius == 1 && d.n_global == 1 && d.coords == nullptr &&
+  return d.dtype == NS_BF16 && d.head_dim == 64 && d.radius == 1 && d.n_global >= 1 && d.n_global <= 8 &&
+         d.coords == nullptr &&
          (d.block == 8 || d.block == 4 || d.block == 2) && (d.grid_w + 7) / 8 <= 128 && d.scale > 0.f &&
          // tokens are addressed with 32-bit byte offsets from the (batch, head) base
          (long long)d.tokens * d.q_stride_t * 2 < 0x7fffffffLL &&
@@ -663,9 +699,11 @@ ns_status launch_attn_sweep(const AttnArgs &a, float *cls_logits, float *cls_par
   p.nbw = (d.grid_w + 7) / 8;
   p.heads = d.heads;
   p.tokens = d.tokens;
+  p.n_global = d.n_global;
   p.scale = d.scale;
-  p.cls_logits = cls_logits;
-  p.cls_partials = cls_partials;
+  // the global query's row on the way: with one global token only (several take the row kernel)
+  p.cls_logits = d.n_global == 1 ? cls_logits : nullptr;
+  p.cls_partials = d.n_global == 1 ? cls_partials : nullptr;
   const long long strips = (long long)d.batch * d.heads * p.nbh;
   if (strips > 0x7fffffffLL) return fail(NS_ERR_UNSUPPORTED, "launch grid too large");
   // a wave records the query blocks it has to redo in a 32-bit mask

@@ -107,6 +107,8 @@ def test_pruned_and_multi_global_attention_writes_stay_inside(nb, monkeypatch):
     attention_case(nb, monkeypatch, "generic", 1, 2, 12, 12, 4, "f32", keep=77)
     attention_case(nb, monkeypatch, "", 1, 2, 16, 16, 8, "bf16", n_global=3)
     attention_case(nb, monkeypatch, "", 1, 2, 24, 24, 8, "bf16", keep=300, n_global=5)
+    attention_case(nb, monkeypatch, "sweep", 1, 2, 20, 27, 8, "bf16", n_global=8)
+    attention_case(nb, monkeypatch, "block", 1, 2, 37, 21, 16, "bf16", n_global=4)
 
 
 @pytest.mark.parametrize("B,N,k,C", [(2, 1000, 377, 256), (3, 4096, 2458, 1024), (2, 16384, 9831, 64), (1, 20000, 7, 128),

@@ -50,6 +50,53 @@ def test_attention_with_several_global_tokens(nb, G, gh, gw, block, dtype, kerne
     assert torch.equal(s1, s2)
 
 
+@pytest.mark.parametrize("force,G,gh,gw,block,gain", [
+    ("sweep", 2, 24, 24, 8, 1.0), ("sweep", 8, 16, 40, 8, 1.0), ("sweep", 3, 20, 27, 8, 1.0), ("sweep", 5, 24, 16, 4, 1.0),
+    ("sweep", 4, 19, 18, 2, 1.0), ("sweep", 3, 24, 24, 8, 14.0), ("sweep", 7, 8, 8, 8, 1.0),
+    ("block", 2, 32, 32, 16, 1.0), ("block", 8, 48, 32, 16, 1.0), ("block", 3, 37, 21, 16, 1.0), ("block", 5, 70, 53, 32, 1.0),
+    ("block", 4, 32, 48, 16, 14.0), ("block", 6, 5, 5, 64, 1.0)])
+def test_tiled_kernels_with_several_global_tokens(nb, monkeypatch, force, G, gh, gw, block, gain):
+    """Up to eight global tokens on the sweep and the block kernel (their K and V rows stay in LDS
+    next to the first one's): grids the tiles divide and do not divide, windows 2-32, a block
+    larger than the grid, and logits large enough (gain 14) to send query tiles through the
+    running-maximum path.  The global rows come from the row kernel."""
+    monkeypatch.setenv("NSATTN_KERNEL", force)
+    B, H = 2, 3
+    q, k, v = synth.small_case(500 + G, B, H, 64, gh, gw, "bf16", n_global=G)
+    if gain != 1.0:
+        q = synth.round_to_bf16(q * np.float32(gain))
+    ref = oracle.ns_attn(q, k, v, gh, gw, block, 0.125, n_global=G)
+    dq, dk, dv = (to_dev(a, "bf16") for a in (q, k, v))
+    name = nb.ns_attn_patch_kernel_name(dq, gh, gw, block, n_global=G)
+    assert name == ("attn_sweep_kernel" if force == "sweep" else "attn_block16_kernel")
+    out, logits, lse, scores = nb.ns_attn_forward_scores(dq, dk, dv, gh, gw, block, 0.125, n_global=G)
+    torch.cuda.synchronize()
+    assert_attn_close(to_np(out), ref, "bf16", "%s G = %d" % (force, G))
+    ref_scores = oracle.cls_scores(q, k, 0.125, n_global=G)
+    np.testing.assert_allclose(to_np(scores), ref_scores, rtol=5e-5, atol=1e-10)
+    out2 = nb.ns_attn_forward(dq, dk, dv, gh, gw, block, 0.125, n_global=G)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+
+
+def test_sweep_is_chosen_for_a_few_global_tokens_at_size(nb, monkeypatch):
+    """A backbone with register tokens on a grid large enough to fill the chip: the tiled kernel is
+    the default, nine or more global tokens go to the list kernel."""
+    monkeypatch.delenv("NSATTN_KERNEL", raising=False)
+    B, H, g, G = 2, 16, 64, 5
+    q, k, v = synth.small_case(600, B, H, 64, g, g, "bf16", n_global=G)
+    dq, dk, dv = (to_dev(a, "bf16") for a in (q, k, v))
+    assert nb.ns_attn_patch_kernel_name(dq, g, g, 8, n_global=G) == "attn_sweep_kernel"
+    assert nb.ns_attn_patch_kernel_name(dq, g, g, 16, n_global=G) == "attn_block16_kernel"
+    for block in (8, 16):
+        ref = oracle.ns_attn(q, k, v, g, g, block, 0.125, n_global=G)
+        out = nb.ns_attn_forward(dq, dk, dv, g, g, block, 0.125, n_global=G)
+        torch.cuda.synchronize()
+        assert_attn_close(to_np(out), ref, "bf16", "G = 5 on the 64 x 64 grid, block %d" % block)
+    q9, k9, v9 = synth.small_case(601, 1, H, 64, g, g, "bf16", n_global=9)
+    assert nb.ns_attn_patch_kernel_name(to_dev(q9, "bf16"), g, g, 8, n_global=9) == "attn_mfma_ragged_kernel"
+
+
 def test_pruned_sequence_with_several_global_tokens(nb):
     G, g, block = 3, 30, 8
     rng = np.random.default_rng(9)
