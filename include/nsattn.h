@@ -267,6 +267,26 @@ ns_status vit_forward_features(const ns_vit_desc *desc, const ns_vit_block_weigh
                                void *const *tap_out, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The stack with several pruning stages instead of one: stage i follows block stage_after[i] and keeps
+ * stage_keep[i] of the patches still present, ranked by that block's importance scores (the scores of a
+ * pruned sequence are those of its own tokens: softmax over the tokens present).  The paper describes a
+ * single stage ("Time-Efficiency Optimization"); this entry point applies its selection rule repeatedly.
+ * desc->prune_after and desc->keep_k are ignored.
+ *   stage_after  HOST array [n_stages], 1-based block numbers, strictly ascending
+ *   stage_keep   HOST array [n_stages], positive, stage_keep[0] <= patches, never growing
+ *   x_out  out   [B, G + stage_keep[n_stages-1], dim] bf16 (n_stages == 0: [B, T, dim])
+ *   kept_idx out, nullable [B, stage_keep[n_stages-1]] int32: ORIGINAL patch indices of the final
+ *                survivors, ascending
+ *   workspace    vit_stages_workspace_bytes(...) bytes, 256-byte aligned
+ * NS_ERR_INVALID_ARG for stage lists that break the rules above.
+ */
+size_t vit_stages_workspace_bytes(const ns_vit_desc *desc, int32_t n_stages, const int32_t *stage_after,
+                                  const int32_t *stage_keep);
+ns_status vit_forward_stages(const ns_vit_desc *desc, int32_t n_stages, const int32_t *stage_after,
+                             const int32_t *stage_keep, const ns_vit_block_weights *weights, const void *x_in,
+                             void *x_out, int32_t *kept_idx, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Tokenisation of the ViT backbone the blocks belong to (paper, "Settings": a ViT foundation model
  * is the backbone; its input is the resized image): non-overlapping patch x patch pixel squares, one
  * linear map per patch, a learned CLS token in front, learned position embeddings added.

@@ -23,6 +23,7 @@ EXPORTS = ["ns_attn_workspace_bytes", "ns_attn_forward", "cls_scores_workspace_b
            "cls_scores_static_max_bytes", "cls_scores_static",
            "cls_scores_from_logits", "ns_attn_forward_scores", "topk_filter_workspace_bytes", "topk_filter", "topk_filter_global", "vit_forward_features",
            "vit_embed_workspace_bytes", "vit_embed", "vit_block_workspace_bytes", "vit_block_forward", "linear_forward", "vit_workspace_bytes", "vit_forward",
+           "vit_stages_workspace_bytes", "vit_forward_stages",
            "ns_attn_patch_kernel_time", "ns_attn_patch_kernel_name", "ns_last_error",
            "ns_version"]
 
@@ -112,6 +113,12 @@ def _load() -> ctypes.CDLL:
     lib.vit_forward.argtypes = [ctypes.POINTER(ns_vit_desc), ctypes.POINTER(ns_vit_block_weights), vp, vp, vp, vp,
                                 sz, vp]
     lib.vit_forward_features.restype = ctypes.c_int
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    lib.vit_stages_workspace_bytes.restype = ctypes.c_size_t
+    lib.vit_stages_workspace_bytes.argtypes = [ctypes.POINTER(ns_vit_desc), ctypes.c_int32, i32p, i32p]
+    lib.vit_forward_stages.restype = ctypes.c_int
+    lib.vit_forward_stages.argtypes = [ctypes.POINTER(ns_vit_desc), ctypes.c_int32, i32p, i32p,
+                                       ctypes.POINTER(ns_vit_block_weights), vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.vit_forward_features.argtypes = [ctypes.POINTER(ns_vit_desc), ctypes.POINTER(ns_vit_block_weights), vp, vp,
                                          vp, i32, ctypes.POINTER(i32), ctypes.POINTER(vp), vp, sz, vp]
     lib.ns_last_error.restype = ctypes.c_char_p
@@ -463,3 +470,45 @@ def vit_forward(x, layer_weights, grid_h, grid_w, block, heads, prune_after=0, k
     _check(lib.vit_forward_features(ctypes.byref(d), warr, _ptr(x), _ptr(out), _ptr(kept), len(taps), tl, tp,
                                     _ptr(ws), ws.numel(), _stream(stream)))
     return out, kept, taps
+
+
+def vit_forward_stages(x, layer_weights, grid_h, grid_w, block, heads, stage_after, stage_keep, ln_eps=1e-6,
+                       scale=None, out=None, workspace=None, stream=None, n_global=1):
+    """The stack with several pruning stages: after block stage_after[i] (1-based, ascending) the
+    stage_keep[i] best-scoring of the patches still present are kept.
+
+    Returns (x_out [B, n_global + stage_keep[-1], dim], kept_idx [B, stage_keep[-1]] original patch
+    indices, ascending); without stages (x_out [B,T,dim], None)."""
+    if x.dtype != torch.bfloat16 or not x.is_contiguous():
+        raise ValueError("x must be a contiguous bfloat16 tensor [B,T,dim]")
+    B, T, dim = x.shape
+    d = ns_vit_desc()
+    a = d.block.attn
+    a.batch, a.heads, a.head_dim = B, heads, dim // heads
+    a.grid_h, a.grid_w, a.block, a.radius, a.n_global = grid_h, grid_w, block, 1, int(n_global)
+    a.dtype, a.tokens = NS_BF16, T
+    a.scale = float(dim // heads) ** -0.5 if scale is None else float(scale)
+    d.block.dim, d.block.mlp_dim, d.block.ln_eps = dim, layer_weights[0]["w_fc1"].shape[0], float(ln_eps)
+    d.layers = len(layer_weights)
+    warr = (ns_vit_block_weights * len(layer_weights))()
+    for i, lw in enumerate(layer_weights):
+        for n in WEIGHT_NAMES:
+            t = lw[n]
+            want = torch.bfloat16 if n.startswith("w_") else torch.float32
+            if t.dtype != want or not t.is_contiguous() or t.device != x.device:
+                raise ValueError("layer %d weight %s must be a contiguous %s tensor on %s" % (i, n, want, x.device))
+            setattr(warr[i], n, t.data_ptr())
+    ns = len(stage_after)
+    if len(stage_keep) != ns:
+        raise ValueError("stage_after and stage_keep must have the same length")
+    aft = (ctypes.c_int32 * max(ns, 1))(*[int(v) for v in stage_after])
+    kp = (ctypes.c_int32 * max(ns, 1))(*[int(v) for v in stage_keep])
+    k_last = int(stage_keep[-1]) if ns else 0
+    if out is None:
+        out = torch.empty((B, int(n_global) + k_last if ns else T, dim), dtype=x.dtype, device=x.device)
+    kept = torch.empty((B, k_last), dtype=torch.int32, device=x.device) if ns else None
+    nbytes = lib.vit_stages_workspace_bytes(ctypes.byref(d), ns, aft, kp)
+    ws = _workspace(max(nbytes, 1), x.device, workspace)
+    _check(lib.vit_forward_stages(ctypes.byref(d), ns, aft, kp, warr, _ptr(x), _ptr(out), _ptr(kept), _ptr(ws),
+                                  ws.numel(), _stream(stream)))
+    return out, kept

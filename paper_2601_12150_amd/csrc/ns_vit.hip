@@ -251,6 +251,14 @@ ns_status block_attn_desc(const ns_vit_block_desc *d, ns_attn_desc &ad) {
   return NS_OK;
 }
 
+// idx[i] = r * grid_w + c of the packed position (r << 16 | c): the original patch index of a survivor
+__global__ __launch_bounds__(256) void coords_to_index_kernel(const int32_t *coords, int32_t *idx, size_t n, int grid_w) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  const uint32_t pc = (uint32_t)coords[i];
+  idx[i] = (int32_t)((pc >> 16) * (uint32_t)grid_w + (pc & 0xffffu));
+}
+
 // y[b][j][:] = x[b][G + j][:]: the patch rows of a sequence without its global rows, 16 bytes per
 // lane.  grid (ceil(N * vec_per_row / 256), B).
 __global__ __launch_bounds__(256) void patch_rows_kernel(const uint4 *x, uint4 *y, int N, int G, int vec_per_row) {
@@ -346,6 +354,24 @@ ns_status check_stack(const ns_vit_desc *d, bool &prune) {
   if (prune && d->keep_k > d->block.attn.tokens - d->block.attn.n_global)
     return fail(NS_ERR_INVALID_ARG, "keep_k exceeds the number of patches");
   if (d->keep_k < 0) return fail(NS_ERR_INVALID_ARG, "keep_k must not be negative");
+  return NS_OK;
+}
+
+// Stage lists: block numbers strictly ascending in 1..layers, keep counts positive, at most the
+// number of patches and never growing.
+ns_status check_stages(const ns_vit_desc *d, int n_stages, const int32_t *after, const int32_t *keep) {
+  if (!d) return fail(NS_ERR_INVALID_ARG, "descriptor is NULL");
+  if (d->layers < 1) return fail(NS_ERR_INVALID_ARG, "layers must be positive");
+  if (d->block.attn.coords) return fail(NS_ERR_INVALID_ARG, "the stack starts from the full grid: attn.coords must be NULL");
+  if (n_stages < 0 || n_stages > d->layers) return fail(NS_ERR_INVALID_ARG, "n_stages out of range");
+  if (n_stages > 0 && (!after || !keep)) return fail(NS_ERR_INVALID_ARG, "stage arrays are NULL");
+  const int N = d->block.attn.tokens - d->block.attn.n_global;
+  for (int i = 0; i < n_stages; i++) {
+    if (after[i] < 1 || after[i] > d->layers || (i > 0 && after[i] <= after[i - 1]))
+      return fail(NS_ERR_INVALID_ARG, "stage_after must be strictly ascending in 1..layers");
+    if (keep[i] < 1 || keep[i] > (i > 0 ? keep[i - 1] : N))
+      return fail(NS_ERR_INVALID_ARG, "stage_keep must be positive, at most the number of patches, and not grow");
+  }
   return NS_OK;
 }
 
@@ -536,31 +562,34 @@ ns_status vit_forward(const ns_vit_desc *desc, const ns_vit_block_weights *weigh
                               workspace_bytes, stream);
 }
 
-ns_status vit_forward_features(const ns_vit_desc *desc, const ns_vit_block_weights *weights, const void *x_in,
-                               void *x_out, int32_t *kept_idx, int32_t n_taps, const int32_t *tap_layers,
-                               void *const *tap_out, void *workspace, size_t workspace_bytes, void *stream) {
-  bool prune;
-  ns_status st = check_stack(desc, prune);
-  if (st != NS_OK) return st;
+// The stack with a list of pruning stages (HOST arrays, validated by the caller): shared by the
+// entry points below.  `d` carries the first stage in prune_after / keep_k (or none), which is what
+// the workspace is sized for.
+static ns_status stack_run(const ns_vit_desc &d, int n_stages, const int32_t *after, const int32_t *keep,
+                           const ns_vit_block_weights *weights, const void *x_in, void *x_out, int32_t *kept_idx,
+                           int32_t n_taps, const int32_t *tap_layers, void *const *tap_out, void *workspace,
+                           size_t workspace_bytes, void *stream) {
+  const bool prune = n_stages > 0;
+  ns_status st;
   if (n_taps < 0 || (n_taps > 0 && (!tap_layers || !tap_out)))
     return fail(NS_ERR_INVALID_ARG, "n_taps must be >= 0 and the tap arrays given with it");
   for (int i = 0; i < n_taps; i++) {
-    if (tap_layers[i] < 1 || tap_layers[i] > desc->layers || (i > 0 && tap_layers[i] <= tap_layers[i - 1]))
+    if (tap_layers[i] < 1 || tap_layers[i] > d.layers || (i > 0 && tap_layers[i] <= tap_layers[i - 1]))
       return fail(NS_ERR_INVALID_ARG, "tap_layers must be ascending in 1..layers");
-    if (prune && tap_layers[i] > desc->prune_after)
+    if (prune && tap_layers[i] > after[0])
       return fail(NS_ERR_INVALID_ARG, "a feature map after the pruning stage has no grid structure left");
     if (!tap_out[i] || reinterpret_cast<uintptr_t>(tap_out[i]) % 16)
       return fail(NS_ERR_INVALID_ARG, "tap_out[%d] is NULL or misaligned", i);
   }
-  const size_t bw = stack_block_workspace_bytes(*desc, prune);
+  const size_t bw = stack_block_workspace_bytes(d, prune);
   if (bw == 0) {                      // the block's own validation says why: pass its status on
     ns_attn_desc ad;
-    st = block_attn_desc(&desc->block, ad);
+    st = block_attn_desc(&d.block, ad);
     if (st == NS_OK) st = attn_validate(&ad);
     return st != NS_OK ? st : fail(NS_ERR_INVALID_ARG, "invalid block descriptor");
   }
   if (!weights || !x_in || !x_out) return fail(NS_ERR_INVALID_ARG, "weights, x_in and x_out must not be NULL");
-  const StackWorkspace L = stack_layout(*desc, bw);
+  const StackWorkspace L = stack_layout(d, bw);
   if (!workspace) return fail(NS_ERR_WORKSPACE, "workspace is NULL, %zu bytes needed", L.total);
   if (reinterpret_cast<uintptr_t>(workspace) % 256) return fail(NS_ERR_WORKSPACE, "workspace must be 256-byte aligned");
   if (workspace_bytes < L.total) return fail(NS_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, L.total);
@@ -568,19 +597,22 @@ ns_status vit_forward_features(const ns_vit_desc *desc, const ns_vit_block_weigh
   unsigned char *ws = static_cast<unsigned char *>(workspace);
   void *buf[2] = {ws + L.xa, ws + L.xb};
   float *scores = reinterpret_cast<float *>(ws + L.scores);
-  int32_t *kept = kept_idx ? kept_idx : reinterpret_cast<int32_t *>(ws + L.kept);
-  int32_t *cin = reinterpret_cast<int32_t *>(ws + L.coords_in), *cout = reinterpret_cast<int32_t *>(ws + L.coords_out);
+  int32_t *kept_ws = reinterpret_cast<int32_t *>(ws + L.kept);
+  // the survivors' grid positions: read from one list, written to the other, stage by stage
+  int32_t *cbuf[2] = {reinterpret_cast<int32_t *>(ws + L.coords_in), reinterpret_cast<int32_t *>(ws + L.coords_out)};
+  int cflip = 0;
 
-  ns_vit_block_desc bd = desc->block;
-  const ns_attn_desc full = desc->block.attn;
+  ns_vit_block_desc bd = d.block;
+  const ns_attn_desc full = d.block.attn;
   const int N = full.tokens - full.n_global;
+  int n_cur = N;              // patches in the sequence
   const void *cur = x_in;
   int flip = 0;
   bool lists_built = false;   // block lists stay valid from block to block until the sequence changes
-  int tap = 0;
-  for (int l = 0; l < desc->layers; l++) {
-    const bool last = l + 1 == desc->layers, scoring = prune && l + 1 == desc->prune_after;
-    // the last block writes x_out directly unless the pruning stage still follows it
+  int tap = 0, stage = 0;
+  for (int l = 0; l < d.layers; l++) {
+    const bool last = l + 1 == d.layers, scoring = stage < n_stages && l + 1 == after[stage];
+    // the last block writes x_out directly unless a pruning stage still follows it
     void *dst = (last && !scoring) ? x_out : buf[flip];
     st = block_forward_impl(&bd, &weights[l], cur, dst, scoring ? scores : nullptr, ws + L.block_ws, bw, s,
                             lists_built);
@@ -598,22 +630,71 @@ ns_status vit_forward_features(const ns_vit_desc *desc, const ns_vit_block_weigh
       tap++;
     }
     if (scoring) {
-      dim3 grid((N + 255) / 256, full.batch);
-      hipLaunchKernelGGL(raster_coords_kernel, grid, dim3(256), 0, s, cin, N, full.grid_w);
-      st = check_launch("raster_coords_kernel");
-      if (st != NS_OK) return st;
+      int32_t *cin = cbuf[cflip], *cout = cbuf[cflip ^ 1];
+      if (stage == 0) {
+        dim3 grid((N + 255) / 256, full.batch);
+        hipLaunchKernelGGL(raster_coords_kernel, grid, dim3(256), 0, s, cin, N, full.grid_w);
+        st = check_launch("raster_coords_kernel");
+        if (st != NS_OK) return st;
+      }
+      const int k = keep[stage];
+      // the first stage's indices are the original patch indices: with one stage they go straight to the caller
+      int32_t *kept = (n_stages == 1 && kept_idx) ? kept_idx : kept_ws;
       void *y = last ? x_out : buf[flip];
-      st = topk_filter_global(full.batch, N, desc->keep_k, full.n_global, scores, cur, bd.dim, NS_BF16, cin, kept,
+      st = topk_filter_global(full.batch, n_cur, k, full.n_global, scores, cur, bd.dim, NS_BF16, cin, kept,
                               y, cout, ws + L.block_ws, bw, s);   // the block's workspace is idle here
       if (st != NS_OK) return st;
       cur = y;
       flip ^= 1;
-      bd.attn.tokens = full.n_global + desc->keep_k;
+      cflip ^= 1;
+      n_cur = k;
+      bd.attn.tokens = full.n_global + k;
       bd.attn.coords = cout;
       lists_built = false;
+      stage++;
+      if (stage == n_stages && n_stages > 1 && kept_idx) {
+        // later stages select among survivors: the original indices come from the positions
+        const size_t n = (size_t)full.batch * k;
+        hipLaunchKernelGGL(coords_to_index_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, cout, kept_idx, n,
+                           full.grid_w);
+        st = check_launch("coords_to_index_kernel");
+        if (st != NS_OK) return st;
+      }
     }
   }
   return NS_OK;
+}
+
+ns_status vit_forward_features(const ns_vit_desc *desc, const ns_vit_block_weights *weights, const void *x_in,
+                               void *x_out, int32_t *kept_idx, int32_t n_taps, const int32_t *tap_layers,
+                               void *const *tap_out, void *workspace, size_t workspace_bytes, void *stream) {
+  bool prune;
+  ns_status st = check_stack(desc, prune);
+  if (st != NS_OK) return st;
+  const int32_t after = desc->prune_after, keep = desc->keep_k;
+  return stack_run(*desc, prune ? 1 : 0, &after, &keep, weights, x_in, x_out, kept_idx, n_taps, tap_layers, tap_out,
+                   workspace, workspace_bytes, stream);
+}
+
+size_t vit_stages_workspace_bytes(const ns_vit_desc *desc, int32_t n_stages, const int32_t *stage_after,
+                                  const int32_t *stage_keep) {
+  if (check_stages(desc, n_stages, stage_after, stage_keep) != NS_OK) return 0;
+  ns_vit_desc d = *desc;
+  d.prune_after = n_stages ? stage_after[0] : 0;
+  d.keep_k = n_stages ? stage_keep[0] : 0;
+  return vit_workspace_bytes(&d);
+}
+
+ns_status vit_forward_stages(const ns_vit_desc *desc, int32_t n_stages, const int32_t *stage_after,
+                             const int32_t *stage_keep, const ns_vit_block_weights *weights, const void *x_in,
+                             void *x_out, int32_t *kept_idx, void *workspace, size_t workspace_bytes, void *stream) {
+  const ns_status st = check_stages(desc, n_stages, stage_after, stage_keep);
+  if (st != NS_OK) return st;
+  ns_vit_desc d = *desc;
+  d.prune_after = n_stages ? stage_after[0] : 0;
+  d.keep_k = n_stages ? stage_keep[0] : 0;
+  return stack_run(d, n_stages, stage_after, stage_keep, weights, x_in, x_out, kept_idx, 0, nullptr, nullptr, workspace,
+                   workspace_bytes, stream);
 }
 
 }  // extern "C"

@@ -95,6 +95,16 @@ int main() {
     EXPECT(vit_workspace_bytes(&v) == 0);
     v.keep_k = 100;
     EXPECT(vit_forward(&v, nullptr, fake, fake2, nullptr, ws, (size_t)1 << 40, nullptr) == NS_ERR_INVALID_ARG);
+    {
+      const int32_t after_ok[3] = {2, 5, 24}, keep_ok[3] = {9000, 9000, 10};
+      const int32_t after_bad[2] = {5, 5}, keep_bad[2] = {10, 20};
+      EXPECT(vit_stages_workspace_bytes(&v, 3, after_ok, keep_ok) > 0);
+      EXPECT(vit_stages_workspace_bytes(&v, 0, nullptr, nullptr) > 0);
+      EXPECT(vit_stages_workspace_bytes(&v, 2, after_bad, keep_ok) == 0);
+      EXPECT(vit_stages_workspace_bytes(&v, 2, after_ok, keep_bad) == 0);
+      EXPECT(vit_forward_stages(&v, 2, after_bad, keep_ok, nullptr, fake, fake2, nullptr, ws, (size_t)1 << 40, nullptr) == NS_ERR_INVALID_ARG);
+      EXPECT(vit_forward_stages(&v, 3, after_ok, keep_ok, nullptr, fake, fake2, nullptr, ws, (size_t)1 << 40, nullptr) == NS_ERR_INVALID_ARG);
+    }
     v.block.dim = 1000;      // heads * head_dim != dim
     EXPECT(vit_block_workspace_bytes(&v.block) == 0);
     EXPECT(vit_embed_workspace_bytes(1, 3, 128, 128, 16, 1024) > 0);

@@ -112,6 +112,71 @@ def test_stack_with_pruning_stage(nb, layers, after, keep_pct, g, block):
     assert_attn_close(to_np(out), h, "bf16", "stack output")
 
 
+@pytest.mark.parametrize("layers,after,keep_pct,g,block", [(5, (1, 3), (70, 40), 16, 8), (6, (2, 3, 5), (80, 50, 20), 20, 8),
+                                                           (4, (2, 4), (60, 60), 32, 16), (3, (1, 2), (50, 3), 16, 8)])
+def test_stack_with_several_pruning_stages(nb, layers, after, keep_pct, g, block):
+    """Several pruning stages (the paper's rule applied repeatedly): each stage ranks the patches still
+    present by the scores of the block before it.  The oracle follows the GPU's kept set after every
+    stage (obtained from the same stack cut off after that stage), checks it against its own scores
+    outside the tie band, and the final outputs are compared element by element."""
+    B, heads, dim, mlp = 2, 8, 512, 640
+    N, T = g * g, 1 + g * g
+    keeps = [(N * pc + 99) // 100 for pc in keep_pct]
+    rng = np.random.default_rng(31)
+    x = synth.round_to_bf16(rng.standard_normal((B, T, dim)).astype(np.float32))
+    ws = [synth.make_block_weights(dim, mlp, seed=60 + i, dtype="bf16", ln_random=True) for i in range(layers)]
+    dws = [dev_weights(w) for w in ws]
+    dx = torch.from_numpy(x).to(torch.bfloat16).cuda()
+    out, kept = nb.vit_forward_stages(dx, dws, g, g, block, heads, list(after), keeps)
+    torch.cuda.synchronize()
+    assert out.shape == (B, 1 + keeps[-1], dim)
+
+    raster = synth.raster_coords(g, g)
+    h = x.astype(np.float64)
+    present = np.tile(np.arange(N, dtype=np.int64), (B, 1))          # original indices of the patches in the sequence
+    coords = None
+    stage = 0
+    for i in range(layers):
+        scoring = stage < len(after) and i + 1 == after[stage]
+        if scoring:
+            h, scores = ov.vit_block(h, ws[i], g, g, block, heads, coords=coords, want_scores=True, storage="bf16")
+            # the GPU's survivors after this stage: the same stack cut off here
+            _, kept_j = nb.vit_forward_stages(dx, dws[:i + 1], g, g, block, heads, list(after[:stage + 1]), keeps[:stage + 1])
+            torch.cuda.synchronize()
+            kept_orig = kept_j.cpu().numpy().astype(np.int64)
+            assert np.all(np.diff(kept_orig, axis=1) > 0)
+            # as positions in the current sequence
+            local = np.stack([np.searchsorted(present[b], kept_orig[b]) for b in range(B)])
+            assert all(np.array_equal(present[b][local[b]], kept_orig[b]) for b in range(B)), "survivors must come from the sequence"
+            ref_local = oracle.topk(scores.astype(np.float32), keeps[stage])
+            assert_kept_sets_match(local.astype(np.int32), ref_local, scores, keeps[stage])
+            idx = np.concatenate([np.zeros((B, 1), dtype=np.int64), 1 + local], axis=1)
+            h = np.take_along_axis(h, idx[:, :, None], axis=1)
+            present = kept_orig
+            coords = np.stack([raster[present[b]] for b in range(B)])
+            stage += 1
+        else:
+            h = ov.vit_block(h, ws[i], g, g, block, heads, coords=coords, storage="bf16")
+    assert np.array_equal(kept.cpu().numpy(), present)
+    assert_attn_close(to_np(out), h, "bf16", "stack output after %d stages" % len(after))
+    # one stage through this entry point is vit_forward
+    out1, kept1 = nb.vit_forward_stages(dx, dws, g, g, block, heads, [after[0]], [keeps[0]])
+    out2, kept2 = nb.vit_forward(dx, dws, g, g, block, heads, prune_after=after[0], keep_k=keeps[0])
+    torch.cuda.synchronize()
+    assert torch.equal(out1, out2) and torch.equal(kept1, kept2)
+
+
+def test_stage_lists_are_validated(nb):
+    x = torch.zeros((1, 65, 512), dtype=torch.bfloat16, device="cuda")
+    ws = [dev_weights(synth.make_block_weights(512, 640, seed=i)) for i in range(3)]
+    for after, keep in (([2, 2], [30, 20]), ([2, 1], [30, 20]), ([1, 2], [20, 30]), ([1], [65]), ([4], [10]), ([0], [10]), ([1], [0])):
+        with pytest.raises(nb.NsError) as e:
+            nb.vit_forward_stages(x, ws, 8, 8, 8, 8, after, keep)
+        assert e.value.code == nb.NS_ERR_INVALID_ARG
+    out, kept = nb.vit_forward_stages(x, ws, 8, 8, 8, 8, [], [])
+    assert out.shape == x.shape and kept is None
+
+
 def test_stack_pruning_of_a_long_sequence(nb):
     """More than 32768 patches: the stack's selection runs with several workgroups per image and
     takes its scratch from the stack's workspace.  The stack must keep exactly what topk_filter
