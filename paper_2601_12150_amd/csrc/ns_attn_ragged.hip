@@ -14,7 +14,7 @@
 // (one row address per lane), V gathered global -> LDS with direct 16-byte transfers and read
 // transposed with ds_read_b64_tr_b16.  The softmax keeps a running maximum per query (this
 // kernel is not the tuned one: no fixed exponent reference, no sub-block pipeline); the next
-// tile's K and V are requested before the current tile is processed.
+// tile's K and V are requested as soon as the current tile's logits are computed.
 #include "ns_common.h"
 
 namespace ns {
@@ -160,18 +160,32 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_ragged_kernel(RaggedParams p
     for (int i = 1; i < 9; i++) kfill = nb == i ? fill9[i] : kfill;
     kbase = 0;
   };
-  // requests of the current key tile: K fragments into registers, V into an LDS buffer
-  auto request = [&](bf16x8 (&kf)[2][4], int buf, int &cnt) {
+  // The tile after the one described last: its fill and, per lane, the token of its slot (the load
+  // of the token travels together with the requests issued just before it and is consumed a
+  // tile later).  False when the walk is over.
+  auto next_desc = [&](int &cnt, int &tok) {
+    if (!have_next()) return false;
+    advance();
     cnt = min(kfill - kbase, 64);
-    const int tok = slot_token(kblk, kbase, cnt);
+    tok = slot_token(kblk, kbase, cnt);
+    return true;
+  };
+  // requests of a key tile whose slot tokens are known: V into an LDS buffer (first: the transfers
+  // are older than the fragment loads, so when the fragments are there, V is too), K fragments
+  // into registers
+  auto request = [&](bf16x8 (&kf)[2][4], int buf, int tok) {
+    // (the lane numbers of the exchanges below are computed here, from an untraceable copy of the
+    // lane number: kept in ten registers across the loop, two of them were spilled, and their
+    // reload between the transfers waited for every transfer just issued)
+    const int ln = opaque(lane);
 #pragma unroll
     for (int it = 0; it < 8; it++) {
-      const uint32_t vt = (uint32_t)__shfl(tok, it * 8 + (lane >> 3));
+      const uint32_t vt = (uint32_t)__shfl(tok, it * 8 + (ln >> 3));
       dma16(vb, vt * rowB + vchunk, lds_base + buf * 8192 + it * 1024);
     }
 #pragma unroll
     for (int mt = 0; mt < 2; mt++) {
-      const uint32_t kt = (uint32_t)__shfl(tok, l32 + 32 * mt);
+      const uint32_t kt = (uint32_t)__shfl(tok, (ln & 31) + 32 * mt);
       const char *row = kb + (size_t)kt * rowB + 64 * hh;
 #pragma unroll
       for (int s = 0; s < 4; s++) kf[mt][s] = *reinterpret_cast<const bf16x8 *>(row + 16 * s);
@@ -196,20 +210,28 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_ragged_kernel(RaggedParams p
         o[dt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[sp], o[dt][nt], 0, 0, 0);
       }
   };
-  // one key tile: kf / buf / cnt describe it; its requests are complete
-  auto process = [&](const bf16x8 (&kf)[2][4], int buf, int cnt) {
+  // the logits of a tile (its K fragments are there): [nt][mt], missing keys masked
+  auto logits = [&](const bf16x8 (&kf)[2][4], int cnt, f32x16 (&sv)[2][2]) {
 #pragma unroll
     for (int nt = 0; nt < 2; nt++) {
-      f32x16 s0 = stage_a(kf, 0, nt), s1 = stage_a(kf, 1, nt);
+      sv[nt][0] = stage_a(kf, 0, nt);
+      sv[nt][1] = stage_a(kf, 1, nt);
       if (cnt < 64) {
         // register e of a 32x32 block is key 8*(e/4) + 4*hh + e%4 (+32 for the second block)
 #pragma unroll
         for (int e = 0; e < 16; e++) {
           const int key = 8 * (e >> 2) + 4 * hh + (e & 3);
-          s0[e] = key < cnt ? s0[e] : -INFINITY;
-          s1[e] = key + 32 < cnt ? s1[e] : -INFINITY;
+          sv[nt][0][e] = key < cnt ? sv[nt][0][e] : -INFINITY;
+          sv[nt][1][e] = key + 32 < cnt ? sv[nt][1][e] : -INFINITY;
         }
       }
+    }
+  };
+  // weights and output product of a tile from its logits; V is in LDS buffer buf
+  auto weigh = [&](const f32x16 (&sv)[2][2], int buf) {
+#pragma unroll
+    for (int nt = 0; nt < 2; nt++) {
+      const f32x16 &s0 = sv[nt][0], &s1 = sv[nt][1];
       float mx0 = fmaxf(s0[0], s0[1]), mx1 = fmaxf(s1[0], s1[1]);
 #pragma unroll
       for (int e = 2; e < 16; e += 2) {
@@ -243,27 +265,41 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_ragged_kernel(RaggedParams p
     }
   };
 
-  bf16x8 kfa[2][4], kfb[2][4];
-  int cnta = 0, cntb = 0;
-  advance();
-  request(kfa, 0, cnta);
+  // The walk.  A tile's logits come first: after them its K fragments are dead, and the next
+  // tile's requests go out into the same registers (and the other V buffer) while the weights and
+  // the output product of this one are computed.  Nothing with a register result is in flight
+  // while a tile's fragments are waited for except the next token load, so no wait drains requests
+  // that were just issued.
+  bf16x8 kf[2][4];
+  int cnt_cur = 0, tok_cur = 0, cnt_nxt = 0, tok_nxt = 0;
+  next_desc(cnt_cur, tok_cur);                 // (the query block's own run is not empty: there is a first tile)
+  request(kf, 0, tok_cur);
+  bool has_nxt = next_desc(cnt_nxt, tok_nxt);
+  int buf = 0;
   while (true) {
-    // tile in (kfa, buffer 0); request the next one into (kfb, buffer 1) first
-    const bool more1 = have_next();
-    if (more1) { advance(); request(kfb, 1, cntb); }
-    // this tile's V transfers are older than everything requested just now: at most the 16 new
-    // requests may still be in flight
-    if (more1) asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    process(kfa, 0, cnta);
-    // the tile's LDS reads have returned before the next transfer into its buffer is requested
+    f32x16 sv[2][2];
+    logits(kf, cnt_cur, sv);
+    // An ordering point that depends on the last logit tile, i.e. on the fragment load issued last:
+    // every request of this tile is older than that load, so once it has returned the tile's V is
+    // in LDS.  No LDS read below may be issued before this point, no transfer above it after it.
+    {
+      float t = sv[1][1][15];
+      asm volatile("" : "+v"(t) :: "memory");
+      sv[1][1][15] = t;
+    }
+    bool has_n2 = false;
+    int cnt_n2 = 0, tok_n2 = 0;
+    if (has_nxt) {
+      request(kf, buf ^ 1, tok_nxt);
+      has_n2 = next_desc(cnt_n2, tok_n2);
+    }
+    weigh(sv, buf);
+    // the tile's LDS reads have returned before a transfer into its buffer is requested
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    if (!more1) break;
-    const bool more2 = have_next();
-    if (more2) { advance(); request(kfa, 0, cnta); }
-    if (more2) asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    process(kfb, 1, cntb);
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    if (!more2) break;
+    if (!has_nxt) break;
+    cnt_cur = cnt_nxt;
+    cnt_nxt = cnt_n2; tok_nxt = tok_n2; has_nxt = has_n2;
+    buf ^= 1;
   }
 
   // ---- normalise and store the rows that exist: lane (query, hh) owns channels 32*dt + 8*ig + 4*hh + 0..3
