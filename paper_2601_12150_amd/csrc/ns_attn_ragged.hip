@@ -42,7 +42,11 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_ragged_kernel(RaggedParams p
   const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int l32 = lane & 31, hh = lane >> 5;
   const int nblocks = p.nbh * p.nbw;
-  const int qtile = blockIdx.x * 4 + wave, h = blockIdx.y, b = blockIdx.z;
+  // workgroups are dealt round-robin to the 8 XCDs: give each XCD a contiguous range of blocks, so
+  // that the K and V rows which neighbouring blocks share are fetched into one L2 only
+  int bx = blockIdx.x;
+  if (gridDim.x % 8 == 0) bx = (bx & 7) * (int)(gridDim.x / 8) + (bx >> 3);
+  const int qtile = bx * 4 + wave, h = blockIdx.y, b = blockIdx.z;
   const int blk = qtile / p.tpb, qbase = (qtile - blk * p.tpb) * 64;
   if (blk >= nblocks) return;                 // no workgroup barriers below
   const int32_t *cnts = p.counts + (size_t)b * nblocks;
