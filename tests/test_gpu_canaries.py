@@ -161,3 +161,14 @@ def test_block_and_stack_writes_stay_inside_their_buffers(nb):
                                out=bands["out"].view(torch.bfloat16, (B, 1 + keep, dim)), workspace=bands["workspace"].bytes)
     check(bands, "vit_forward")
     assert bool(torch.isfinite(out.float()).all())
+    # the same stack with two pruning stages
+    after, keeps = [1, 2], [keep, keep // 3]
+    aft = (ctypes.c_int32 * 2)(*after)
+    kp = (ctypes.c_int32 * 2)(*keeps)
+    nbytes = nb.lib.vit_stages_workspace_bytes(ctypes.byref(v), 2, aft, kp)
+    bands = {"out": Guarded(B * (1 + keeps[-1]) * dim * 2), "workspace": Guarded(nbytes)}
+    out, kept = nb.vit_forward_stages(x, ws, g, g, blk, heads, after, keeps,
+                                      out=bands["out"].view(torch.bfloat16, (B, 1 + keeps[-1], dim)),
+                                      workspace=bands["workspace"].bytes)
+    check(bands, "vit_forward_stages")
+    assert bool(torch.isfinite(out.float()).all()) and int(kept.max()) < N
