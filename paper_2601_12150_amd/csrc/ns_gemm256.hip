@@ -92,10 +92,7 @@ __device__ __forceinline__ void gemm256_emit(const Gemm256Params &p, unsigned ch
     const f32x4 v1 = *reinterpret_cast<const f32x4 *>(ebuf + t * kEpiRow + nl * 4 + 16);
     float o[8] = {v0[0] + b0[0], v0[1] + b0[1], v0[2] + b0[2], v0[3] + b0[3],
                   v1[0] + b1[0], v1[1] + b1[1], v1[2] + b1[2], v1[3] + b1[3]};
-    if (GELU) {
-#pragma unroll
-      for (int e = 0; e < 8; e++) o[e] = gelu_erf(o[e]);
-    }
+    if (GELU) gelu_erf8(o);
     if (RES) {
       o[0] += bf16_lo(r4.x); o[1] += bf16_hi(r4.x); o[2] += bf16_lo(r4.y); o[3] += bf16_hi(r4.y);
       o[4] += bf16_lo(r4.z); o[5] += bf16_hi(r4.z); o[6] += bf16_lo(r4.w); o[7] += bf16_hi(r4.w);
@@ -221,11 +218,14 @@ __device__ __forceinline__ void gemm256_wave(const Gemm256Params &p, unsigned ch
   // wave, slice kt+1 is in flight into the other stage, fragment buffer 0 holds (slice kt, k-step
   // 0).  After the third k-step every wave has issued its last reads of slice kt; with the barrier
   // there slice kt+1 is complete for all, and slice kt+2 can be requested into slice kt's stage.
-  // Requests past the last slice repeat it (into a stage nobody reads any more).
   const int nk = p.K / 64;
   issue(0, 0);
-  issue(min(1, nk - 1), 1);
-  wait_vm<PER_SLICE>();
+  if (nk > 1) {
+    issue(1, 1);
+    wait_vm<PER_SLICE>();
+  } else {
+    wait_vm<0>();
+  }
   __syncthreads();
   read_frags(0, 0, 0);
   for (int kt = 0; kt < nk; kt++) {
@@ -242,12 +242,11 @@ __device__ __forceinline__ void gemm256_wave(const Gemm256Params &p, unsigned ch
     wait_vm<0>();                                     // slice kt+1 (this wave's share)
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the fragments of slice kt are in registers
     __syncthreads();
-    issue(min(kt + 2, nk - 1), cur);
+    if (kt + 2 < nk) issue(kt + 2, cur);
     read_frags(0, cur ^ 1, 0);
     mma(1);
     interleave();
   }
-  wait_vm<0>();               // the repeated requests of the last iterations
   __syncthreads();             // every wave is done with the stages: they become the epilogue's staging area
 
   // ---- epilogue, one 32-token slab at a time
