@@ -276,6 +276,28 @@ def test_stack_feature_maps(nb):
     assert e.value.code == nb.NS_ERR_INVALID_ARG
 
 
+@pytest.mark.parametrize("n", [256, 128])      # the 256 x 256 kernel and the 128 x 128 kernel
+def test_gelu_epilogue_value_by_value(nb, n):
+    """The GELU of the linear map's epilogue on chosen pre-activations: with the identity as weight and no bias
+    the pre-activation is the input itself (exact in fp32), so every output is the bf16 rounding of gelu(x) — checked
+    against the float64 erf form, relative to the value (the tail of negative x is where a form that subtracts loses
+    its digits) plus the approximation's absolute error (1.5e-7 in erfc, times |x| / 2)."""
+    M = 256
+    vals = np.concatenate([np.linspace(-9.0, 9.0, M * n - 8), [0.0, -0.0, 1e-6, -1e-6, 40.0, -40.0, 1e4, -1e4]])
+    x = synth.round_to_bf16(vals.astype(np.float32)).reshape(M, n)
+    w = np.eye(n, dtype=np.float32)
+    dev = lambda a: torch.from_numpy(a).to(torch.bfloat16).cuda()
+    y = nb.linear_forward(dev(x), dev(w), torch.zeros(n, device="cuda"), None, gelu=True)
+    torch.cuda.synchronize()
+    got = to_np(y).astype(np.float64)
+    ref = ov.gelu(x.astype(np.float64))
+    err = np.abs(got - ref)
+    bound = 2.0 ** -8 * np.abs(ref) + 1e-7 * np.abs(x) + 1e-30
+    worst = int(np.argmax(err / bound))
+    assert np.all(err <= bound), (x.flat[worst], got.flat[worst], ref.flat[worst])
+    assert np.all(got[x >= 0] >= 0) and np.all(got[x < 0] <= 0)
+
+
 @pytest.mark.parametrize("M,N,K,gelu,res", [
     (1025, 1024, 1024, False, True),    # one extended row tile chain: 4 tiles, the last with a ninth slab
     (577, 512, 256, True, False),       # remainder 65: a partial tile of its own (3 slabs)
