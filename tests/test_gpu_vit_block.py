@@ -25,7 +25,7 @@ def dev_weights(w):
             for k, v in w.items()}
 
 
-def block_case(nb, B, g, block, heads, dim, mlp, seed, coords_keep=None):
+def block_case(nb, B, g, block, heads, dim, mlp, seed, coords_keep=None, edit=None):
     print("block case B=%d grid=%d block=%d heads=%d dim=%d mlp=%d pruned=%s" % (
         B, g, block, heads, dim, mlp, coords_keep is not None), flush=True)
     rng = np.random.default_rng(seed)
@@ -35,7 +35,10 @@ def block_case(nb, B, g, block, heads, dim, mlp, seed, coords_keep=None):
         kept = np.sort(rng.choice(g * g, size=coords_keep, replace=False))
         T = 1 + len(kept)
         coords = np.ascontiguousarray(np.broadcast_to(synth.raster_coords(g, g)[kept], (B, len(kept))))
-    x = synth.round_to_bf16(rng.standard_normal((B, T, dim)).astype(np.float32))
+    x = rng.standard_normal((B, T, dim)).astype(np.float32)
+    if edit is not None:
+        edit(x, rng)
+    x = synth.round_to_bf16(x)
     w = synth.make_block_weights(dim, mlp, seed=seed, dtype="bf16", ln_random=True)
     # the oracle in its "bf16 storage" precision model: every tensor the block keeps in memory between
     # two steps is rounded to bf16 there as well, all arithmetic in float64
@@ -64,6 +67,20 @@ def test_block_matches_oracle(nb, B, g, block, heads, dim, mlp):
 
 def test_block_on_pruned_sequence(nb):
     block_case(nb, 1, 24, 8, 8, 512, 1024, seed=12, coords_keep=350)
+
+
+def test_block_with_degenerate_rows(nb):
+    """Rows that strain the normalisation: constant (variance 0), all zero, a mean of 100 standard deviations
+    (a one-pass variance would cancel), single outlier channels, tiny amplitudes — the global token's row among them."""
+    def edit(x, rng):
+        x[:, 0] = 0.75                       # the global token: constant
+        x[:, 5] = 0.0
+        x[:, 9] += 100.0
+        x[:, 17, 3] = 250.0
+        x[:, 18, ::64] = -60.0
+        x[:, 40:48] *= 1e-3
+        x[:, 100:108] *= 30.0
+    block_case(nb, 2, 16, 8, 8, 512, 1024, seed=13, edit=edit)
 
 
 def test_block_validation(nb):
